@@ -1,0 +1,147 @@
+"""fp64 CPU oracle for the GLM full-batch iteration (TEST INFRASTRUCTURE).
+
+Thin ctypes wrapper over ``glm_oracle.c``.  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; the GPU library never
+does.  Nothing here depends on the GPU package, and the GPU package does not
+depend on anything here.
+
+The paper prints no formula or value for a training iteration (it only states,
+Sec. 2 "Normalizing Quality Metrics", that the loss is evaluated every
+iteration, and lists the algorithms in Sec. 3 "Setup"), so against paper-printed
+values every function here is "parity unpinned"; the CPU tests pin them with
+closed forms, finite differences, the normal equations and convexity
+invariants instead.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Sequence
+
+import numpy as np
+
+LOGISTIC, HINGE, SQUARED = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "glm_oracle.c")
+_LIB_PATH = os.path.join(_HERE, "libglm_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile glm_oracle.c with gcc (OpenMP on) into libglm_oracle.so beside it."""
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
+        tmp = _LIB_PATH + f".tmp{os.getpid()}"
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB_PATH)
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        fp = ctypes.POINTER(ctypes.c_float)
+        dp = ctypes.POINTER(ctypes.c_double)
+        lib.oracle_loss_grad.restype = ctypes.c_int
+        lib.oracle_loss_grad.argtypes = [ctypes.c_int, fp, fp, ctypes.c_int64, ctypes.c_int32,
+                                         dp, ctypes.c_double, dp, dp]
+        lib.oracle_loss_grad_chunked.restype = ctypes.c_int
+        lib.oracle_loss_grad_chunked.argtypes = [ctypes.c_int, fp, fp, ctypes.c_int64, ctypes.c_int32,
+                                                 dp, ctypes.c_double, ctypes.c_int32, dp, dp]
+        lib.oracle_run.restype = ctypes.c_int
+        lib.oracle_run.argtypes = [ctypes.c_int, fp, fp, ctypes.c_int64, ctypes.c_int32,
+                                   dp, ctypes.c_double, ctypes.c_double, ctypes.c_int32,
+                                   ctypes.c_int32, dp, dp, dp]
+        lib.oracle_max_threads.restype = ctypes.c_int
+        lib.oracle_max_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def _f32(a, shape=None):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float32:
+        raise TypeError("oracle inputs X and y must be float32 (the bits the GPU reads)")
+    if shape is not None and a.shape != shape:
+        raise ValueError(f"expected shape {shape}, got {a.shape}")
+    return a
+
+
+def _fptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _dptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def loss_grad(loss: int, X, y, w, lam: float, chunks: int = 0):
+    """(L, g) at w: L = mean_i l_i + lam/2 |w|^2, g = X^T r / N + lam w, all in fp64.
+
+    ``chunks`` > 1 evaluates contiguous row chunks independently (OpenMP) and
+    adds them in chunk order; 0/1 is the strictly sequential evaluation.
+    """
+    X = _f32(X)
+    N, D = X.shape
+    y = _f32(y, (N,))
+    w = np.ascontiguousarray(np.asarray(w, dtype=np.float64))
+    if w.shape != (D,):
+        raise ValueError("w must have shape (D,)")
+    g = np.empty(D, dtype=np.float64)
+    L = ctypes.c_double(0.0)
+    lib = _load()
+    if chunks and chunks > 1:
+        rc = lib.oracle_loss_grad_chunked(int(loss), _fptr(X), _fptr(y), N, D, _dptr(w),
+                                          float(lam), int(chunks), ctypes.byref(L), _dptr(g))
+    else:
+        rc = lib.oracle_loss_grad(int(loss), _fptr(X), _fptr(y), N, D, _dptr(w), float(lam),
+                                  ctypes.byref(L), _dptr(g))
+    if rc != 0:
+        raise ValueError("oracle_loss_grad rejected its arguments")
+    return float(L.value), g
+
+
+def run(loss: int, X, y, w0, lam: float, eta: float, K: int, chunks: int = 0):
+    """K constant-step GD iterations from w0.
+
+    Returns (loss_hist[K], gnorm_hist[K], w_K, g_last); entry k of the histories
+    belongs to the iterate entering iteration k.
+    """
+    X = _f32(X)
+    N, D = X.shape
+    y = _f32(y, (N,))
+    w = np.array(w0, dtype=np.float64, copy=True)
+    if w.shape != (D,):
+        raise ValueError("w0 must have shape (D,)")
+    lh = np.empty(K, dtype=np.float64)
+    gh = np.empty(K, dtype=np.float64)
+    gl = np.zeros(D, dtype=np.float64)
+    rc = _load().oracle_run(int(loss), _fptr(X), _fptr(y), N, D, _dptr(w), float(lam), float(eta),
+                            int(K), int(chunks), _dptr(lh), _dptr(gh), _dptr(gl))
+    if rc != 0:
+        raise ValueError("oracle_run rejected its arguments")
+    return lh, gh, w, gl
+
+
+def run_sweep(loss: int, X, y, W0, lams: Sequence[float], etas: Sequence[float], K: int,
+              chunks: int = 0):
+    """M independent models sharing X: model m is ``run`` with (lams[m], etas[m]).
+
+    W0 is [M, D].  Returns (loss_hist[K, M], gnorm_hist[K, M], W_K[M, D], G_last[M, D]).
+    """
+    W0 = np.asarray(W0, dtype=np.float64)
+    M, D = W0.shape
+    lh = np.empty((K, M)); gh = np.empty((K, M))
+    WK = np.empty((M, D)); GL = np.empty((M, D))
+    for m in range(M):
+        a, b, c, d = run(loss, X, y, W0[m], float(lams[m]), float(etas[m]), K, chunks)
+        lh[:, m], gh[:, m], WK[m], GL[m] = a, b, c, d
+    return lh, gh, WK, GL
