@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the full-batch GLM iteration on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {0,1,2,3,4}] [--check]
+
+One "step" is one gradient-descent iteration: a full pass of the whole hot path
+(margins, loss and residual, gradient, loss value, update) over the whole synthetic
+data set, which is resident in HBM before the timed region starts.  The default
+workload is the 4,000,000 x 1024 logistic-regression configuration (16.4 GB of X).
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4])
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only; the line says so)")
+    ap.add_argument("--check", action="store_true", help="also compare against the oracle on the full data")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline_single(p, target_rows):
+    """The oracle as it stands, timed on the host cores on the first `target_rows` rows of the
+    same workload; the rate is scaled to whole-data iterations per second."""
+    import numpy as np
+    import oracle
+    n = min(p.N, target_rows)
+    Xs = p.X[:n].cpu().numpy()
+    ys = p.y[:n].cpu().numpy()
+    threads = oracle.max_threads()
+    w = np.zeros(p.D)
+    oracle.loss_grad(p.loss, Xs[: max(1, n // 16)], ys[: max(1, n // 16)], w, p.lam, chunks=threads)
+    reps, t_tot = 0, 0.0
+    while reps < 2 or (t_tot < 10.0 and reps < 50):
+        t0 = time.perf_counter()
+        L, g = oracle.loss_grad(p.loss, Xs, ys, w, p.lam, chunks=threads)
+        t_tot += time.perf_counter() - t0
+        w = w - p.eta * g
+        reps += 1
+    per_iter_sample = t_tot / reps
+    per_iter_full = per_iter_sample * (p.N / n)
+    return {"value": 1.0 / per_iter_full, "unit": "iter/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {n} of {p.N} rows, {reps} oracle iterations of {per_iter_sample:.3f} s, "
+                      f"rate scaled by {n}/{p.N}"}
+
+
+def bench_single(args, cfg):
+    import numpy as np
+    import torch
+    from paper_1802_04819_amd import glm, synth
+
+    maker = {0: lambda: synth.config0(device="cuda"),
+             1: lambda: synth.config1(args.scale, device="cuda"),
+             2: lambda: synth.config2(args.scale, device="cuda")}[cfg]
+    p = maker()
+    K = args.steps if args.steps is not None else p.K
+    job = glm.Job(p.X, p.y, p.w0.clone(), p.loss, p.lam, p.eta, max(K, args.warmup, 1))
+    ws = glm.alloc_workspace([job])
+
+    def reset():
+        job.w.zero_()
+        job.c.hist_len = 0
+
+    if args.warmup > 0:
+        glm.glm_step(job, args.warmup, ws)
+    torch.cuda.synchronize()
+    reset()
+    torch.cuda.synchronize()
+    glm.glm_profile_begin(K)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    glm.glm_step(job, K, ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    k1_ms = glm.glm_profile_end(K)
+    hist = job.history().cpu().numpy().copy()
+    w_run1 = job.w.clone()
+
+    # rerun from the same start: the trajectory must be bit-identical
+    reset()
+    glm.glm_step(job, K, ws)
+    torch.cuda.synchronize()
+    rerun_identical = bool(np.array_equal(hist, job.history().cpu().numpy()) and torch.equal(w_run1, job.w))
+
+    sec = t1 - t0
+    bytes_per_launch = 4.0 * p.N * p.D + 4.0 * p.N
+    avg_ms = float(np.mean(k1_ms)) if k1_ms else float("nan")
+    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "GD iterations/sec (full-batch GLM step; achieved HBM GB/s in roofline)",
+        "value": K / sec, "unit": "iter/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": 1e3 * sec / K, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": p.name, "config_index": cfg, "N": p.N, "D": p.D,
+                   "loss": synth.LOSS_NAMES[p.loss], "lambda": p.lam, "step": p.eta,
+                   "bytes_per_iteration": bytes_per_launch, "scale": args.scale},
+        "roofline": {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "avg_launch_ms": avg_ms, "launches": len(k1_ms),
+                     "whole_step_GBps": bytes_per_launch * K / sec / 1e9},
+        "rerun_bit_identical": rerun_identical,
+        "loss_first": float(hist[0]), "loss_last": float(hist[-1]),
+    }
+    if args.check:
+        import oracle
+        Xn, yn = p.X.cpu().numpy(), p.y.cpu().numpy()
+        job.w.zero_(); job.c.hist_len = 0
+        glm.glm_step(job, 1, ws)
+        torch.cuda.synchronize()
+        L, g = oracle.loss_grad(p.loss, Xn, yn, np.zeros(p.D), p.lam, chunks=oracle.max_threads())
+        gg = job.grad.cpu().numpy().astype(np.float64)
+        out["check"] = {"rel_err_loss_k0": abs(job.loss_hist[0].item() - L) / abs(L),
+                        "rel_err_gnorm_k0": abs(np.linalg.norm(gg) - np.linalg.norm(g)) / np.linalg.norm(g)}
+    if not args.no_cpu_baseline:
+        rows = {0: p.N, 1: 1_000_000, 2: 400_000}[cfg]
+        out["cpu_baseline"] = cpu_baseline_single(p, rows)
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    if args.config in (0, 1, 2):
+        out = bench_single(args, args.config)
+    else:
+        print(f"bench.py: config {args.config} is not wired into the benchmark yet", file=sys.stderr)
+        sys.exit(4)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,148 @@
+/*
+ * slaqglm -- full-batch training iteration of generalized-linear-model jobs on
+ * one AMD Instinct MI355X (gfx950), as a plain C ABI.
+ *
+ * Background.  A quality-driven cluster scheduler for ML training (SLAQ,
+ * arXiv:1802.04819) runs a set J of iterative training jobs; every scheduling
+ * epoch it hands each job j an allocation a_j (Sec. 2, "Scheduling Based on
+ * Quality Improvements") and consumes the loss value each job produces in
+ * every iteration (Sec. 2, "Normalizing Quality Metrics").  The jobs include
+ * logistic regression, SVM and linear regression trained by gradient descent
+ * (Sec. 2, class I; Sec. 3, "Setup").  This library is the execution layer
+ * under such a scheduler for those three models: it runs iterations and
+ * appends one loss value per iteration to each job's loss history.
+ *
+ * One iteration k of a job with data X [N, D], labels y [N], weights w_k [D]:
+ *     z_i   = sum_j X[i][j] w_k[j]
+ *     l_i,r_i = per-sample loss and residual dl/dz (see glm_loss_t)
+ *     L_k   = (1/N) sum_i l_i + (lambda/2) |w_k|^2          -> loss_hist[hist_len + k]
+ *     g_k   = (1/N) X^T r + lambda w_k                       -> grad
+ *     w_k+1 = w_k - step * g_k                               -> w
+ * X is streamed from device memory exactly once per iteration.
+ *
+ * Conventions for every entry point
+ *   - Returns a glm_status_t; never throws, aborts or prints.
+ *   - All arguments are validated before anything is enqueued: a call that
+ *     returns an error has had no effect on device memory or on the structs.
+ *   - Pointers marked DEVICE are device addresses owned by the caller; the
+ *     library does not allocate, free or keep them.  Pointers marked HOST are
+ *     ordinary host memory, read during the call only.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and the call returns without waiting for it.
+ *     Results are valid once the stream has been synchronised.  Calls that
+ *     share a workspace must be ordered on one stream.
+ *   - Results are deterministic: the same library, device and arguments give
+ *     bit-identical loss_hist, grad and w on every run (no floating-point
+ *     atomics; every reduction has a fixed order that depends only on N and D
+ *     of the job, never on what else is packed into the launch).
+ */
+#ifndef SLAQGLM_H
+#define SLAQGLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Per-sample loss l(z, y) and residual r = dl/dz for margin z and label y.
+ *   GLM_LOGISTIC  y in {0,1}    l = log(1 + e^z) - y z       r = 1/(1+e^-z) - y
+ *   GLM_HINGE     y in {-1,+1}  l = max(0, 1 - y z)          r = -y if 1 - y z > 0, else 0
+ *   GLM_SQUARED   y real        l = (z - y)^2 / 2            r = z - y
+ * (logistic regression, linear SVM and linear regression of Sec. 3 "Setup"). */
+typedef enum { GLM_LOGISTIC = 0, GLM_HINGE = 1, GLM_SQUARED = 2 } glm_loss_t;
+
+typedef enum {
+    GLM_OK       =  0,
+    GLM_EINVAL   = -1,  /* null/misaligned pointer, size or hyper-parameter out of range */
+    GLM_ENOSPC   = -2,  /* loss history or workspace too small for the request */
+    GLM_EHIP     = -3,  /* the HIP runtime reported an error (launch, copy, no device) */
+    GLM_ENOTIMPL = -4
+} glm_status_t;
+
+/* One training job (Sec. 3 "Setup": an algorithm, a dataset, hyper-parameters
+ * and the current model) together with its loss history (Sec. 2: the sequence
+ * of per-iteration loss values the scheduler's predictor fits). HOST struct. */
+typedef struct {
+    const float *X;        /* DEVICE [N, D] fp32, row-major, leading dimension D, 16-byte aligned */
+    const float *y;        /* DEVICE [N] fp32 labels / targets, encoding per glm_loss_t            */
+    float       *w;        /* DEVICE [D] fp32, 16-byte aligned; in: w_k, out: w_{k+iters}          */
+    float       *grad;     /* DEVICE [D] fp32; out: gradient at the iterate that entered the last
+                              iteration run (untouched if no iteration ran)                        */
+    float       *loss_hist;/* DEVICE [hist_cap] fp32; the call writes entries
+                              hist_len .. hist_len+iters-1; entry k is L at the iterate ENTERING
+                              iteration k, so entry 0 is the loss of the initial model            */
+    int64_t      N;        /* rows, >= 1                                                           */
+    int32_t      D;        /* columns, multiple of 4, 4 <= D <= 4096                               */
+    int32_t      loss;     /* glm_loss_t                                                           */
+    float        lambda;   /* L2 coefficient, finite, >= 0                                         */
+    float        step;     /* gradient-descent step, finite, >= 0; 0 evaluates loss and gradient
+                              and leaves w unchanged                                               */
+    int64_t      hist_len; /* entries already in loss_hist (= iterations done so far); advanced by
+                              the number of iterations enqueued when a call succeeds               */
+    int64_t      hist_cap; /* capacity of loss_hist                                                */
+} glm_job_t;
+
+/* Bytes of DEVICE workspace that glm_step (J = 1), glm_step_batched (J jobs) or
+ * glm_sweep (M_sweep > 0: jobs[0] gives N and D, only those two fields are read)
+ * need for these shapes.  The workspace holds per-block partial sums and launch
+ * tables; it carries no state between calls and must be 256-byte aligned.
+ * Errors: GLM_EINVAL for a null pointer, J < 1, or a shape outside the limits. */
+int glm_workspace_bytes(const glm_job_t *jobs /*HOST [J]*/, int32_t J, int32_t M_sweep,
+                        size_t *out_bytes /*HOST*/);
+
+/* Run `iters` >= 0 gradient-descent iterations of one job (Sec. 2, class I).
+ * Appends `iters` values to the job's loss history and advances job->hist_len.
+ * Errors: GLM_EINVAL (bad field, iters < 0), GLM_ENOSPC (hist_len + iters >
+ * hist_cap, or ws_bytes below glm_workspace_bytes(job, 1, 0)), GLM_EHIP. */
+int glm_step(glm_job_t *job /*HOST*/, int32_t iters, void *ws /*DEVICE*/, size_t ws_bytes,
+             void *hip_stream);
+
+/* One scheduling epoch for J concurrent jobs (Sec. 2 "Scheduling Based on
+ * Quality Improvements": jobs j in J, allocation a_j): job j runs alloc[j] >= 0
+ * iterations (0 = idle this epoch).  The jobs may differ in every field.  All
+ * jobs still active in round r = 1..max_j alloc[j] are packed into one launch.
+ * The result for each job is bit-identical to glm_step(&jobs[j], alloc[j]).
+ * Jobs must not share w, grad or loss_hist; they may share X and y.
+ * Errors as glm_step, checked for every job before anything is enqueued;
+ * ws_bytes is checked against glm_workspace_bytes(jobs, J, 0). */
+int glm_step_batched(glm_job_t *jobs /*HOST [J]*/, int32_t J, const int32_t *alloc /*HOST [J]*/,
+                     void *ws /*DEVICE*/, size_t ws_bytes, void *hip_stream);
+
+/* Hyper-parameter sweep (Sec. 1, "Training ML is an exploratory process"):
+ * M models with their own lambda and step train on one shared X for `iters`
+ * iterations; model m is exactly the job (X, y, W[m], lambdas[m], steps[m]).
+ * X.W and X^T.R are computed as dense fp32 matrix products.
+ *   W         DEVICE [M, D] model-major, in/out          G  DEVICE [M, D] out, last gradients
+ *   loss_hist DEVICE [iters, M], entry [k, m] = L_m at the iterate entering iteration k
+ *   lambdas, steps  HOST [M]
+ * Limits: 1 <= M <= 64, D multiple of 32 and <= 4096 (else GLM_EINVAL). */
+int glm_sweep(const float *X /*DEVICE*/, const float *y /*DEVICE*/, int64_t N, int32_t D, int32_t M,
+              int32_t loss, float *W /*DEVICE*/, float *G /*DEVICE*/,
+              const float *lambdas /*HOST*/, const float *steps /*HOST*/, int32_t iters,
+              float *loss_hist /*DEVICE*/, void *ws /*DEVICE*/, size_t ws_bytes, void *hip_stream);
+
+/* Measurement aid: reads n floats of DEVICE memory once with the same 128-bit
+ * access pattern as the training kernels and writes one float per block to
+ * `sink` (DEVICE, at least glm_read_probe_sink_floats() floats), so a caller
+ * can time the attainable streaming-read rate of the device.  n % 4 == 0. */
+int glm_read_probe(const float *src /*DEVICE*/, size_t n, float *sink /*DEVICE*/, void *hip_stream);
+int32_t glm_read_probe_sink_floats(void);
+
+/* Per-launch timing of the row-pass kernel (the one that streams X), for
+ * roofline reporting.  After glm_profile_begin(cap) every row-pass launch is
+ * bracketed by HIP events on its own stream, up to cap launches.
+ * glm_profile_end waits for those events, writes the durations in milliseconds
+ * to ms[0..*count-1] (HOST, room for cap values) and turns recording off.
+ * Not thread-safe; meant for a benchmark's single thread. */
+int glm_profile_begin(int32_t cap);
+int glm_profile_end(float *ms /*HOST*/, int32_t *count /*HOST*/);
+
+/* Static text for a status code. */
+const char *glm_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLAQGLM_H */

@@ -1,0 +1,270 @@
+// C-ABI entry points of libslaqglm: validation, workspace layout, launch tables, launch loops.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <numeric>
+#include <vector>
+
+#include "glm_internal.h"
+
+namespace slaqglm {
+
+int class_of_D(int D) {
+    for (int k = 0; k < kNumClasses; ++k) {
+        const ClassInfo ci = class_info(k);
+        if (D <= 4 * ci.lpr * ci.c) return k;
+    }
+    return -1;
+}
+
+// Row blocks of a job: enough that every wave gets at least one loop trip, capped per class.
+// Depends on (N, D) only, so a job is reduced in the same order whatever it is packed with.
+int row_blocks(long long N, int cls) {
+    const ClassInfo ci = class_info(cls);
+    const long long rows_per_block_trip = 4LL * ci.b * (64 / ci.lpr);
+    const long long want = (N + rows_per_block_trip - 1) / rows_per_block_trip;
+    return (int)std::max<long long>(1, std::min<long long>(want, ci.pmax));
+}
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate_shape(long long N, int D) {
+    if (N < 1 || D < 4 || D > 4096 || (D & 3) != 0) return GLM_EINVAL;
+    return GLM_OK;
+}
+
+int validate_job(const glm_job_t &j) {
+    if (validate_shape(j.N, j.D) != GLM_OK) return GLM_EINVAL;
+    if (!j.X || !j.y || !j.w || !j.grad || !j.loss_hist) return GLM_EINVAL;
+    if (!aligned16(j.X) || !aligned16(j.w)) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(j.y) & 3u) || (reinterpret_cast<uintptr_t>(j.grad) & 3u) ||
+        (reinterpret_cast<uintptr_t>(j.loss_hist) & 3u))
+        return GLM_EINVAL;
+    if (j.loss < GLM_LOGISTIC || j.loss > GLM_SQUARED) return GLM_EINVAL;
+    if (!std::isfinite(j.lambda) || j.lambda < 0.0f) return GLM_EINVAL;
+    if (!std::isfinite(j.step) || j.step < 0.0f) return GLM_EINVAL;
+    if (j.hist_len < 0 || j.hist_cap < 0 || j.hist_len > j.hist_cap) return GLM_EINVAL;
+    return GLM_OK;
+}
+
+// Workspace layout for a set of jobs: [launch tables][job 0 partials][job 1 partials]...
+struct JobSlots { size_t gpart, lpart, wn2; int P, cls; };
+struct Layout {
+    size_t tab_jobs = 0, tab_blk0 = 0, tab_cblk0 = 0;   // byte offsets
+    std::vector<JobSlots> slots;
+    size_t total = 0;
+};
+
+Layout make_layout(const glm_job_t *jobs, int J) {
+    Layout L;
+    size_t off = 0;
+    L.tab_jobs = off;  off = align_up(off + sizeof(DevJob) * (size_t)J);
+    L.tab_blk0 = off;  off = align_up(off + sizeof(int) * (size_t)(J + 1));
+    L.tab_cblk0 = off; off = align_up(off + sizeof(int) * (size_t)(J + 1));
+    L.slots.resize(J);
+    for (int j = 0; j < J; ++j) {
+        JobSlots &s = L.slots[j];
+        s.cls = class_of_D(jobs[j].D);
+        s.P = row_blocks(jobs[j].N, s.cls);
+        s.gpart = off; off = align_up(off + sizeof(float) * (size_t)s.P * jobs[j].D);
+        s.lpart = off; off = align_up(off + sizeof(float) * (size_t)s.P);
+        s.wn2 = off;   off = align_up(off + sizeof(double));
+    }
+    L.total = off;
+    return L;
+}
+
+// Pinned host staging for the launch tables.  One buffer per process, grown on demand; an
+// event marks the last copy that read it so that the next call does not overwrite it early.
+struct Staging {
+    std::mutex mu;
+    void *host = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+};
+Staging g_stage;
+
+// Profiling of row-pass launches (bench only).
+struct Profile {
+    bool on = false;
+    int cap = 0;
+    std::vector<hipEvent_t> ev;   // 2 per launch
+    int used = 0;
+};
+Profile g_prof;
+
+hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, hipStream_t st) {
+    // Active jobs sorted by iteration count, descending (stable): the jobs still active in
+    // round r are then a prefix of the table, and one table serves every round.
+    std::vector<int> order;
+    order.reserve(J);
+    for (int j = 0; j < J; ++j) if (iters[j] > 0) order.push_back(j);
+    if (order.empty()) return hipSuccess;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return iters[a] > iters[b]; });
+    const int A = (int)order.size();
+    const int R = iters[order[0]];
+
+    const Layout L = make_layout(jobs, J);
+    char *base = static_cast<char *>(ws);
+    const size_t tab_bytes = L.slots.empty() ? 0 : L.slots[0].gpart;   // tables precede partials
+
+    std::lock_guard<std::mutex> lock(g_stage.mu);
+    hipError_t e;
+    if (g_stage.pending) {
+        if ((e = hipEventSynchronize(g_stage.ev)) != hipSuccess) return e;
+        g_stage.pending = false;
+    }
+    if (g_stage.cap < tab_bytes) {
+        if (g_stage.host) { (void)hipHostFree(g_stage.host); g_stage.host = nullptr; g_stage.cap = 0; }
+        const size_t want = std::max<size_t>(tab_bytes, 1 << 16);
+        if ((e = hipHostMalloc(&g_stage.host, want, hipHostMallocDefault)) != hipSuccess) return e;
+        g_stage.cap = want;
+    }
+    if (!g_stage.ev) {
+        if ((e = hipEventCreateWithFlags(&g_stage.ev, hipEventDisableTiming)) != hipSuccess) return e;
+    }
+    char *h = static_cast<char *>(g_stage.host);
+    std::memset(h, 0, tab_bytes);
+    DevJob *dj = reinterpret_cast<DevJob *>(h + L.tab_jobs);
+    int *blk0 = reinterpret_cast<int *>(h + L.tab_blk0);
+    int *cblk0 = reinterpret_cast<int *>(h + L.tab_cblk0);
+    int max_cls = 0;
+    blk0[0] = 0; cblk0[0] = 0;
+    for (int a = 0; a < A; ++a) {
+        const int j = order[a];
+        const glm_job_t &src = jobs[j];
+        const JobSlots &s = L.slots[j];
+        DevJob &d = dj[a];
+        d.X = src.X; d.y = src.y; d.w = src.w; d.grad = src.grad;
+        d.loss_out = src.loss_hist + src.hist_len;
+        d.gpart = reinterpret_cast<float *>(base + s.gpart);
+        d.lpart = reinterpret_cast<float *>(base + s.lpart);
+        d.wn2 = reinterpret_cast<double *>(base + s.wn2);
+        d.N = src.N; d.invN = 1.0 / (double)src.N; d.D = src.D; d.loss = src.loss;
+        d.lambda = src.lambda; d.step = src.step; d.P = s.P; d.cls = s.cls; d.iters = iters[j];
+        max_cls = std::max(max_cls, s.cls);
+        blk0[a + 1] = blk0[a] + s.P;
+        cblk0[a + 1] = cblk0[a] + (src.D + kFinCols - 1) / kFinCols;
+    }
+    if ((e = hipMemcpyAsync(base, h, tab_bytes, hipMemcpyHostToDevice, st)) != hipSuccess) return e;
+    if ((e = hipEventRecord(g_stage.ev, st)) != hipSuccess) return e;
+    g_stage.pending = true;
+
+    const DevJob *d_jobs = reinterpret_cast<const DevJob *>(base + L.tab_jobs);
+    const int *d_blk0 = reinterpret_cast<const int *>(base + L.tab_blk0);
+    const int *d_cblk0 = reinterpret_cast<const int *>(base + L.tab_cblk0);
+    int nact = A;
+    for (int r = 0; r < R; ++r) {
+        while (nact > 0 && iters[order[nact - 1]] <= r) --nact;
+        const bool prof = g_prof.on && g_prof.used < g_prof.cap;
+        if (prof && (e = hipEventRecord(g_prof.ev[2 * g_prof.used], st)) != hipSuccess) return e;
+        if ((e = launch_row_pass(d_jobs, d_blk0, nact, blk0[nact], max_cls, st)) != hipSuccess) return e;
+        if (prof) {
+            if ((e = hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st)) != hipSuccess) return e;
+            ++g_prof.used;
+        }
+        if ((e = launch_finalize(d_jobs, d_cblk0, nact, cblk0[nact], r, st)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+}  // namespace slaqglm
+
+using namespace slaqglm;
+
+extern "C" {
+
+int glm_workspace_bytes(const glm_job_t *jobs, int32_t J, int32_t M_sweep, size_t *out_bytes) {
+    if (!jobs || !out_bytes || J < 1 || M_sweep < 0) return GLM_EINVAL;
+    if (M_sweep > 0) return GLM_ENOTIMPL;
+    for (int j = 0; j < J; ++j)
+        if (validate_shape(jobs[j].N, jobs[j].D) != GLM_OK) return GLM_EINVAL;
+    *out_bytes = make_layout(jobs, J).total;
+    return GLM_OK;
+}
+
+int glm_step_batched(glm_job_t *jobs, int32_t J, const int32_t *alloc, void *ws, size_t ws_bytes,
+                     void *hip_stream) {
+    if (!jobs || !alloc || J < 1) return GLM_EINVAL;
+    for (int j = 0; j < J; ++j) {
+        const int rc = validate_job(jobs[j]);
+        if (rc != GLM_OK) return rc;
+        if (alloc[j] < 0) return GLM_EINVAL;
+    }
+    for (int j = 0; j < J; ++j)
+        if (jobs[j].hist_len + (int64_t)alloc[j] > jobs[j].hist_cap) return GLM_ENOSPC;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    if (ws_bytes < make_layout(jobs, J).total) return GLM_ENOSPC;
+    const hipError_t e = run_rounds(jobs, J, alloc, ws, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return GLM_EHIP;
+    for (int j = 0; j < J; ++j) jobs[j].hist_len += alloc[j];
+    return GLM_OK;
+}
+
+int glm_step(glm_job_t *job, int32_t iters, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!job) return GLM_EINVAL;
+    return glm_step_batched(job, 1, &iters, ws, ws_bytes, hip_stream);
+}
+
+int glm_sweep(const float *, const float *, int64_t, int32_t, int32_t, int32_t, float *, float *,
+              const float *, const float *, int32_t, float *, void *, size_t, void *) {
+    return GLM_ENOTIMPL;
+}
+
+int glm_read_probe(const float *src, size_t n, float *sink, void *hip_stream) {
+    if (!src || !sink || n == 0 || (n & 3) != 0 || !aligned16(src)) return GLM_EINVAL;
+    return launch_read_probe(src, n, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? GLM_OK : GLM_EHIP;
+}
+
+int32_t glm_read_probe_sink_floats(void) { return kProbeBlocks; }
+
+int glm_profile_begin(int32_t cap) {
+    if (cap < 1 || cap > (1 << 20) || g_prof.on) return GLM_EINVAL;
+    g_prof.ev.resize(2 * (size_t)cap);
+    for (size_t i = 0; i < g_prof.ev.size(); ++i) {
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+            for (size_t k = 0; k < i; ++k) (void)hipEventDestroy(g_prof.ev[k]);
+            g_prof.ev.clear();
+            return GLM_EHIP;
+        }
+    }
+    g_prof.cap = cap; g_prof.used = 0; g_prof.on = true;
+    return GLM_OK;
+}
+
+int glm_profile_end(float *ms, int32_t *count) {
+    if (!ms || !count || !g_prof.on) return GLM_EINVAL;
+    int rc = GLM_OK;
+    for (int i = 0; i < g_prof.used; ++i) {
+        if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms[i], g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess)
+            rc = GLM_EHIP;
+    }
+    *count = g_prof.used;
+    for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+    g_prof.ev.clear();
+    g_prof.on = false; g_prof.cap = 0; g_prof.used = 0;
+    return rc;
+}
+
+const char *glm_strerror(int status) {
+    switch (status) {
+        case GLM_OK: return "ok";
+        case GLM_EINVAL: return "invalid argument";
+        case GLM_ENOSPC: return "loss history or workspace too small";
+        case GLM_EHIP: return "HIP runtime error";
+        case GLM_ENOTIMPL: return "not implemented";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

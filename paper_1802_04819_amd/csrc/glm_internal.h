@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of libslaqglm (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "slaqglm.h"
+
+namespace slaqglm {
+
+// Device-side view of one job for the duration of one call.  Built on the host,
+// copied into the workspace, read by the kernels through scalar loads.
+struct DevJob {
+    const float *X;
+    const float *y;
+    float       *w;
+    float       *grad;
+    float       *loss_out;   // loss_hist + hist_len: round r of the call writes loss_out[r]
+    float       *gpart;      // [P, D]  per-row-block partial sums of X^T r
+    float       *lpart;      // [P]     per-row-block partial sums of the per-sample loss
+    double      *wn2;        // [1]     |w|^2 of the iterate that entered the round
+    long long    N;
+    double       invN;
+    int          D;
+    int          loss;
+    float        lambda;
+    float        step;
+    int          P;          // row blocks; a function of (N, D) only
+    int          cls;        // lane-layout class; a function of D only
+    int          iters;      // rounds this job takes part in during this call
+    int          pad;
+};
+
+// Lane-layout classes of the row pass.  A row of D floats is D/4 float4 slots; a wave of 64
+// lanes covers it with LPR lanes per row (64/LPR rows side by side) and C slots per lane.
+constexpr int kNumClasses = 9;
+struct ClassInfo { int lpr; int c; int b; int pmax; };
+// b = wave-loads in flight per loop trip; pmax = cap on row blocks per job.
+__host__ __device__ constexpr ClassInfo class_info(int cls) {
+    constexpr ClassInfo t[kNumClasses] = {
+        {4, 1, 8, 2048},    // D <= 16
+        {8, 1, 8, 2048},    // D <= 32
+        {16, 1, 8, 2048},   // D <= 64
+        {32, 1, 8, 2048},   // D <= 128
+        {64, 1, 8, 2048},   // D <= 256
+        {64, 2, 8, 2048},   // D <= 512
+        {64, 4, 4, 2048},   // D <= 1024
+        {64, 8, 2, 1024},   // D <= 2048
+        {64, 16, 1, 1024},  // D <= 4096
+    };
+    return t[cls];
+}
+int class_of_D(int D);
+int row_blocks(long long N, int cls);
+
+constexpr int kRowBlockThreads = 256;   // 4 waves
+constexpr int kFinCols = 32;            // columns per finalize block
+constexpr int kFinSegs = 8;             // row-block segments summed side by side per column
+
+// Launchers (glm_rows.hip).  `tab_*` are device pointers into the workspace.
+hipError_t launch_row_pass(const DevJob *jobs, const int *blk0, int nact, int total_blocks,
+                           int max_cls, hipStream_t st);
+hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int total_blocks,
+                           int round, hipStream_t st);
+hipError_t launch_read_probe(const float *src, size_t n, float *sink, hipStream_t st);
+constexpr int kProbeBlocks = 4096;
+
+}  // namespace slaqglm

@@ -1,0 +1,219 @@
+"""ctypes binding of libslaqglm (declared in include/slaqglm.h).
+
+Argument marshalling only: every step of the iteration runs in the library's HIP
+kernels.  PyTorch supplies device memory (tensors) and the stream handle.  There
+is no fallback: if the library cannot be loaded, or no GPU is present when a
+compute entry point is called, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+GLM_LOGISTIC, GLM_HINGE, GLM_SQUARED = 0, 1, 2
+GLM_OK, GLM_EINVAL, GLM_ENOSPC, GLM_EHIP, GLM_ENOTIMPL = 0, -1, -2, -3, -4
+
+EXPORTS = (
+    "glm_workspace_bytes", "glm_step", "glm_step_batched", "glm_sweep", "glm_read_probe",
+    "glm_read_probe_sink_floats", "glm_profile_begin", "glm_profile_end", "glm_strerror",
+)
+
+
+class glm_job_t(ctypes.Structure):
+    """Mirror of the C struct glm_job_t."""
+    _fields_ = [
+        ("X", ctypes.c_void_p), ("y", ctypes.c_void_p), ("w", ctypes.c_void_p),
+        ("grad", ctypes.c_void_p), ("loss_hist", ctypes.c_void_p),
+        ("N", ctypes.c_int64), ("D", ctypes.c_int32), ("loss", ctypes.c_int32),
+        ("lambda_", ctypes.c_float), ("step", ctypes.c_float),
+        ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64),
+    ]
+
+
+class GlmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB_PATH
+
+
+def load():
+    """Load libslaqglm.so from the package directory (building it only if it is absent)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build_lib(force=True)
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    jp = ctypes.POINTER(glm_job_t)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    lib.glm_workspace_bytes.restype = ctypes.c_int
+    lib.glm_workspace_bytes.argtypes = [jp, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.glm_step.restype = ctypes.c_int
+    lib.glm_step.argtypes = [jp, ctypes.c_int32, vp, sz, vp]
+    lib.glm_step_batched.restype = ctypes.c_int
+    lib.glm_step_batched.argtypes = [jp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), vp, sz, vp]
+    lib.glm_sweep.restype = ctypes.c_int
+    lib.glm_sweep.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                              vp, vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
+                              ctypes.c_int32, vp, vp, sz, vp]
+    lib.glm_read_probe.restype = ctypes.c_int
+    lib.glm_read_probe.argtypes = [vp, sz, vp, vp]
+    lib.glm_read_probe_sink_floats.restype = ctypes.c_int32
+    lib.glm_read_probe_sink_floats.argtypes = []
+    lib.glm_profile_begin.restype = ctypes.c_int
+    lib.glm_profile_begin.argtypes = [ctypes.c_int32]
+    lib.glm_profile_end.restype = ctypes.c_int
+    lib.glm_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
+    lib.glm_strerror.restype = ctypes.c_char_p
+    lib.glm_strerror.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load().glm_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != GLM_OK:
+        raise GlmError(status, where)
+
+
+def _stream_handle(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(int(stream.cuda_stream))
+
+
+def _require_gpu():
+    if not torch.cuda.is_available():
+        raise RuntimeError("libslaqglm needs a GPU: torch.cuda.is_available() is False")
+
+
+class Job:
+    """A glm_job_t plus the tensors its pointers refer to (kept alive here)."""
+
+    def __init__(self, X: torch.Tensor, y: torch.Tensor, w: torch.Tensor, loss: int, lam: float,
+                 step: float, hist_cap: int, grad: Optional[torch.Tensor] = None,
+                 loss_hist: Optional[torch.Tensor] = None):
+        for t, name in ((X, "X"), (y, "y"), (w, "w")):
+            if t.dtype != torch.float32 or not t.is_contiguous():
+                raise TypeError(f"{name} must be a contiguous float32 tensor")
+        if X.dim() != 2 or y.shape != (X.shape[0],) or w.shape != (X.shape[1],):
+            raise ValueError("expected X [N, D], y [N], w [D]")
+        dev = X.device
+        self.X, self.y, self.w = X, y, w
+        self.grad = grad if grad is not None else torch.zeros(X.shape[1], dtype=torch.float32, device=dev)
+        self.loss_hist = (loss_hist if loss_hist is not None
+                          else torch.zeros(max(int(hist_cap), 1), dtype=torch.float32, device=dev))
+        self.c = glm_job_t(X.data_ptr(), y.data_ptr(), w.data_ptr(), self.grad.data_ptr(),
+                           self.loss_hist.data_ptr(), int(X.shape[0]), int(X.shape[1]), int(loss),
+                           float(lam), float(step), 0, int(hist_cap))
+
+    @property
+    def hist_len(self) -> int:
+        return int(self.c.hist_len)
+
+    def history(self) -> torch.Tensor:
+        """The loss values appended so far (device tensor view; synchronise before reading)."""
+        return self.loss_hist[: self.hist_len]
+
+
+def _as_array(jobs: Sequence[Job]):
+    arr = (glm_job_t * len(jobs))()
+    for i, j in enumerate(jobs):
+        arr[i] = j.c
+    return arr
+
+
+def _copy_back(arr, jobs: Sequence[Job]):
+    for i, j in enumerate(jobs):
+        j.c.hist_len = arr[i].hist_len
+
+
+def glm_workspace_bytes(jobs: Sequence[Job], M_sweep: int = 0) -> int:
+    out = ctypes.c_size_t(0)
+    arr = _as_array(jobs)
+    _check(load().glm_workspace_bytes(arr, len(jobs), int(M_sweep), ctypes.byref(out)),
+           "glm_workspace_bytes")
+    return int(out.value)
+
+
+def alloc_workspace(jobs: Sequence[Job], M_sweep: int = 0) -> torch.Tensor:
+    """A uint8 device tensor of the size glm_workspace_bytes reports (torch allocations are
+    at least 256-byte aligned)."""
+    n = glm_workspace_bytes(jobs, M_sweep)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=jobs[0].X.device)
+
+
+def glm_step(job: Job, iters: int, ws: torch.Tensor, stream=None) -> None:
+    _require_gpu()
+    _check(load().glm_step(ctypes.byref(job.c), int(iters), ctypes.c_void_p(ws.data_ptr()),
+                           ws.numel() * ws.element_size(), _stream_handle(stream)), "glm_step")
+
+
+def glm_step_batched(jobs: Sequence[Job], alloc, ws: torch.Tensor, stream=None) -> None:
+    _require_gpu()
+    a = np.ascontiguousarray(np.asarray(alloc, dtype=np.int32))
+    if a.shape != (len(jobs),):
+        raise ValueError("alloc must have one entry per job")
+    arr = _as_array(jobs)
+    rc = load().glm_step_batched(arr, len(jobs), a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                 ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size(),
+                                 _stream_handle(stream))
+    _check(rc, "glm_step_batched")
+    _copy_back(arr, jobs)
+
+
+def glm_sweep(X: torch.Tensor, y: torch.Tensor, loss: int, W: torch.Tensor, G: torch.Tensor,
+              lambdas, steps, iters: int, loss_hist: torch.Tensor, ws: torch.Tensor,
+              stream=None) -> None:
+    _require_gpu()
+    M, D = int(W.shape[0]), int(W.shape[1])
+    lam = np.ascontiguousarray(np.asarray(lambdas, dtype=np.float32))
+    eta = np.ascontiguousarray(np.asarray(steps, dtype=np.float32))
+    if lam.shape != (M,) or eta.shape != (M,):
+        raise ValueError("lambdas and steps must have M entries")
+    fp = ctypes.POINTER(ctypes.c_float)
+    rc = load().glm_sweep(ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(y.data_ptr()),
+                          int(X.shape[0]), D, M, int(loss), ctypes.c_void_p(W.data_ptr()),
+                          ctypes.c_void_p(G.data_ptr()), lam.ctypes.data_as(fp), eta.ctypes.data_as(fp),
+                          int(iters), ctypes.c_void_p(loss_hist.data_ptr()),
+                          ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size(),
+                          _stream_handle(stream))
+    _check(rc, "glm_sweep")
+
+
+def glm_read_probe(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    _require_gpu()
+    _check(load().glm_read_probe(ctypes.c_void_p(src.data_ptr()), src.numel(),
+                                 ctypes.c_void_p(sink.data_ptr()), _stream_handle(stream)),
+           "glm_read_probe")
+
+
+def glm_read_probe_sink_floats() -> int:
+    return int(load().glm_read_probe_sink_floats())
+
+
+def glm_profile_begin(cap: int) -> None:
+    _check(load().glm_profile_begin(int(cap)), "glm_profile_begin")
+
+
+def glm_profile_end(cap: int) -> List[float]:
+    ms = (ctypes.c_float * int(cap))()
+    n = ctypes.c_int32(0)
+    _check(load().glm_profile_end(ms, ctypes.byref(n)), "glm_profile_end")
+    return [float(ms[i]) for i in range(n.value)]
