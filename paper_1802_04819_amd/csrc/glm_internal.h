@@ -39,13 +39,13 @@ struct ClassInfo { int lpr; int c; int b; int pmax; };
 // b = wave-loads in flight per loop trip; pmax = cap on row blocks per job.
 __host__ __device__ constexpr ClassInfo class_info(int cls) {
     constexpr ClassInfo t[kNumClasses] = {
-        {4, 1, 8, 2048},    // D <= 16
-        {8, 1, 8, 2048},    // D <= 32
-        {16, 1, 8, 2048},   // D <= 64
-        {32, 1, 8, 2048},   // D <= 128
-        {64, 1, 8, 2048},   // D <= 256
-        {64, 2, 8, 2048},   // D <= 512
-        {64, 4, 4, 2048},   // D <= 1024
+        {4, 1, 8, 1024},    // D <= 16
+        {8, 1, 8, 1024},    // D <= 32
+        {16, 1, 8, 1024},   // D <= 64
+        {32, 1, 8, 1024},   // D <= 128
+        {64, 1, 8, 1024},   // D <= 256
+        {64, 2, 8, 1024},   // D <= 512
+        {64, 4, 8, 2048},   // D <= 1024
         {64, 8, 2, 1024},   // D <= 2048
         {64, 16, 1, 1024},  // D <= 4096
     };
@@ -55,8 +55,8 @@ int class_of_D(int D);
 int row_blocks(long long N, int cls);
 
 constexpr int kRowBlockThreads = 256;   // 4 waves
-constexpr int kFinCols = 32;            // columns per finalize block
-constexpr int kFinSegs = 8;             // row-block segments summed side by side per column
+constexpr int kFinCols = 16;            // columns per finalize block
+constexpr int kFinSegs = 64;            // row-block segments summed side by side per column
 
 // Launchers (glm_rows.hip).  `tab_*` are device pointers into the workspace.
 hipError_t launch_row_pass(const DevJob *jobs, const int *blk0, int nact, int total_blocks,

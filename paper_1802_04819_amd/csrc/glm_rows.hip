@@ -250,8 +250,10 @@ hipError_t launch_row_pass(const DevJob *jobs, const int *blk0, int nact, int to
 
 __global__ __launch_bounds__(kFinCols * kFinSegs) void finalize_kernel(
     const DevJob *__restrict__ jobs, const int *__restrict__ cblk0, int nact, int round) {
+    constexpr int T = kFinCols * kFinSegs;
     __shared__ double sred[kFinSegs][kFinCols];
-    __shared__ double lred[kFinCols * kFinSegs];
+    __shared__ double lred[T];
+    __shared__ double lred2[32];
     const int a = find_segment(cblk0, nact, blockIdx.x);
     const DevJob &jb = jobs[a];
     const int cb = blockIdx.x - cblk0[a];
@@ -261,20 +263,27 @@ __global__ __launch_bounds__(kFinCols * kFinSegs) void finalize_kernel(
     const int D = jb.D, P = jb.P;
     const int col = cb * kFinCols + cl;
 
-    // column sums: segment `seg` adds row blocks [P*seg/8, P*(seg+1)/8) in index order
+    // column sums: segment `seg` adds row blocks [P*seg/S, P*(seg+1)/S) in index order
     double s = 0.0;
     if (col < D) {
         const int p0 = (int)((long long)P * seg / kFinSegs);
         const int p1 = (int)((long long)P * (seg + 1) / kFinSegs);
         const float *__restrict__ gp = jb.gpart + col;
-        for (int p = p0; p < p1; ++p) s += (double)gp[(size_t)p * D];
+        int p = p0;
+        for (; p + 16 <= p1; p += 16) {          // 16 loads in flight, added in index order
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = gp[(size_t)(p + u) * D];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) s += (double)v[u];
+        }
+        for (; p < p1; ++p) s += (double)gp[(size_t)p * D];
     }
     sred[seg][cl] = s;
 
     // loss sum (first column block of the job only): thread t adds a contiguous run of blocks
     const bool does_loss = (cb == 0);
     if (does_loss) {
-        constexpr int T = kFinCols * kFinSegs;
         const int p0 = (int)((long long)P * tid / T);
         const int p1 = (int)((long long)P * (tid + 1) / T);
         double ls = 0.0;
@@ -285,18 +294,26 @@ __global__ __launch_bounds__(kFinCols * kFinSegs) void finalize_kernel(
 
     if (seg == 0 && col < D) {
         double tot = sred[0][cl];
-#pragma unroll
+#pragma unroll 8
         for (int q = 1; q < kFinSegs; ++q) tot += sred[q][cl];
         const float wj = jb.w[col];
         const double g = tot * jb.invN + (double)jb.lambda * (double)wj;
         jb.grad[col] = (float)g;
         if (jb.step != 0.0f) jb.w[col] = (float)((double)wj - (double)jb.step * g);
     }
-    if (does_loss && tid == 0) {
-        double S = 0.0;
-        for (int q = 0; q < kFinCols * kFinSegs; ++q) S += lred[q];
-        const double L = S * jb.invN + 0.5 * (double)jb.lambda * (*jb.wn2);
-        jb.loss_out[round] = (float)L;
+    if (does_loss) {                       // fixed two-level sum of the T thread partials
+        if (tid < 32) {
+            double S = 0.0;
+            for (int q = 0; q < T / 32; ++q) S += lred[tid * (T / 32) + q];
+            lred2[tid] = S;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double S = 0.0;
+            for (int q = 0; q < 32; ++q) S += lred2[q];
+            const double L = S * jb.invN + 0.5 * (double)jb.lambda * (*jb.wn2);
+            jb.loss_out[round] = (float)L;
+        }
     }
 }
 
