@@ -100,6 +100,33 @@ struct Profile {
 };
 Profile g_prof;
 
+// Waits until the staging buffer is free, makes it at least `bytes` large and returns it.
+// Caller holds g_stage.mu, fills the buffer, enqueues the copy and calls stage_mark().
+hipError_t stage_acquire(size_t bytes, char **out) {
+    hipError_t e;
+    if (g_stage.pending) {
+        if ((e = hipEventSynchronize(g_stage.ev)) != hipSuccess) return e;
+        g_stage.pending = false;
+    }
+    if (g_stage.cap < bytes) {
+        if (g_stage.host) { (void)hipHostFree(g_stage.host); g_stage.host = nullptr; g_stage.cap = 0; }
+        const size_t want = std::max<size_t>(bytes, 1 << 16);
+        if ((e = hipHostMalloc(&g_stage.host, want, hipHostMallocDefault)) != hipSuccess) return e;
+        g_stage.cap = want;
+    }
+    if (!g_stage.ev) {
+        if ((e = hipEventCreateWithFlags(&g_stage.ev, hipEventDisableTiming)) != hipSuccess) return e;
+    }
+    *out = static_cast<char *>(g_stage.host);
+    return hipSuccess;
+}
+
+hipError_t stage_mark(hipStream_t st) {
+    const hipError_t e = hipEventRecord(g_stage.ev, st);
+    if (e == hipSuccess) g_stage.pending = true;
+    return e;
+}
+
 hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, hipStream_t st) {
     // Active jobs sorted by iteration count, descending (stable): the jobs still active in
     // round r are then a prefix of the table, and one table serves every round.
@@ -117,20 +144,8 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
 
     std::lock_guard<std::mutex> lock(g_stage.mu);
     hipError_t e;
-    if (g_stage.pending) {
-        if ((e = hipEventSynchronize(g_stage.ev)) != hipSuccess) return e;
-        g_stage.pending = false;
-    }
-    if (g_stage.cap < tab_bytes) {
-        if (g_stage.host) { (void)hipHostFree(g_stage.host); g_stage.host = nullptr; g_stage.cap = 0; }
-        const size_t want = std::max<size_t>(tab_bytes, 1 << 16);
-        if ((e = hipHostMalloc(&g_stage.host, want, hipHostMallocDefault)) != hipSuccess) return e;
-        g_stage.cap = want;
-    }
-    if (!g_stage.ev) {
-        if ((e = hipEventCreateWithFlags(&g_stage.ev, hipEventDisableTiming)) != hipSuccess) return e;
-    }
-    char *h = static_cast<char *>(g_stage.host);
+    char *h = nullptr;
+    if ((e = stage_acquire(tab_bytes, &h)) != hipSuccess) return e;
     std::memset(h, 0, tab_bytes);
     DevJob *dj = reinterpret_cast<DevJob *>(h + L.tab_jobs);
     int *blk0 = reinterpret_cast<int *>(h + L.tab_blk0);
@@ -154,8 +169,7 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
         cblk0[a + 1] = cblk0[a] + (src.D + kFinCols - 1) / kFinCols;
     }
     if ((e = hipMemcpyAsync(base, h, tab_bytes, hipMemcpyHostToDevice, st)) != hipSuccess) return e;
-    if ((e = hipEventRecord(g_stage.ev, st)) != hipSuccess) return e;
-    g_stage.pending = true;
+    if ((e = stage_mark(st)) != hipSuccess) return e;
 
     const DevJob *d_jobs = reinterpret_cast<const DevJob *>(base + L.tab_jobs);
     const int *d_blk0 = reinterpret_cast<const int *>(base + L.tab_blk0);
@@ -175,6 +189,29 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
     return hipSuccess;
 }
 
+// Workspace layout of the sweep: [lambdas | steps][R][lossP][Gpart].
+struct SweepLayout { size_t hyper, R, lossP, Gpart, total; int T, S; };
+
+SweepLayout make_sweep_layout(long long N, int D) {
+    SweepLayout L;
+    L.T = (int)((N + kSweepFwdRows - 1) / kSweepFwdRows);
+    const long long chunks = (N + kSweepBwdRows - 1) / kSweepBwdRows;
+    L.S = (int)std::min<long long>(chunks, kSweepSplitMax);
+    size_t off = 0;
+    L.hyper = off; off = align_up(off + sizeof(float) * 2 * kSweepM);
+    L.R = off;     off = align_up(off + sizeof(float) * (size_t)N * kSweepM);
+    L.lossP = off; off = align_up(off + sizeof(float) * (size_t)kSweepM * L.T);
+    L.Gpart = off; off = align_up(off + sizeof(float) * (size_t)L.S * kSweepM * D);
+    L.total = off;
+    return L;
+}
+
+int validate_sweep_shape(long long N, int D, int M) {
+    if (N < 1 || N > (1LL << 31) * kSweepFwdRows - 1) return GLM_EINVAL;
+    if (D < 32 || D > 4096 || (D % 32) != 0 || M < 1 || M > kSweepM) return GLM_EINVAL;
+    return GLM_OK;
+}
+
 }  // namespace
 }  // namespace slaqglm
 
@@ -184,7 +221,11 @@ extern "C" {
 
 int glm_workspace_bytes(const glm_job_t *jobs, int32_t J, int32_t M_sweep, size_t *out_bytes) {
     if (!jobs || !out_bytes || J < 1 || M_sweep < 0) return GLM_EINVAL;
-    if (M_sweep > 0) return GLM_ENOTIMPL;
+    if (M_sweep > 0) {
+        if (validate_sweep_shape(jobs[0].N, jobs[0].D, M_sweep) != GLM_OK) return GLM_EINVAL;
+        *out_bytes = make_sweep_layout(jobs[0].N, jobs[0].D).total;
+        return GLM_OK;
+    }
     for (int j = 0; j < J; ++j)
         if (validate_shape(jobs[j].N, jobs[j].D) != GLM_OK) return GLM_EINVAL;
     *out_bytes = make_layout(jobs, J).total;
@@ -214,9 +255,58 @@ int glm_step(glm_job_t *job, int32_t iters, void *ws, size_t ws_bytes, void *hip
     return glm_step_batched(job, 1, &iters, ws, ws_bytes, hip_stream);
 }
 
-int glm_sweep(const float *, const float *, int64_t, int32_t, int32_t, int32_t, float *, float *,
-              const float *, const float *, int32_t, float *, void *, size_t, void *) {
-    return GLM_ENOTIMPL;
+int glm_sweep(const float *X, const float *y, int64_t N, int32_t D, int32_t M, int32_t loss, float *W,
+              float *G, const float *lambdas, const float *steps, int32_t iters, float *loss_hist,
+              void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!X || !y || !W || !G || !lambdas || !steps || !loss_hist || iters < 0) return GLM_EINVAL;
+    if (validate_sweep_shape(N, D, M) != GLM_OK) return GLM_EINVAL;
+    if (!aligned16(X) || !aligned16(W)) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(y) & 3u) || (reinterpret_cast<uintptr_t>(G) & 3u) ||
+        (reinterpret_cast<uintptr_t>(loss_hist) & 3u))
+        return GLM_EINVAL;
+    if (loss < GLM_LOGISTIC || loss > GLM_SQUARED) return GLM_EINVAL;
+    for (int m = 0; m < M; ++m) {
+        if (!std::isfinite(lambdas[m]) || lambdas[m] < 0.0f) return GLM_EINVAL;
+        if (!std::isfinite(steps[m]) || steps[m] < 0.0f) return GLM_EINVAL;
+    }
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    const SweepLayout L = make_sweep_layout(N, D);
+    if (ws_bytes < L.total) return GLM_ENOSPC;
+    if (iters == 0) return GLM_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(ws);
+    {
+        std::lock_guard<std::mutex> lock(g_stage.mu);
+        char *h = nullptr;
+        if (stage_acquire(sizeof(float) * 2 * kSweepM, &h) != hipSuccess) return GLM_EHIP;
+        float *hf = reinterpret_cast<float *>(h);
+        for (int m = 0; m < kSweepM; ++m) {
+            hf[m] = m < M ? lambdas[m] : 0.0f;
+            hf[kSweepM + m] = m < M ? steps[m] : 0.0f;
+        }
+        if (hipMemcpyAsync(base + L.hyper, h, sizeof(float) * 2 * kSweepM, hipMemcpyHostToDevice, st) !=
+            hipSuccess)
+            return GLM_EHIP;
+        if (stage_mark(st) != hipSuccess) return GLM_EHIP;
+    }
+    SweepArgs a;
+    a.X = X; a.y = y; a.W = W; a.G = G; a.loss_hist = loss_hist;
+    a.lambdas = reinterpret_cast<const float *>(base + L.hyper);
+    a.steps = a.lambdas + kSweepM;
+    a.R = reinterpret_cast<float *>(base + L.R);
+    a.lossP = reinterpret_cast<float *>(base + L.lossP);
+    a.Gpart = reinterpret_cast<float *>(base + L.Gpart);
+    a.N = N; a.D = D; a.M = M; a.loss = loss; a.T = L.T; a.S = L.S;
+    for (int k = 0; k < iters; ++k) {
+        hipEvent_t *ev = nullptr;
+        if (g_prof.on && g_prof.used + 2 <= g_prof.cap) {
+            ev = &g_prof.ev[2 * g_prof.used];
+            g_prof.used += 2;
+        }
+        if (launch_sweep_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
+    }
+    return GLM_OK;
 }
 
 int glm_read_probe(const float *src, size_t n, float *sink, void *hip_stream) {

@@ -66,4 +66,22 @@ hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int t
 hipError_t launch_read_probe(const float *src, size_t n, float *sink, hipStream_t st);
 constexpr int kProbeBlocks = 4096;
 
+// Sweep (glm_sweep.hip).  M models are padded to kSweepM columns of R and rows of Gpart.
+constexpr int kSweepM = 64;
+constexpr int kSweepFwdRows = 128;      // rows per forward tile
+constexpr int kSweepBwdRows = 32;       // rows per backward chunk
+constexpr int kSweepBwdCols = 256;      // columns per backward slab
+constexpr int kSweepSplitMax = 128;     // row splits of the backward contraction
+struct SweepArgs {
+    const float *X; const float *y; float *W; float *G; float *loss_hist;
+    const float *lambdas; const float *steps;       // device copies, [M]
+    float *R;        // [N, kSweepM] residuals
+    float *lossP;    // [M, T] per-tile loss sums
+    float *Gpart;    // [S, kSweepM, D] partial gradients
+    long long N; int D, M, loss, T, S;
+};
+// Enqueues forward, backward and finalize of iteration k.  `ev`, if not null, points at
+// four events recorded around the forward and around the backward kernel.
+hipError_t launch_sweep_iteration(const SweepArgs &a, int k, hipEvent_t *ev, hipStream_t st);
+
 }  // namespace slaqglm

@@ -159,6 +159,21 @@ def alloc_workspace(jobs: Sequence[Job], M_sweep: int = 0) -> torch.Tensor:
     return torch.empty(max(n, 256), dtype=torch.uint8, device=jobs[0].X.device)
 
 
+def sweep_workspace_bytes(N: int, D: int, M: int) -> int:
+    """glm_workspace_bytes for a sweep of M models over an [N, D] matrix."""
+    shape = glm_job_t()
+    shape.N, shape.D = int(N), int(D)
+    out = ctypes.c_size_t(0)
+    _check(load().glm_workspace_bytes(ctypes.byref(shape), 1, int(M), ctypes.byref(out)),
+           "glm_workspace_bytes")
+    return int(out.value)
+
+
+def alloc_sweep_workspace(X: torch.Tensor, M: int) -> torch.Tensor:
+    n = sweep_workspace_bytes(int(X.shape[0]), int(X.shape[1]), M)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=X.device)
+
+
 def glm_step(job: Job, iters: int, ws: torch.Tensor, stream=None) -> None:
     _require_gpu()
     _check(load().glm_step(ctypes.byref(job.c), int(iters), ctypes.c_void_p(ws.data_ptr()),
