@@ -1,0 +1,125 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot replay whole trajectories of the 16 GB configuration in test time, so the
+large cases are checked per step: the oracle is evaluated (all host cores, chunked rows) at the
+very fp32 iterate the GPU iteration started from, for a few iterations spread over the run.
+Inputs are drawn on the GPU and copied to the host, so both sides read the same bits.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1802_04819_amd import glm, synth
+from _parity import REL_TOL, check_step_against_oracle, rel
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _threads():
+    return max(2, oracle.max_threads())
+
+
+def test_config1_full_trajectory_and_steps():
+    _say("[case] config 1 full size: hinge 1e6 x 256, 100 iterations")
+    p = synth.config1(device="cuda")
+    Xn, yn = p.X.cpu().numpy(), p.y.cpu().numpy()
+    job = glm.Job(p.X, p.y, p.w0.clone(), p.loss, p.lam, p.eta, p.K)
+    ws = glm.alloc_workspace([job])
+    check_at = {0, 1, 50, 99}
+    gn = []
+    for k in range(p.K):
+        w_in = job.w.cpu().numpy().copy() if k in check_at else None
+        glm.glm_step(job, 1, ws)
+        gn.append(torch.linalg.vector_norm(job.grad.double()).item())
+        if k in check_at:
+            torch.cuda.synchronize()
+            check_step_against_oracle(p.loss, Xn, yn, w_in, p.lam, job.loss_hist[k].item(),
+                                      job.grad.cpu().numpy(), chunks=_threads(), tag=f"cfg1 k={k}")
+    torch.cuda.synchronize()
+    lh, gh, wK, _ = oracle.run(p.loss, Xn, yn, np.zeros(p.D), p.lam, p.eta, p.K, chunks=_threads())
+    got = job.history().cpu().numpy()
+    assert got[0] == 1.0
+    for k in range(p.K):
+        assert rel(got[k], lh[k]) <= REL_TOL, (k, got[k], lh[k])
+        assert rel(gn[k], gh[k]) <= REL_TOL, (k, gn[k], gh[k])
+    assert got.min() < 0.6 * got[0]
+
+
+def test_config2_full_size_steps():
+    _say("[case] config 2 full size: logistic 4e6 x 1024 with scaled columns, 20 iterations")
+    p = synth.config2(device="cuda")
+    assert p.X.shape == (4_000_000, 1024)
+    job = glm.Job(p.X, p.y, p.w0.clone(), p.loss, p.lam, p.eta, p.K)
+    ws = glm.alloc_workspace([job])
+    saved = {}
+    for k in range(p.K):
+        if k in (0, 10, 19):
+            saved[k] = job.w.clone()
+        glm.glm_step(job, 1, ws)
+        if k in (0, 10, 19):
+            saved[k] = (saved[k], job.grad.clone())
+    torch.cuda.synchronize()
+    got = job.history().cpu().numpy()
+    assert abs(got[0] - np.log(2.0)) < 2e-6
+    assert np.all(np.isfinite(got)) and got[-1] < got[0]
+    _say("[case] config 2: copying X to the host for the oracle")
+    Xn, yn = p.X.cpu().numpy(), p.y.cpu().numpy()
+    for k, (w_in, g_out) in saved.items():
+        _say(f"[case] config 2: oracle at iterate {k}")
+        check_step_against_oracle(p.loss, Xn, yn, w_in.cpu().numpy(), p.lam, got[k],
+                                  g_out.cpu().numpy(), chunks=_threads(), tag=f"cfg2 k={k}")
+
+
+def test_config3_full_size_epoch_sampled_jobs():
+    _say("[case] config 3 full size: 160 jobs, one epoch, sampled jobs against the oracle")
+    specs = synth.config3_specs()
+    probs = [synth.config3_job(s, device="cuda") for s in specs]
+    alloc = synth.config3_alloc(0)
+    jobs = [glm.Job(p.X, p.y, p.w0.clone(), p.loss, p.lam, p.eta, 8) for p in probs]
+    ws = glm.alloc_workspace(jobs)
+    glm.glm_step_batched(jobs, alloc, ws)
+    torch.cuda.synchronize()
+    assert all(j.hist_len == int(a) for j, a in zip(jobs, alloc))
+    for j, p in zip(jobs, probs):            # closed forms at w = 0 for every job
+        first = j.loss_hist[0].item()
+        if p.loss == synth.LOGISTIC:
+            assert abs(first - np.log(2.0)) < 2e-6
+        elif p.loss == synth.HINGE:
+            assert first == 1.0
+        assert torch.isfinite(j.history()).all()
+    for idx in (0, 23, 57, 101, 159):
+        p, j, a = probs[idx], jobs[idx], int(alloc[idx])
+        _say(f"[case] config 3: oracle trajectory of job {idx} ({p.name}, {a} iterations)")
+        lh, gh, wK, _ = oracle.run(p.loss, p.X.cpu().numpy(), p.y.cpu().numpy(), np.zeros(p.D),
+                                   p.lam, p.eta, a, chunks=_threads())
+        got = j.history().cpu().numpy()
+        for k in range(a):
+            assert rel(got[k], lh[k]) <= REL_TOL, (idx, k, got[k], lh[k])
+        assert rel(np.linalg.norm(j.grad.cpu().numpy().astype(np.float64)), gh[-1]) <= REL_TOL
+        assert np.max(np.abs(j.w.cpu().numpy() - wK)) <= REL_TOL * max(np.max(np.abs(wK)), 1e-30)
+
+
+def test_config4_full_size_sampled_models():
+    _say("[case] config 4 full size: 64 models on 1e6 x 1024, sampled models against the oracle")
+    sp = synth.config4(device="cuda")
+    p, M = sp.base, sp.M
+    W = torch.zeros(M, p.D, device="cuda"); G = torch.zeros(M, p.D, device="cuda")
+    hist = torch.zeros(5, M, device="cuda")
+    ws = glm.alloc_sweep_workspace(p.X, M)
+    glm.glm_sweep(p.X, p.y, p.loss, W, G, sp.lams, sp.etas, 4, hist, ws)
+    torch.cuda.synchronize()
+    W4 = W.clone()
+    glm.glm_sweep(p.X, p.y, p.loss, W, G, sp.lams, sp.etas, 1, hist[4:], ws)
+    torch.cuda.synchronize()
+    h = hist.cpu().numpy()
+    assert np.all(np.abs(h[0] - np.log(2.0)) < 2e-6)
+    Xn, yn = p.X.cpu().numpy(), p.y.cpu().numpy()
+    for m in (0, 31, 63):
+        _say(f"[case] config 4: oracle for model {m} at iterate 4")
+        check_step_against_oracle(p.loss, Xn, yn, W4[m].cpu().numpy(), float(sp.lams[m]), h[4, m],
+                                  G[m].cpu().numpy(), chunks=_threads(), tag=f"cfg4 m={m}")
