@@ -33,7 +33,35 @@ def parse():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only; the line says so)")
     ap.add_argument("--check", action="store_true", help="also compare against the oracle on the full data")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, used to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
+
+
+def kernel_sources_sha256():
+    import hashlib
+    d = os.path.join(ROOT, "paper_1802_04819_amd", "csrc")
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(d)):
+        with open(os.path.join(d, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def traffic_from_counters(summary_name):
+    """HBM bytes per launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE, as recorded in a
+    summary under profiles/; None when the kernel sources have changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", summary_name)
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    import re
+    sha = re.search(r"sha256[^`]*`([0-9a-f]{64})`", text)
+    val = re.search(r"^traffic_bytes_per_launch:\s*([0-9.]+)", text, flags=re.M)
+    if not sha or not val or sha.group(1) != kernel_sources_sha256():
+        return None
+    return float(val.group(1))
 
 
 def cpu_baseline_single(p, target_rows):
@@ -113,7 +141,9 @@ def bench_single(args, cfg):
                    "bytes_per_iteration": bytes_per_launch, "scale": args.scale},
         "roofline": {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "avg_launch_ms": avg_ms, "launches": len(k1_ms),
+                     "traffic": (traffic_from_counters("row_pass_cfg2_hbm_counters.md")
+                                 if cfg == 2 and args.scale == 1.0 else None),
+                     "avg_launch_ms": avg_ms, "launches": len(k1_ms),
                      "whole_step_GBps": bytes_per_launch * K / sec / 1e9},
         "rerun_bit_identical": rerun_identical,
         "loss_first": float(hist[0]), "loss_last": float(hist[-1]),
@@ -303,6 +333,12 @@ def main():
         print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.config in (0, 1, 2):
         out = bench_single(args, args.config)
     elif args.config == 3:
