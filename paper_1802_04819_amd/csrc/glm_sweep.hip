@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void sweep_forward_kernel(
     {                                                                                        \
         const int kc_ = (KC);                                                                \
         _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
-            xr[q] = X4[xrow[q] + kc_ * (kFwdK / 4) + xc4[q]];                                \
+            xr[q] = __builtin_nontemporal_load(X4 + xrow[q] + kc_ * (kFwdK / 4) + xc4[q]);   \
         _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                      \
             const f4 t = W4[wrow[q] + kc_ * (kFwdK / 4) + wc4[q]];                       \
             wr[q] = t * wmask[q];                                                            \
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void sweep_backward_kernel(
             row = row < N ? row : N - 1;                                                     \
             int c4 = slab * (kBwdCols / 4) + (idx & 63);   /* slab columns past D read a valid */ \
             c4 = c4 < D4 ? c4 : D4 - 1;                    /* slot; their sums are never stored */ \
-            xr[q] = X4[row * D4 + c4];                                                       \
+            xr[q] = __builtin_nontemporal_load(X4 + row * D4 + c4);                          \
         }                                                                                    \
         _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                      \
             const int idx = tid + 256 * q;         /* row = idx / 16, f4 model = idx % 16 */ \
