@@ -76,8 +76,7 @@ __global__ __launch_bounds__(256) void sweep_forward_kernel(
         _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
             xr[q] = __builtin_nontemporal_load(X4 + xrow[q] + kc_ * (kFwdK / 4) + xc4[q]);   \
         _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                      \
-            const f4 t = W4[wrow[q] + kc_ * (kFwdK / 4) + wc4[q]];                       \
-            wr[q] = t * wmask[q];                                                            \
+            wr[q] = W4[wrow[q] + kc_ * (kFwdK / 4) + wc4[q]];                                \
         }                                                                                    \
     }
 #define SLAQ_FWD_STASH()                                                                     \
@@ -88,7 +87,7 @@ __global__ __launch_bounds__(256) void sweep_forward_kernel(
         }                                                                                    \
         _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                      \
             const int idx = tid + 256 * q;                                                   \
-            Ws4[(idx >> 3) * (kFwdLd / 4) + (idx & 7)] = wr[q];                              \
+            Ws4[(idx >> 3) * (kFwdLd / 4) + (idx & 7)] = wr[q] * wmask[q];                   \
         }                                                                                    \
     }
 
@@ -101,6 +100,7 @@ __global__ __launch_bounds__(256) void sweep_forward_kernel(
     for (int kc = 0; kc < nchunk; ++kc) {
         f4 xr[4], wr[2];
         SLAQ_FWD_FETCH(kc + 1 < nchunk ? kc + 1 : kc)   // last trip re-reads its own chunk (cache hit)
+        __builtin_amdgcn_sched_barrier(0);              // keep the prefetch ahead of the matrix ops
         const f4 *arow = Xs4 + (wave * 32 + li) * (kFwdLd / 4) + lh;
         const f4 *b0row = Ws4 + li * (kFwdLd / 4) + lh;
         const f4 *b1row = Ws4 + (32 + li) * (kFwdLd / 4) + lh;
@@ -187,27 +187,29 @@ __global__ __launch_bounds__(256) void sweep_backward_kernel(
         _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                      \
             const int idx = tid + 256 * q;         /* row = idx / 16, f4 model = idx % 16 */ \
             const long long row = rbase + (idx >> 4);                                        \
-            const float keep = row < N ? 1.0f : 0.0f;      /* rows past N add nothing */      \
-            const f4 t = R4[(row < N ? row : N - 1) * (kSweepM / 4) + (idx & 15)];       \
-            rr[q] = t * keep;                                                                \
+            rkeep[q] = row < N ? 1.0f : 0.0f;              /* rows past N add nothing */      \
+            rr[q] = R4[(row < N ? row : N - 1) * (kSweepM / 4) + (idx & 15)];                \
         }                                                                                    \
     }
 #define SLAQ_BWD_STASH()                                                                     \
     {                                                                                        \
         _Pragma("unroll") for (int q = 0; q < 8; ++q) Xs4[tid + 256 * q] = xr[q];            \
-        _Pragma("unroll") for (int q = 0; q < 2; ++q) Rs4[tid + 256 * q] = rr[q];            \
+        _Pragma("unroll") for (int q = 0; q < 2; ++q) Rs4[tid + 256 * q] = rr[q] * rkeep[q]; \
     }
 
     long long c = s;
     if (c < nchunks) {
         f4 xr[8], rr[2];
+        float rkeep[2];
         SLAQ_BWD_FETCH(c)
         SLAQ_BWD_STASH()
     }
     __syncthreads();
     for (; c < nchunks; c += S) {
         f4 xr[8], rr[2];
+        float rkeep[2];
         SLAQ_BWD_FETCH(c + S < nchunks ? c + S : c)     // last trip re-reads its own chunk
+        __builtin_amdgcn_sched_barrier(0);              // keep the prefetch ahead of the matrix ops
         const float *xa = Xs + lh * kBwdCols + wave * 64 + li;
         const float *ra = Rs + lh * kSweepM + li;
 #pragma unroll
