@@ -56,7 +56,8 @@ int validate_job(const glm_job_t &j) {
 // Workspace layout for a set of jobs: [launch tables][job 0 partials][job 1 partials]...
 struct JobSlots { size_t gpart, lpart, wn2; int P, cls; };
 struct Layout {
-    size_t tab_jobs = 0, tab_blk0 = 0, tab_cblk0 = 0;   // byte offsets
+    size_t tab_jobs = 0, tab_map = 0, tab_cblk0 = 0;    // byte offsets
+    size_t tab_end = 0;                                 // tables occupy [0, tab_end)
     std::vector<JobSlots> slots;
     size_t total = 0;
 };
@@ -65,13 +66,18 @@ Layout make_layout(const glm_job_t *jobs, int J) {
     Layout L;
     size_t off = 0;
     L.tab_jobs = off;  off = align_up(off + sizeof(DevJob) * (size_t)J);
-    L.tab_blk0 = off;  off = align_up(off + sizeof(int) * (size_t)(J + 1));
     L.tab_cblk0 = off; off = align_up(off + sizeof(int) * (size_t)(J + 1));
     L.slots.resize(J);
+    size_t blocks = 0;
+    for (int j = 0; j < J; ++j) {
+        L.slots[j].cls = class_of_D(jobs[j].D);
+        L.slots[j].P = row_blocks(jobs[j].N, L.slots[j].cls);
+        blocks += (size_t)L.slots[j].P;
+    }
+    L.tab_map = off;   off = align_up(off + sizeof(int) * blocks);   // block -> job, one int per row block
+    L.tab_end = off;
     for (int j = 0; j < J; ++j) {
         JobSlots &s = L.slots[j];
-        s.cls = class_of_D(jobs[j].D);
-        s.P = row_blocks(jobs[j].N, s.cls);
         s.gpart = off; off = align_up(off + sizeof(float) * (size_t)s.P * jobs[j].D);
         s.lpart = off; off = align_up(off + sizeof(float) * (size_t)s.P);
         s.wn2 = off;   off = align_up(off + sizeof(double));
@@ -140,7 +146,7 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
 
     const Layout L = make_layout(jobs, J);
     char *base = static_cast<char *>(ws);
-    const size_t tab_bytes = L.slots.empty() ? 0 : L.slots[0].gpart;   // tables precede partials
+    const size_t tab_bytes = L.tab_end;
 
     std::lock_guard<std::mutex> lock(g_stage.mu);
     hipError_t e;
@@ -148,10 +154,11 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
     if ((e = stage_acquire(tab_bytes, &h)) != hipSuccess) return e;
     std::memset(h, 0, tab_bytes);
     DevJob *dj = reinterpret_cast<DevJob *>(h + L.tab_jobs);
-    int *blk0 = reinterpret_cast<int *>(h + L.tab_blk0);
+    int *blk_job = reinterpret_cast<int *>(h + L.tab_map);
+    std::vector<int> blk0(A + 1, 0);
     int *cblk0 = reinterpret_cast<int *>(h + L.tab_cblk0);
     int max_cls = 0;
-    blk0[0] = 0; cblk0[0] = 0;
+    cblk0[0] = 0;
     for (int a = 0; a < A; ++a) {
         const int j = order[a];
         const glm_job_t &src = jobs[j];
@@ -165,6 +172,8 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
         d.N = src.N; d.invN = 1.0 / (double)src.N; d.D = src.D; d.loss = src.loss;
         d.lambda = src.lambda; d.step = src.step; d.P = s.P; d.cls = s.cls; d.iters = iters[j];
         max_cls = std::max(max_cls, s.cls);
+        d.blk0 = blk0[a];
+        for (int b = 0; b < s.P; ++b) blk_job[blk0[a] + b] = a;
         blk0[a + 1] = blk0[a] + s.P;
         cblk0[a + 1] = cblk0[a] + (src.D + kFinCols - 1) / kFinCols;
     }
@@ -172,14 +181,14 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
     if ((e = stage_mark(st)) != hipSuccess) return e;
 
     const DevJob *d_jobs = reinterpret_cast<const DevJob *>(base + L.tab_jobs);
-    const int *d_blk0 = reinterpret_cast<const int *>(base + L.tab_blk0);
+    const int *d_map = reinterpret_cast<const int *>(base + L.tab_map);
     const int *d_cblk0 = reinterpret_cast<const int *>(base + L.tab_cblk0);
     int nact = A;
     for (int r = 0; r < R; ++r) {
         while (nact > 0 && iters[order[nact - 1]] <= r) --nact;
         const bool prof = g_prof.on && g_prof.used < g_prof.cap;
         if (prof && (e = hipEventRecord(g_prof.ev[2 * g_prof.used], st)) != hipSuccess) return e;
-        if ((e = launch_row_pass(d_jobs, d_blk0, nact, blk0[nact], max_cls, st)) != hipSuccess) return e;
+        if ((e = launch_row_pass(d_jobs, d_map, blk0[nact], max_cls, st)) != hipSuccess) return e;
         if (prof) {
             if ((e = hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st)) != hipSuccess) return e;
             ++g_prof.used;

@@ -29,25 +29,26 @@ struct DevJob {
     int          P;          // row blocks; a function of (N, D) only
     int          cls;        // lane-layout class; a function of D only
     int          iters;      // rounds this job takes part in during this call
-    int          pad;
+    int          blk0;       // first row block of this job in the packed grid of the call
 };
 
 // Lane-layout classes of the row pass.  A row of D floats is D/4 float4 slots; a wave of 64
 // lanes covers it with LPR lanes per row (64/LPR rows side by side) and C slots per lane.
 constexpr int kNumClasses = 9;
 struct ClassInfo { int lpr; int c; int b; int pmax; };
-// b = wave-loads in flight per loop trip; pmax = cap on row blocks per job.
+// b = wave-loads in flight per loop trip; pmax = cap on row blocks per job (two blocks per
+// compute unit: measured best both for one large job and for many jobs packed in one launch).
 __host__ __device__ constexpr ClassInfo class_info(int cls) {
     constexpr ClassInfo t[kNumClasses] = {
-        {4, 1, 8, 1024},    // D <= 16
-        {8, 1, 8, 1024},    // D <= 32
-        {16, 1, 8, 1024},   // D <= 64
-        {32, 1, 8, 1024},   // D <= 128
-        {64, 1, 8, 1024},   // D <= 256
-        {64, 2, 8, 1024},   // D <= 512
-        {64, 4, 8, 2048},   // D <= 1024
-        {64, 8, 2, 1024},   // D <= 2048
-        {64, 16, 1, 1024},  // D <= 4096
+        {4, 1, 8, 512},     // D <= 16
+        {8, 1, 8, 512},     // D <= 32
+        {16, 1, 8, 512},    // D <= 64
+        {32, 1, 8, 512},    // D <= 128
+        {64, 1, 8, 512},    // D <= 256
+        {64, 2, 8, 512},    // D <= 512
+        {64, 4, 8, 1024},   // D <= 1024
+        {64, 8, 2, 512},    // D <= 2048
+        {64, 16, 1, 512},   // D <= 4096
     };
     return t[cls];
 }
@@ -59,7 +60,7 @@ constexpr int kFinCols = 16;            // columns per finalize block
 constexpr int kFinSegs = 64;            // row-block segments summed side by side per column
 
 // Launchers (glm_rows.hip).  `tab_*` are device pointers into the workspace.
-hipError_t launch_row_pass(const DevJob *jobs, const int *blk0, int nact, int total_blocks,
+hipError_t launch_row_pass(const DevJob *jobs, const int *blk_job, int total_blocks,
                            int max_cls, hipStream_t st);
 hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int total_blocks,
                            int round, hipStream_t st);

@@ -314,14 +314,13 @@ __device__ __forceinline__ int find_segment(const int *__restrict__ tab, int n, 
 
 template <int MAXCLS>
 __global__ __launch_bounds__(kRowBlockThreads) void row_pass_kernel(
-    const DevJob *__restrict__ jobs, const int *__restrict__ blk0, int nact) {
+    const DevJob *__restrict__ jobs, const int *__restrict__ blk_job) {
     constexpr int CMAX = class_info(MAXCLS).c;
     __shared__ float4 gred4[4 * 64 * CMAX];
     __shared__ float lred[256];
     float *gred = reinterpret_cast<float *>(gred4);
-    const int a = find_segment(blk0, nact, blockIdx.x);
-    const DevJob &jb = jobs[a];
-    const int vb = blockIdx.x - blk0[a];
+    const DevJob &jb = jobs[blk_job[blockIdx.x]];      // block -> job: one table entry per block
+    const int vb = blockIdx.x - jb.blk0;
     switch (jb.cls) {
 #define SLAQ_CASE(K)                                                                          \
     case K:                                                                                   \
@@ -336,15 +335,15 @@ __global__ __launch_bounds__(kRowBlockThreads) void row_pass_kernel(
     }
 }
 
-hipError_t launch_row_pass(const DevJob *jobs, const int *blk0, int nact, int total_blocks,
+hipError_t launch_row_pass(const DevJob *jobs, const int *blk_job, int total_blocks,
                            int max_cls, hipStream_t st) {
     if (total_blocks <= 0) return hipSuccess;
     dim3 grid((unsigned)total_blocks), block(kRowBlockThreads);
-    if (max_cls <= 4) hipLaunchKernelGGL(row_pass_kernel<4>, grid, block, 0, st, jobs, blk0, nact);
-    else if (max_cls == 5) hipLaunchKernelGGL(row_pass_kernel<5>, grid, block, 0, st, jobs, blk0, nact);
-    else if (max_cls == 6) hipLaunchKernelGGL(row_pass_kernel<6>, grid, block, 0, st, jobs, blk0, nact);
-    else if (max_cls == 7) hipLaunchKernelGGL(row_pass_kernel<7>, grid, block, 0, st, jobs, blk0, nact);
-    else hipLaunchKernelGGL(row_pass_kernel<8>, grid, block, 0, st, jobs, blk0, nact);
+    if (max_cls <= 4) hipLaunchKernelGGL(row_pass_kernel<4>, grid, block, 0, st, jobs, blk_job);
+    else if (max_cls == 5) hipLaunchKernelGGL(row_pass_kernel<5>, grid, block, 0, st, jobs, blk_job);
+    else if (max_cls == 6) hipLaunchKernelGGL(row_pass_kernel<6>, grid, block, 0, st, jobs, blk_job);
+    else if (max_cls == 7) hipLaunchKernelGGL(row_pass_kernel<7>, grid, block, 0, st, jobs, blk_job);
+    else hipLaunchKernelGGL(row_pass_kernel<8>, grid, block, 0, st, jobs, blk_job);
     return hipGetLastError();
 }
 
