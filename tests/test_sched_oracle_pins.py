@@ -1,0 +1,127 @@
+"""CPU pins for the scheduler-side oracle (loss normaliser, convergence-curve predictor, greedy
+allocator; Sec. 2 of the paper).  The paper prints no worked example, so the pins are exact
+curves, hand-computed values, invariances and brute force."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import sched_oracle as so
+
+
+def test_normalized_changes_hand_example():
+    # changes 3, 1, 0.5, then a larger one 4 (the normaliser follows the running maximum), then -1
+    nu, norm = so.normalized_changes([10.0, 7.0, 6.0, 5.5, 1.5, 2.5])
+    np.testing.assert_allclose(nu, [1.0, 1 / 3, 0.5 / 3, 1.0, -0.25], rtol=1e-15)
+    assert norm == 4.0
+    nu, norm = so.normalized_changes([2.0, 2.0, 2.0])
+    assert np.all(nu == 0) and norm == 0.0
+
+
+def test_first_normalized_change_is_one_and_values_stay_in_unit_interval():
+    rng = np.random.default_rng(0)
+    L = np.cumsum(-rng.random(50)) + 100
+    nu, _ = so.normalized_changes(L)
+    assert nu[0] == 1.0 and np.all(np.abs(nu) <= 1.0)
+
+
+@pytest.mark.parametrize("a,b,c,d", [(0.002, 0.05, 1.2, 0.3), (0.0, 0.08, 0.5, 2.0), (0.01, 0.0, 2.0, 0.05)])
+def test_exact_sublinear_curve_is_extrapolated(a, b, c, d):
+    k = np.arange(60, dtype=np.float64)
+    f = 1.0 / (a * k * k + b * k + c) + d
+    n = 40
+    pred, gain, fit = so.predict_job(f[:n], so.CLASS_SUBLINEAR, gamma=0.9, window=128, horizon=20)
+    assert fit["ok"]
+    span = f[:n].max() - f[:n].min()
+    assert np.max(np.abs(pred - f[n:n + 20])) <= 2e-3 * span
+    # predicted reductions telescope to the predicted total drop, in units of the largest change
+    _, norm = so.normalized_changes(f[:n])
+    assert np.sum(gain) == pytest.approx((so.fitted_value_at_last(fit) - pred[-1]) / norm, rel=1e-12)
+    assert np.all(gain > 0) and np.all(np.diff(gain) < 0)          # diminishing returns (Sec. 1)
+
+
+def test_exact_geometric_curve_is_extrapolated():
+    k = np.arange(50, dtype=np.float64)
+    f = 3.0 * 0.8 ** k + 0.25
+    pred, gain, fit = so.predict_job(f[:25], so.CLASS_LINEAR, gamma=0.9, horizon=15)
+    assert fit["ok"]
+    assert np.max(np.abs(pred - f[25:40])) <= 2e-3 * (f[:25].max() - f[:25].min())
+
+
+def test_prediction_commutes_with_affine_maps_of_the_loss():
+    k = np.arange(30, dtype=np.float64)
+    rng = np.random.default_rng(1)
+    L = 1.0 / (0.01 * k * k + 0.1 * k + 1.0) + 0.2 + 1e-4 * rng.standard_normal(30)
+    p1, g1, _ = so.predict_job(L, horizon=10)
+    p2, g2, _ = so.predict_job(5.0 * L + 17.0, horizon=10)
+    np.testing.assert_allclose(p2, 5.0 * p1 + 17.0, rtol=1e-9)
+    np.testing.assert_allclose(g2, g1, rtol=1e-6)                   # normalised reductions have no unit
+
+
+@pytest.mark.parametrize("loss,eta,cls", [(oracle.LOGISTIC, 0.5, so.CLASS_SUBLINEAR),
+                                          (oracle.SQUARED, 0.1, so.CLASS_LINEAR)])
+def test_tenth_next_iteration_of_gradient_descent_within_five_percent(loss, eta, cls):
+    # Sec. 2 reports under 5 % error when predicting the 10th next iteration.  The histories come
+    # from the GLM oracle: gradient descent on the logistic loss converges sublinearly (class I);
+    # on a strongly convex least-squares problem it converges linearly (class II).
+    rng = np.random.default_rng(3)
+    N, D = 2000, 40
+    X = rng.standard_normal((N, D)).astype(np.float32)
+    m = X.astype(np.float64) @ (rng.standard_normal(D) / np.sqrt(D)) + 0.3 * rng.standard_normal(N)
+    y = (m.astype(np.float32) if loss == oracle.SQUARED else (m > 0).astype(np.float32))
+    lh, _, _, _ = oracle.run(loss, X, y, np.zeros(D), 1e-3, eta, 70)
+    for n in (15, 25, 40, 60):
+        pred, _, fit = so.predict_job(lh[:n], cls, horizon=10)
+        assert fit["ok"]
+        assert abs(pred[9] - lh[n + 9]) <= 0.05 * lh[n + 9], (n, pred[9], lh[n + 9])
+
+
+def test_short_or_flat_histories_predict_the_last_loss():
+    p, g, fit = so.predict_job([3.0, 2.0, 1.5], horizon=4)
+    assert not fit["ok"] and np.all(p == 1.5) and np.all(g == 0)
+    p, g, fit = so.predict_job([2.0] * 10, horizon=4)
+    assert not fit["ok"] and np.all(p == 2.0) and np.all(g == 0)
+
+
+def test_only_the_window_is_used_and_recent_points_weigh_more():
+    k = np.arange(200, dtype=np.float64)
+    f = 1.0 / (0.001 * k * k + 0.05 * k + 1.0) + 0.1
+    junk = np.concatenate([np.full(100, 50.0), f[100:160]])
+    a, _, _ = so.predict_job(junk, window=60, horizon=5)
+    b, _, _ = so.predict_job(f[100:160], window=60, horizon=5)
+    np.testing.assert_array_equal(a, b)
+    # one early outlier moves the prediction less than the same outlier at the end
+    base, _, _ = so.predict_job(f[:40], horizon=5)
+    early = f[:40].copy(); early[2] *= 1.05
+    late = f[:40].copy(); late[37] *= 1.05
+    pe, _, _ = so.predict_job(early, horizon=5)
+    pl, _, _ = so.predict_job(late, horizon=5)
+    assert np.max(np.abs(pe - base)) < np.max(np.abs(pl - base))
+
+
+def test_greedy_hand_example():
+    gain = np.array([[9.0, 5.0, 1.0], [8.0, 7.0, 6.0], [2.0, 1.0, 0.5]])
+    # start 1,1,1; extra units go to the largest next gains: job 1 (7), job 1 (6), job 0 (5)
+    np.testing.assert_array_equal(so.greedy_allocate(gain, 3), [1, 1, 1])
+    np.testing.assert_array_equal(so.greedy_allocate(gain, 4), [1, 2, 1])
+    np.testing.assert_array_equal(so.greedy_allocate(gain, 6), [2, 3, 1])
+    np.testing.assert_array_equal(so.greedy_allocate(gain, 100), [3, 3, 3])       # capped at H
+    with pytest.raises(ValueError):
+        so.greedy_allocate(gain, 2)
+    tie = np.array([[1.0, 0.5], [1.0, 0.5]])
+    np.testing.assert_array_equal(so.greedy_allocate(tie, 3), [2, 1])             # lowest index wins
+
+
+def test_greedy_is_optimal_for_diminishing_gains_by_brute_force():
+    rng = np.random.default_rng(7)
+    for _ in range(20):
+        J, H = 4, 5
+        gain = -np.sort(-rng.random((J, H)), axis=1)          # decreasing along h
+        C = int(rng.integers(J, J * H + 1))
+        a = so.greedy_allocate(gain, C)
+        assert a.sum() == C and a.min() >= 1
+        total = sum(gain[j, :a[j]].sum() for j in range(J))
+        best = max(sum(gain[j, :alloc[j]].sum() for j in range(J))
+                   for alloc in itertools.product(range(1, H + 1), repeat=J) if sum(alloc) == C)
+        assert total == pytest.approx(best, rel=1e-12)
