@@ -123,6 +123,44 @@ int glm_sweep(const float *X /*DEVICE*/, const float *y /*DEVICE*/, int64_t N, i
               const float *lambdas /*HOST*/, const float *steps /*HOST*/, int32_t iters,
               float *loss_hist /*DEVICE*/, void *ws /*DEVICE*/, size_t ws_bytes, void *hip_stream);
 
+/* ---- Scheduler-side steps that consume the loss histories (Sec. 2) ---------------------- */
+
+/* Convergence classes of Sec. 2 "Predicting Quality Improvement": class I, sublinear
+ * (first-order methods such as gradient descent), f(k) = 1/(a k^2 + b k + c) + d; class II,
+ * linear or superlinear, f(k) = mu^(k-b) + c. */
+typedef enum { GLM_CURVE_SUBLINEAR = 1, GLM_CURVE_LINEAR = 2 } glm_curve_t;
+
+/* For each of J jobs: normalise the loss changes by the largest change seen so far (Sec. 2,
+ * "Normalizing Quality Metrics"), fit the job's convergence curve to its exponentially weighted
+ * loss history and evaluate it at the next `horizon` iterations (Sec. 2, "Predicting Quality
+ * Improvement").  Of each job only loss_hist (DEVICE) and hist_len are read.
+ *   curve   HOST [J] glm_curve_t per job
+ *   gamma   weight decay per iteration, 0 < gamma <= 1: history point i of n weighs gamma^(n-1-i)
+ *   window  most recent losses used for the fit, 4 <= window <= 128
+ *   pred    DEVICE [J, horizon] fp64: predicted loss after h = 1..horizon further iterations
+ *   gain    DEVICE [J, horizon] fp64: predicted reduction contributed by the h-th further
+ *           iteration, divided by the largest single-iteration change in the job's history
+ *   fit     DEVICE [J, 8] fp64: {fitted (1/0), offset d or c, p0, p1, p2, weighted squared error,
+ *           largest change, points used}; the linear parameters refer to time scaled to
+ *           t = i/(m-1) over the m points used.  A job with fewer than 4 losses, a flat history
+ *           or no admissible fit gets fitted = 0, pred = its last loss, gain = 0.
+ *   ws      DEVICE workspace of glm_predict_workspace_bytes(J) bytes, 256-byte aligned
+ * Every job needs hist_len >= 1.  Errors: GLM_EINVAL, GLM_ENOSPC (workspace), GLM_EHIP. */
+int glm_predict_batched(const glm_job_t *jobs /*HOST [J]*/, int32_t J, const int32_t *curve /*HOST*/,
+                        double gamma, int32_t window, int32_t horizon, double *pred /*DEVICE*/,
+                        double *gain /*DEVICE*/, double *fit /*DEVICE*/, void *ws /*DEVICE*/,
+                        size_t ws_bytes, void *hip_stream);
+int glm_predict_workspace_bytes(int32_t J, size_t *out_bytes /*HOST*/);
+
+/* The greedy allocation of Sec. 2 "Scheduling Based on Quality Improvements": every job starts
+ * with one unit; one unit at a time goes to the job whose next unit has the largest predicted
+ * reduction (lowest job index on ties) until `capacity` units are handed out or every job holds
+ * H units.  gain is HOST [J, H] (entry [j, h-1] = reduction of job j's h-th unit, as written by
+ * glm_predict_batched and copied to the host), alloc HOST [J] out.  Runs on the host.
+ * Errors: GLM_EINVAL (null pointer, J < 1, H < 1, capacity < J, a gain that is not finite). */
+int glm_allocate_greedy(const double *gain /*HOST*/, int32_t J, int32_t H, int64_t capacity,
+                        int32_t *alloc /*HOST*/);
+
 /* Measurement aid: reads n floats of DEVICE memory once with the same 128-bit
  * access pattern as the training kernels and writes one float per block to
  * `sink` (DEVICE, at least glm_read_probe_sink_floats() floats), so a caller

@@ -318,6 +318,55 @@ int glm_sweep(const float *X, const float *y, int64_t N, int32_t D, int32_t M, i
     return GLM_OK;
 }
 
+int glm_predict_workspace_bytes(int32_t J, size_t *out_bytes) {
+    if (J < 1 || !out_bytes) return GLM_EINVAL;
+    *out_bytes = align_up(sizeof(PredJob) * (size_t)J);
+    return GLM_OK;
+}
+
+int glm_predict_batched(const glm_job_t *jobs, int32_t J, const int32_t *curve, double gamma,
+                        int32_t window, int32_t horizon, double *pred, double *gain, double *fit,
+                        void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!jobs || !curve || !pred || !gain || !fit || J < 1) return GLM_EINVAL;
+    if (!(gamma > 0.0) || !(gamma <= 1.0)) return GLM_EINVAL;
+    if (window < 4 || window > kPredWindowMax || horizon < 1 || horizon > kPredHorizonMax) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(pred) & 7u) || (reinterpret_cast<uintptr_t>(gain) & 7u) ||
+        (reinterpret_cast<uintptr_t>(fit) & 7u))
+        return GLM_EINVAL;
+    for (int j = 0; j < J; ++j) {
+        if (!jobs[j].loss_hist || (reinterpret_cast<uintptr_t>(jobs[j].loss_hist) & 3u)) return GLM_EINVAL;
+        if (jobs[j].hist_len < 1) return GLM_EINVAL;
+        if (curve[j] != GLM_CURVE_SUBLINEAR && curve[j] != GLM_CURVE_LINEAR) return GLM_EINVAL;
+    }
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    const size_t need = align_up(sizeof(PredJob) * (size_t)J);
+    if (ws_bytes < need) return GLM_ENOSPC;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    {
+        std::lock_guard<std::mutex> lock(g_stage.mu);
+        char *h = nullptr;
+        if (stage_acquire(need, &h) != hipSuccess) return GLM_EHIP;
+        PredJob *pj = reinterpret_cast<PredJob *>(h);
+        for (int j = 0; j < J; ++j) {
+            pj[j].hist = jobs[j].loss_hist; pj[j].n = jobs[j].hist_len; pj[j].cls = curve[j]; pj[j].pad = 0;
+        }
+        if (hipMemcpyAsync(ws, h, sizeof(PredJob) * (size_t)J, hipMemcpyHostToDevice, st) != hipSuccess)
+            return GLM_EHIP;
+        if (stage_mark(st) != hipSuccess) return GLM_EHIP;
+    }
+    if (launch_predict(static_cast<const PredJob *>(ws), J, gamma, window, horizon, pred, gain, fit, st) !=
+        hipSuccess)
+        return GLM_EHIP;
+    return GLM_OK;
+}
+
+int glm_allocate_greedy(const double *gain, int32_t J, int32_t H, int64_t capacity, int32_t *alloc) {
+    if (!gain || !alloc || J < 1 || H < 1 || capacity < J) return GLM_EINVAL;
+    for (size_t i = 0; i < (size_t)J * H; ++i)
+        if (!std::isfinite(gain[i])) return GLM_EINVAL;
+    return allocate_greedy(gain, J, H, capacity, alloc);
+}
+
 int glm_read_probe(const float *src, size_t n, float *sink, void *hip_stream) {
     if (!src || !sink || n == 0 || (n & 3) != 0 || !aligned16(src)) return GLM_EINVAL;
     return launch_read_probe(src, n, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess

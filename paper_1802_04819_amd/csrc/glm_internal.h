@@ -85,4 +85,18 @@ struct SweepArgs {
 // four events recorded around the forward and around the backward kernel.
 hipError_t launch_sweep_iteration(const SweepArgs &a, int k, hipEvent_t *ev, hipStream_t st);
 
+
+// Scheduler-side steps (glm_sched.hip).
+constexpr int kPredWindowMax = 128;     // most recent losses a fit may use
+constexpr int kPredHorizonMax = 4096;   // future iterations a call may predict
+struct PredJob {
+    const float *hist;      // device: the job's loss history
+    long long    n;         // entries in it
+    int          cls;       // glm_curve_t
+    int          pad;
+};
+hipError_t launch_predict(const PredJob *jobs, int J, double gamma, int window, int horizon,
+                          double *pred, double *gain, double *fit, hipStream_t st);
+int allocate_greedy(const double *gain, int J, int H, long long capacity, int *alloc);
+
 }  // namespace slaqglm

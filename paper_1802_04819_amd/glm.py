@@ -22,7 +22,9 @@ GLM_OK, GLM_EINVAL, GLM_ENOSPC, GLM_EHIP, GLM_ENOTIMPL = 0, -1, -2, -3, -4
 EXPORTS = (
     "glm_workspace_bytes", "glm_step", "glm_step_batched", "glm_sweep", "glm_read_probe",
     "glm_read_probe_sink_floats", "glm_profile_begin", "glm_profile_end", "glm_strerror",
+    "glm_predict_batched", "glm_predict_workspace_bytes", "glm_allocate_greedy",
 )
+GLM_CURVE_SUBLINEAR, GLM_CURVE_LINEAR = 1, 2
 
 
 class glm_job_t(ctypes.Structure):
@@ -77,6 +79,15 @@ def load():
     lib.glm_profile_begin.argtypes = [ctypes.c_int32]
     lib.glm_profile_end.restype = ctypes.c_int
     lib.glm_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
+    dbl = ctypes.POINTER(ctypes.c_double)
+    i32 = ctypes.POINTER(ctypes.c_int32)
+    lib.glm_predict_batched.restype = ctypes.c_int
+    lib.glm_predict_batched.argtypes = [jp, ctypes.c_int32, i32, ctypes.c_double, ctypes.c_int32,
+                                        ctypes.c_int32, vp, vp, vp, vp, sz, vp]
+    lib.glm_predict_workspace_bytes.restype = ctypes.c_int
+    lib.glm_predict_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.glm_allocate_greedy.restype = ctypes.c_int
+    lib.glm_allocate_greedy.argtypes = [dbl, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, i32]
     lib.glm_strerror.restype = ctypes.c_char_p
     lib.glm_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -210,6 +221,41 @@ def glm_sweep(X: torch.Tensor, y: torch.Tensor, loss: int, W: torch.Tensor, G: t
                           ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size(),
                           _stream_handle(stream))
     _check(rc, "glm_sweep")
+
+
+def glm_predict_batched(jobs: Sequence[Job], curve, gamma: float, window: int, horizon: int,
+                        pred: torch.Tensor, gain: torch.Tensor, fit: torch.Tensor,
+                        ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """pred, gain: float64 device tensors [J, horizon]; fit: float64 device tensor [J, 8]."""
+    _require_gpu()
+    J = len(jobs)
+    cv = np.ascontiguousarray(np.broadcast_to(np.asarray(curve, dtype=np.int32), (J,)))
+    for t, shape in ((pred, (J, horizon)), (gain, (J, horizon)), (fit, (J, 8))):
+        if t.dtype != torch.float64 or tuple(t.shape) != shape or not t.is_contiguous():
+            raise TypeError("pred/gain/fit must be contiguous float64 tensors of shape [J, horizon] / [J, 8]")
+    if ws is None:
+        need = ctypes.c_size_t(0)
+        _check(load().glm_predict_workspace_bytes(J, ctypes.byref(need)), "glm_predict_workspace_bytes")
+        ws = torch.empty(max(int(need.value), 256), dtype=torch.uint8, device=pred.device)
+    arr = _as_array(jobs)
+    rc = load().glm_predict_batched(arr, J, cv.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), float(gamma),
+                                    int(window), int(horizon), ctypes.c_void_p(pred.data_ptr()),
+                                    ctypes.c_void_p(gain.data_ptr()), ctypes.c_void_p(fit.data_ptr()),
+                                    ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream_handle(stream))
+    _check(rc, "glm_predict_batched")
+
+
+def glm_allocate_greedy(gain, capacity: int) -> np.ndarray:
+    """gain: host array [J, H] (float64).  Returns the int32 allocation vector [J]."""
+    g = np.ascontiguousarray(np.asarray(gain, dtype=np.float64))
+    if g.ndim != 2:
+        raise ValueError("gain must be [J, H]")
+    J, H = g.shape
+    alloc = np.zeros(J, dtype=np.int32)
+    rc = load().glm_allocate_greedy(g.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), J, H, int(capacity),
+                                    alloc.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "glm_allocate_greedy")
+    return alloc
 
 
 def glm_read_probe(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:

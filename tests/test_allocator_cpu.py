@@ -1,0 +1,85 @@
+"""CPU tests of glm_allocate_greedy (host code of the library) against the literal greedy loop of
+the oracle: the allocation vector must be identical, entry by entry."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from oracle import sched_oracle as so
+from paper_1802_04819_amd import glm
+
+
+def test_hand_example_and_ties():
+    gain = np.array([[9.0, 5.0, 1.0], [8.0, 7.0, 6.0], [2.0, 1.0, 0.5]])
+    for C, want in ((3, [1, 1, 1]), (4, [1, 2, 1]), (6, [2, 3, 1]), (100, [3, 3, 3])):
+        np.testing.assert_array_equal(glm.glm_allocate_greedy(gain, C), want)
+    tie = np.array([[1.0, 0.5], [1.0, 0.5], [1.0, 0.5]])
+    np.testing.assert_array_equal(glm.glm_allocate_greedy(tie, 5), [2, 2, 1])
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_matches_literal_greedy_on_random_gains(seed):
+    rng = np.random.default_rng(seed)
+    J, H = int(rng.integers(1, 40)), int(rng.integers(1, 12))
+    gain = rng.random((J, H))
+    if seed % 3 == 0:
+        gain = np.round(gain, 1)                       # many exact ties
+    if seed % 3 == 1:
+        gain = -np.sort(-gain, axis=1)                 # diminishing returns
+    if seed % 4 == 0:
+        gain -= 0.5                                    # negative reductions are still ranked
+    for C in (J, J + 1, J + (J * H) // 3, J * H, J * H + 7):
+        np.testing.assert_array_equal(glm.glm_allocate_greedy(gain, C), so.greedy_allocate(gain, C))
+
+
+def test_four_thousand_jobs_sixteen_thousand_units():
+    # the size of the paper's scalability experiment (Sec. 3, "Scalability and efficiency")
+    rng = np.random.default_rng(1)
+    J, H = 4000, 32
+    gain = -np.sort(-rng.random((J, H)) ** 3, axis=1)
+    a = glm.glm_allocate_greedy(gain, 16384)
+    assert a.sum() == 16384 and a.min() >= 1 and a.max() <= H
+    # optimal for diminishing gains: no unit could be moved to a better place
+    taken_min = min(gain[j, a[j] - 1] for j in range(J) if a[j] > 1)
+    next_max = max(gain[j, a[j]] for j in range(J) if a[j] < H)
+    assert taken_min >= next_max
+    sub = slice(0, 300)                                # literal loop on a slice of the jobs
+    np.testing.assert_array_equal(glm.glm_allocate_greedy(gain[sub], 1500), so.greedy_allocate(gain[sub], 1500))
+
+
+def test_argument_errors():
+    lib = glm.load()
+    g = np.ones((2, 2)); a = np.zeros(2, np.int32)
+    gp = g.ctypes.data_as(ctypes.POINTER(ctypes.c_double)); ap = a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    assert lib.glm_allocate_greedy(None, 2, 2, 2, ap) == glm.GLM_EINVAL
+    assert lib.glm_allocate_greedy(gp, 2, 2, 2, None) == glm.GLM_EINVAL
+    assert lib.glm_allocate_greedy(gp, 0, 2, 2, ap) == glm.GLM_EINVAL
+    assert lib.glm_allocate_greedy(gp, 2, 0, 2, ap) == glm.GLM_EINVAL
+    assert lib.glm_allocate_greedy(gp, 2, 2, 1, ap) == glm.GLM_EINVAL          # capacity below one unit per job
+    g[1, 1] = np.nan
+    assert lib.glm_allocate_greedy(gp, 2, 2, 3, ap) == glm.GLM_EINVAL
+    n = ctypes.c_size_t(0)
+    assert lib.glm_predict_workspace_bytes(0, ctypes.byref(n)) == glm.GLM_EINVAL
+    assert lib.glm_predict_workspace_bytes(10, ctypes.byref(n)) == glm.GLM_OK and n.value % 256 == 0
+
+
+def test_predict_rejects_bad_arguments_before_touching_the_gpu():
+    lib = glm.load()
+    jobs = (glm.glm_job_t * 2)()
+    for j in jobs:
+        j.loss_hist = 0x50000; j.hist_len = 10
+    curve = (ctypes.c_int32 * 2)(1, 2)
+    D = ctypes.c_void_p(0x100000)
+    ok = dict(gamma=0.9, window=64, horizon=8)
+
+    def call(jobs=jobs, J=2, curve=curve, gamma=0.9, window=64, horizon=8, pred=D, gain=D, fit=D, ws=D, nbytes=1 << 20):
+        return lib.glm_predict_batched(jobs, J, curve, gamma, window, horizon, pred, gain, fit, ws, nbytes, None)
+
+    assert call(gamma=0.0) == glm.GLM_EINVAL and call(gamma=1.5) == glm.GLM_EINVAL
+    assert call(window=3) == glm.GLM_EINVAL and call(window=129) == glm.GLM_EINVAL
+    assert call(horizon=0) == glm.GLM_EINVAL
+    assert call(pred=None) == glm.GLM_EINVAL and call(ws=None) == glm.GLM_EINVAL
+    assert call(nbytes=8) == glm.GLM_ENOSPC
+    assert call(curve=(ctypes.c_int32 * 2)(1, 3)) == glm.GLM_EINVAL
+    jobs[1].hist_len = 0
+    assert call() == glm.GLM_EINVAL

@@ -1,0 +1,175 @@
+"""GPU tests of glm_predict_batched against the fp64 scheduler oracle, and of the closed loop
+train -> predict -> allocate."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import sched_oracle as so
+from paper_1802_04819_amd import glm, synth
+
+pytestmark = pytest.mark.gpu
+
+# Both sides work in fp64 on the same fp32 history; they differ in summation order and in the
+# 3x3 solver.  The weighted normal equations of a quadratic on [0, 1] have condition numbers up to
+# ~1e8 (few points, strong decay), so the fitted parameters agree to ~1e-8 relative and
+# predictions are compared to 1e-6 of the history's span.  The winning candidate is an argmin over 64 values: when two
+# candidates tie to rounding either is a correct answer, and the test then checks that the
+# library's choice is as good as the oracle's (same weighted error to 1e-9) and consistent.
+PRED_TOL = 1e-6
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+class _Hist:
+    """Minimal stand-in for a Job: only loss_hist and hist_len are read by the predictor."""
+    def __init__(self, values, device="cuda"):
+        self.t = torch.tensor(np.asarray(values, dtype=np.float32), device=device)
+        self.c = glm.glm_job_t()
+        self.c.loss_hist = self.t.data_ptr()
+        self.c.hist_len = len(values)
+
+
+def _predict(hists, curve, gamma, window, horizon):
+    J = len(hists)
+    pred = torch.zeros(J, horizon, dtype=torch.float64, device="cuda")
+    gain = torch.zeros_like(pred)
+    fit = torch.zeros(J, 8, dtype=torch.float64, device="cuda")
+    glm.glm_predict_batched(hists, curve, gamma, window, horizon, pred, gain, fit)
+    torch.cuda.synchronize()
+    return pred.cpu().numpy(), gain.cpu().numpy(), fit.cpu().numpy()
+
+
+def _check_against_oracle(values32, cls, gamma, window, horizon, pred, gain, fit, tag):
+    L = np.asarray(values32, dtype=np.float32).astype(np.float64)
+    p_o, g_o, f_o = so.predict_job(L, cls, gamma, window, horizon)
+    _, norm = so.normalized_changes(L) if len(L) >= 2 else (None, 0.0)
+    assert fit[6] == pytest.approx(norm, rel=1e-15, abs=0), tag
+    assert bool(fit[0]) == f_o["ok"], tag
+    if not f_o["ok"]:
+        assert np.all(pred == f_o["last"]) and np.all(gain == 0), tag
+        return
+    Lw = L[-window:]
+    span = Lw.max() - Lw.min()
+    if np.max(np.abs(pred - p_o)) > PRED_TOL * span:
+        # a different candidate won: it must be as good as the oracle's under the oracle's arithmetic
+        m = len(Lw)
+        t = np.arange(m) / (m - 1)
+        w = gamma ** np.arange(m - 1, -1, -1, dtype=np.float64)
+        p_alt, sse_alt = so._fit_for_offset(cls, t, Lw, w, fit[1])
+        assert sse_alt <= f_o["sse"] * (1 + 1e-9) + 1e-300, (tag, sse_alt, f_o["sse"])
+        alt = dict(f_o); alt.update(off=fit[1], p=p_alt)
+        p_o = so.predict(alt, horizon)
+        prev = np.concatenate([[so.fitted_value_at_last(alt)], p_o[:-1]])
+        g_o = (prev - p_o) / norm
+    assert np.max(np.abs(pred - p_o)) <= PRED_TOL * span, (tag, pred, p_o)
+    assert np.max(np.abs(gain - g_o)) <= PRED_TOL * span / norm + 1e-12, (tag, gain, g_o)
+
+
+def _curves():
+    k = np.arange(200, dtype=np.float64)
+    rng = np.random.default_rng(0)
+    out = []
+    out.append(("exact sublinear", 1, 1.0 / (0.002 * k * k + 0.05 * k + 1.2) + 0.3))
+    out.append(("noisy sublinear", 1, 1.0 / (0.01 * k + 0.5) + 2.0 + 1e-3 * rng.standard_normal(200)))
+    out.append(("exact geometric", 2, 3.0 * 0.9 ** k + 0.25))
+    out.append(("noisy geometric", 2, 5.0 * 0.95 ** k + 1.0 + 1e-3 * rng.standard_normal(200)))
+    out.append(("geometric fitted as sublinear", 1, 3.0 * 0.9 ** k + 0.25))
+    out.append(("increasing", 1, 1.0 + 0.01 * k))
+    out.append(("large offset", 1, 1e4 + 1.0 / (0.1 * k + 1.0)))
+    out.append(("tiny scale", 2, 1e-6 * 0.8 ** k + 1e-7))
+    return out
+
+
+@pytest.mark.parametrize("n", [4, 5, 17, 64, 128, 200])
+def test_predictions_match_oracle_on_synthetic_curves(n):
+    _say(f"[case] predictor parity, history length {n}")
+    curves = _curves()
+    hists = [_Hist(c[2][:n]) for c in curves]
+    cls = [c[1] for c in curves]
+    for gamma, window, horizon in ((0.9, 128, 16), (1.0, 32, 5), (0.7, 128, 64)):
+        pred, gain, fit = _predict(hists, cls, gamma, window, horizon)
+        for j, (name, c, vals) in enumerate(curves):
+            _check_against_oracle(vals[:n].astype(np.float32), c, gamma, window, horizon,
+                                  pred[j], gain[j], fit[j], f"{name} n={n} gamma={gamma}")
+
+
+def test_degenerate_histories():
+    _say("[case] predictor: short, flat and single-entry histories")
+    vals = [[3.0], [3.0, 2.0], [3.0, 2.0, 1.5], [2.0] * 10, [1.0, 1.0, 1.0, 0.5]]
+    hists = [_Hist(v) for v in vals]
+    pred, gain, fit = _predict(hists, 1, 0.9, 128, 4)
+    for j, v in enumerate(vals):
+        _check_against_oracle(np.float32(v), 1, 0.9, 128, 4, pred[j], gain[j], fit[j], f"degenerate {j}")
+    assert np.all(fit[:4, 0] == 0) and np.all(pred[3] == 2.0)
+
+
+def test_predictor_on_histories_written_by_glm_step_batched():
+    _say("[case] predictor on real GPU loss histories: parity and the error at +10 iterations")
+    specs = synth.config3_specs(J=24, scale=0.02)
+    probs = [synth.config3_job(s, device="cuda") for s in specs]
+    jobs = [glm.Job(p.X, p.y, p.w0.clone(), p.loss, p.lam, p.eta, 64) for p in probs]
+    ws = glm.alloc_workspace(jobs)
+    glm.glm_step_batched(jobs, np.full(24, 30, np.int32), ws)
+    torch.cuda.synchronize()
+    H = 12
+    pred = torch.zeros(24, H, dtype=torch.float64, device="cuda"); gain = torch.zeros_like(pred)
+    fit = torch.zeros(24, 8, dtype=torch.float64, device="cuda")
+    # gradient descent converges linearly on the strongly convex least-squares jobs (class II) and
+    # sublinearly on the others (class I)
+    curve = [glm.GLM_CURVE_LINEAR if p.loss == synth.SQUARED else glm.GLM_CURVE_SUBLINEAR for p in probs]
+    glm.glm_predict_batched(jobs, curve, 0.9, 128, H, pred, gain, fit)
+    torch.cuda.synchronize()
+    p_np, g_np, f_np = pred.cpu().numpy(), gain.cpu().numpy(), fit.cpu().numpy()
+    for j, job in enumerate(jobs):
+        _check_against_oracle(job.history().cpu().numpy(), curve[j], 0.9, 128, H, p_np[j], g_np[j], f_np[j], f"job {j}")
+    glm.glm_step_batched(jobs, np.full(24, 10, np.int32), ws)       # what actually happened next
+    torch.cuda.synchronize()
+    errs = []
+    for j, (job, p) in enumerate(zip(jobs, probs)):
+        actual = job.loss_hist[39].item()                            # loss 10 iterations after the last fitted one
+        errs.append(abs(p_np[j, 9] - actual) / actual)
+    errs = np.array(errs)
+    smooth = np.array([p.loss != synth.HINGE for p in probs])        # class I assumes a differentiable loss
+    print("prediction errors at +10:", np.round(errs, 4), flush=True)
+    # Sec. 2 reports under 5 % for the paper's own jobs; on this synthetic mix most jobs are far
+    # below that and the worst (least-squares jobs whose error decays at two rates) stay below 10 %
+    assert np.mean(errs[smooth] < 0.05) >= 0.7 and np.max(errs[smooth]) < 0.10, errs
+    assert np.median(errs) < 0.02
+
+
+def test_closed_loop_quality_driven_allocation_beats_equal_shares():
+    _say("[case] closed loop: train, predict, allocate (greedy) vs equal shares, same total work")
+    specs = synth.config3_specs(J=32, scale=0.01)
+    specs = [s for s in specs if s.loss != synth.HINGE][:16]
+    probs = [synth.config3_job(s, device="cuda") for s in specs]
+    J, E, H = len(probs), 6, 16
+    C = 4 * J                                                        # iterations per epoch in total
+
+    def run(policy):
+        jobs = [glm.Job(p.X, p.y, p.w0.clone(), p.loss, p.lam, p.eta, 64 + E * H) for p in probs]
+        # jobs "arrive" with different amounts of progress: job j has already run 4 + 6 j iterations
+        ws = glm.alloc_workspace(jobs)
+        glm.glm_step_batched(jobs, np.array([4 + (6 * j) % 40 for j in range(J)], np.int32), ws)
+        pred = torch.zeros(J, H, dtype=torch.float64, device="cuda"); gain = torch.zeros_like(pred)
+        fit = torch.zeros(J, 8, dtype=torch.float64, device="cuda")
+        for _ in range(E):
+            if policy == "greedy":
+                glm.glm_predict_batched(jobs, glm.GLM_CURVE_SUBLINEAR, 0.9, 128, H, pred, gain, fit)
+                torch.cuda.synchronize()
+                alloc = glm.glm_allocate_greedy(gain.cpu().numpy(), C)
+                assert alloc.sum() == C and alloc.min() >= 1
+            else:
+                alloc = np.full(J, C // J, np.int32)
+            glm.glm_step_batched(jobs, alloc, ws)
+        torch.cuda.synchronize()
+        # normalised loss of a job: where it stands between its first loss and the best loss any run reached
+        return [j.history().cpu().numpy() for j in jobs]
+
+    fair, greedy = run("fair"), run("greedy")
+    floor = [min(f.min(), g.min()) for f, g in zip(fair, greedy)]
+    def mean_norm(hs):
+        return float(np.mean([(h[-1] - lo) / (h[0] - lo) for h, lo in zip(hs, floor)]))
+    assert mean_norm(greedy) < mean_norm(fair), (mean_norm(greedy), mean_norm(fair))
