@@ -29,7 +29,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4])
+    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5],
+                    help="0-4: the benchmark configurations; 5: one scheduling decision (predict + "
+                         "allocate) for 4000 jobs and 16384 units")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only; the line says so)")
     ap.add_argument("--check", action="store_true", help="also compare against the oracle on the full data")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -322,6 +324,94 @@ def bench_sweep(args):
     return out
 
 
+def bench_sched(args):
+    """One scheduling decision at the size of the paper's scalability experiment (Sec. 3,
+    "Scalability and efficiency": 4,000 jobs, 16K units): curve fit and prediction for every job
+    on the GPU, copy of the predicted reductions to the host, greedy allocation on the host.
+    One step is one decision.  (The paper reports hundreds of milliseconds to a few seconds on
+    its own machine; context only.)"""
+    import numpy as np
+    import torch
+    from paper_1802_04819_amd import glm
+
+    J, H, C = 4000, 32, 16384
+    rng = np.random.default_rng(0)
+    hists = []
+
+    class Hist:
+        def __init__(self, v):
+            self.t = torch.tensor(v, dtype=torch.float32, device="cuda")
+            self.c = glm.glm_job_t(); self.c.loss_hist = self.t.data_ptr(); self.c.hist_len = len(v)
+
+    lengths = rng.integers(8, 300, size=J)
+    curve = np.where(rng.random(J) < 0.5, glm.GLM_CURVE_SUBLINEAR, glm.GLM_CURVE_LINEAR).astype(np.int32)
+    raw = []
+    for j in range(J):
+        k = np.arange(lengths[j], dtype=np.float64)
+        if curve[j] == glm.GLM_CURVE_SUBLINEAR:
+            v = 1.0 / (rng.uniform(0, 0.01) * k * k + rng.uniform(0.01, 0.3) * k + rng.uniform(0.5, 2)) + rng.uniform(0, 1)
+        else:
+            v = rng.uniform(0.5, 5) * rng.uniform(0.8, 0.99) ** k + rng.uniform(0, 1)
+        v = v * (1 + 1e-4 * rng.standard_normal(len(k)))
+        raw.append(v.astype(np.float32)); hists.append(Hist(raw[-1]))
+    pred = torch.zeros(J, H, dtype=torch.float64, device="cuda"); gain = torch.zeros_like(pred)
+    fit = torch.zeros(J, 8, dtype=torch.float64, device="cuda")
+    gain_host = torch.empty(J, H, dtype=torch.float64, pin_memory=True)
+    K = args.steps if args.steps is not None else 50
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def decide():
+        glm.glm_predict_batched(hists, curve, 0.9, 128, H, pred, gain, fit)
+        gain_host.copy_(gain, non_blocking=True)
+        torch.cuda.synchronize()
+        return glm.glm_allocate_greedy(gain_host.numpy(), C)
+
+    for _ in range(max(args.warmup, 1)):
+        alloc = decide()
+    k_ms = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        alloc = decide()
+    t1 = time.perf_counter()
+    for _ in range(10):                       # the predict kernel alone
+        ev0.record(); glm.glm_predict_batched(hists, curve, 0.9, 128, H, pred, gain, fit); ev1.record()
+        torch.cuda.synchronize(); k_ms.append(ev0.elapsed_time(ev1))
+    t2 = time.perf_counter()
+    for _ in range(10):
+        glm.glm_allocate_greedy(gain_host.numpy(), C)
+    alloc_ms = (time.perf_counter() - t2) / 10 * 1e3
+    sec = t1 - t0
+    out = {
+        "metric": "scheduling decisions/sec (curve fit + prediction for 4000 jobs on the GPU, greedy "
+                  "allocation of 16384 units on the host)",
+        "value": K / sec, "unit": "decisions/s", "n_gpus": 1, "steps": K, "warmup": max(args.warmup, 1),
+        "ms_per_step": 1e3 * sec / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "sched_4000_jobs_16384_units", "config_index": 5, "jobs": J, "horizon": H,
+                   "capacity": C, "history_lengths": "U[8,300)", "window": 128, "gamma": 0.9},
+        "roofline": {"bound": "latency", "kernel": "predict_kernel", "achieved": None, "peak": None,
+                     "unit": None, "frac": None, "traffic": None,
+                     "predict_kernel_ms": float(np.median(k_ms)), "allocate_host_ms": alloc_ms},
+        "allocation_sum": int(alloc.sum()), "allocation_max": int(alloc.max()),
+    }
+    if not args.no_cpu_baseline:
+        from oracle import sched_oracle as so
+        n_s = 100
+        t = time.perf_counter()
+        gains = [so.predict_job(raw[j].astype(np.float64), int(curve[j]), 0.9, 128, H)[1] for j in range(n_s)]
+        t_pred = time.perf_counter() - t
+        t = time.perf_counter()
+        so.greedy_allocate(np.array(gains), 4 * n_s)
+        t_greedy = time.perf_counter() - t
+        # prediction scales with J; the literal greedy loop with (C - J) * J
+        full = t_pred * J / n_s + t_greedy * ((C - J) * J) / ((3 * n_s) * n_s)
+        out["cpu_baseline"] = {"value": 1.0 / full, "unit": "decisions/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{n_s} of {J} jobs predicted ({t_pred:.2f} s) and allocated with the "
+                                         f"literal greedy loop ({t_greedy:.3f} s), scaled by J and by (C-J)*J"}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -343,8 +433,10 @@ def main():
         out = bench_single(args, args.config)
     elif args.config == 3:
         out = bench_batched(args)
-    else:
+    elif args.config == 4:
         out = bench_sweep(args)
+    else:
+        out = bench_sched(args)
     print(json.dumps(out))
 
 
