@@ -56,6 +56,14 @@ def _load():
         lib.oracle_run.argtypes = [ctypes.c_int, fp, fp, ctypes.c_int64, ctypes.c_int32,
                                    dp, ctypes.c_double, ctypes.c_double, ctypes.c_int32,
                                    ctypes.c_int32, dp, dp, dp]
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        lib.oracle_sparse_loss_grad.restype = ctypes.c_int
+        lib.oracle_sparse_loss_grad.argtypes = [ctypes.c_int, i64p, i32p, fp, fp, ctypes.c_int64,
+                                                ctypes.c_int64, dp, ctypes.c_double, dp, dp]
+        lib.oracle_sparse_run.restype = ctypes.c_int
+        lib.oracle_sparse_run.argtypes = [ctypes.c_int, i64p, i32p, fp, fp, ctypes.c_int64, ctypes.c_int64,
+                                          dp, ctypes.c_double, ctypes.c_double, ctypes.c_int32, dp, dp, dp]
         lib.oracle_max_threads.restype = ctypes.c_int
         lib.oracle_max_threads.argtypes = []
         _lib = lib
@@ -128,6 +136,52 @@ def run(loss: int, X, y, w0, lam: float, eta: float, K: int, chunks: int = 0):
                             int(K), int(chunks), _dptr(lh), _dptr(gh), _dptr(gl))
     if rc != 0:
         raise ValueError("oracle_run rejected its arguments")
+    return lh, gh, w, gl
+
+
+def _csr(row_ptr, col_idx, val, N, D):
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    v = np.ascontiguousarray(val)
+    if v.dtype != np.float32:
+        raise TypeError("CSR values must be float32 (the bits the GPU reads)")
+    if rp.shape != (N + 1,) or rp[0] != 0 or rp[-1] != len(ci) or len(ci) != len(v) or np.any(np.diff(rp) < 0):
+        raise ValueError("inconsistent CSR arrays")
+    if len(ci) and (ci.min() < 0 or ci.max() >= D):
+        raise ValueError("column index out of range")
+    return rp, ci, v
+
+
+def sparse_loss_grad(loss: int, row_ptr, col_idx, val, y, D: int, w, lam: float):
+    """(L, g) at w for X given in CSR form (row_ptr [N+1] int64, col_idx int32, val float32)."""
+    y = _f32(y)
+    N = y.shape[0]
+    rp, ci, v = _csr(row_ptr, col_idx, val, N, D)
+    w = np.ascontiguousarray(np.asarray(w, dtype=np.float64))
+    if w.shape != (D,):
+        raise ValueError("w must have shape (D,)")
+    g = np.empty(D, dtype=np.float64)
+    L = ctypes.c_double(0.0)
+    rc = _load().oracle_sparse_loss_grad(int(loss), rp.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                         ci.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _fptr(v), _fptr(y),
+                                         N, D, _dptr(w), float(lam), ctypes.byref(L), _dptr(g))
+    if rc != 0:
+        raise ValueError("oracle_sparse_loss_grad rejected its arguments")
+    return float(L.value), g
+
+
+def sparse_run(loss: int, row_ptr, col_idx, val, y, D: int, w0, lam: float, eta: float, K: int):
+    """K constant-step GD iterations on a CSR matrix; returns (loss_hist, gnorm_hist, w_K, g_last)."""
+    y = _f32(y)
+    N = y.shape[0]
+    rp, ci, v = _csr(row_ptr, col_idx, val, N, D)
+    w = np.array(w0, dtype=np.float64, copy=True)
+    lh = np.empty(K); gh = np.empty(K); gl = np.zeros(D)
+    rc = _load().oracle_sparse_run(int(loss), rp.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                   ci.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _fptr(v), _fptr(y), N, D,
+                                   _dptr(w), float(lam), float(eta), int(K), _dptr(lh), _dptr(gh), _dptr(gl))
+    if rc != 0:
+        raise ValueError("oracle_sparse_run rejected its arguments")
     return lh, gh, w, gl
 
 

@@ -199,3 +199,82 @@ def config4(scale: float = 1.0, device: str = "cpu", D: int = 1024,
                     name=f"cfg4_sweep_{N}x{D}_M{n_lam * n_eta}")
     lams, etas = sweep_grid(n_lam, n_eta)
     return SweepProblem(base, lams, etas)
+
+
+# --------------------------------------------------------------------------- sparse inputs
+
+@dataclass
+class SparseGLMProblem:
+    """A job whose X is sparse: the same matrix in CSR (rows) and CSC (columns) form."""
+    name: str
+    loss: int
+    row_ptr: torch.Tensor    # [N+1] int64
+    col_idx: torch.Tensor    # [nnz] int32
+    row_val: torch.Tensor    # [nnz] fp32
+    col_ptr: torch.Tensor    # [D+1] int64
+    row_idx: torch.Tensor    # [nnz] int32
+    col_val: torch.Tensor    # [nnz] fp32
+    y: torch.Tensor          # [N] fp32
+    w0: torch.Tensor         # [D] fp32
+    N: int
+    D: int
+    lam: float
+    eta: float
+    K: int
+    seed: int
+
+    @property
+    def nnz(self) -> int:
+        return int(self.col_idx.shape[0])
+
+
+def make_sparse_glm(loss: int, N: int, D: int, mean_nnz: float, seed: int, *, lam: float, eta: float,
+                    K: int, skew: float = 3.0, device: str = "cpu", name: str = "") -> SparseGLMProblem:
+    """Sparse stand-in for the paper's text / LIBSVM-style data (Sec. 3 "Setup"), whose shapes are
+    not stated.  Row i stores n_i entries, n_i = round(mean_nnz * exp(0.5 g_i - 0.125)), g_i ~ N(0,1)
+    (log-normal lengths, a few rows empty or long); each entry's column is floor(D * u**skew),
+    u ~ U(0,1) (a few columns are very popular, most are rare, many are empty); values ~ N(0,1)
+    scaled by 1/sqrt(mean_nnz) so margins stay O(1).  A column may repeat inside a row; repeated
+    entries add, in both layouts.  The CSC arrays are the same entries sorted by column with a
+    stable sort, so a column lists its rows in increasing order.  Labels as in make_glm from
+    w* ~ N(0,1) and noise of variance 0.1.  Draw order: lengths, columns, values, w*, noise."""
+    if loss not in LOSS_NAMES:
+        raise ValueError("unknown loss type")
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(int(seed))
+    ln = torch.randn(N, generator=g, device=dev, dtype=torch.float32)
+    counts = torch.round(mean_nnz * torch.exp(0.5 * ln - 0.125)).to(torch.int64).clamp_(min=0)
+    row_ptr = torch.zeros(N + 1, dtype=torch.int64, device=dev)
+    torch.cumsum(counts, 0, out=row_ptr[1:])
+    nnz = int(row_ptr[-1].item())
+    u = torch.rand(nnz, generator=g, device=dev, dtype=torch.float32)
+    col = torch.clamp((u.double() ** skew * D).to(torch.int64), max=D - 1)
+    del u
+    val = torch.randn(nnz, generator=g, device=dev, dtype=torch.float32) / math.sqrt(max(mean_nnz, 1.0))
+    w_star = torch.randn(D, generator=g, device=dev, dtype=torch.float32)
+    noise = torch.randn(N, generator=g, device=dev, dtype=torch.float32) * math.sqrt(0.1)
+    # margins by a prefix sum over the entries (deterministic, fp64)
+    prod = val.double() * w_star.double()[col]
+    pref = torch.zeros(nnz + 1, dtype=torch.float64, device=dev)
+    torch.cumsum(prod, 0, out=pref[1:])
+    m = pref[row_ptr[1:]] - pref[row_ptr[:-1]] + noise.double()
+    del prod, pref
+    if loss == LOGISTIC:
+        y = (m > 0).to(torch.float32)
+    elif loss == HINGE:
+        y = torch.where(m >= 0, 1.0, -1.0).to(torch.float32)
+    else:
+        y = m.to(torch.float32)
+    # the same entries by column
+    order = torch.sort(col, stable=True).indices
+    rows_of = torch.repeat_interleave(torch.arange(N, device=dev, dtype=torch.int32), counts)
+    row_idx = rows_of[order].contiguous()
+    col_val = val[order].contiguous()
+    del rows_of, order
+    col_ptr = torch.zeros(D + 1, dtype=torch.int64, device=dev)
+    torch.cumsum(torch.bincount(col, minlength=D), 0, out=col_ptr[1:])
+    return SparseGLMProblem(name or f"sparse_{LOSS_NAMES[loss]}_{N}x{D}_nnz{nnz}", loss, row_ptr,
+                            col.to(torch.int32).contiguous(), val.contiguous(), col_ptr, row_idx, col_val,
+                            y.contiguous(), torch.zeros(D, dtype=torch.float32, device=dev), N, D,
+                            float(lam), float(eta), int(K), int(seed))
