@@ -123,6 +123,39 @@ int glm_sweep(const float *X /*DEVICE*/, const float *y /*DEVICE*/, int64_t N, i
               const float *lambdas /*HOST*/, const float *steps /*HOST*/, int32_t iters,
               float *loss_hist /*DEVICE*/, void *ws /*DEVICE*/, size_t ws_bytes, void *hip_stream);
 
+/* ---- Sparse data ------------------------------------------------------------------------ */
+
+/* A job whose X is sparse (the paper's text and LIBSVM-style data sets, Sec. 3 "Setup").  The
+ * caller supplies the same matrix twice: by rows (CSR) for the margins and by columns (CSC)
+ * for X^T r, so that both are gathers with a fixed summation order.  Entries of a row / column
+ * may come in any order and may repeat (repeats add).  HOST struct; the arrays are DEVICE. */
+typedef struct {
+    const int64_t *row_ptr;  /* [N+1] non-decreasing, row_ptr[0] = 0, row_ptr[N] = nnz            */
+    const int32_t *col_idx;  /* [nnz] column of each entry, 0 <= col < D                            */
+    const float   *row_val;  /* [nnz] value of each entry, in row order                             */
+    const int64_t *col_ptr;  /* [D+1] the same entries grouped by column                            */
+    const int32_t *row_idx;  /* [nnz] row of each entry, 0 <= row < N                               */
+    const float   *col_val;  /* [nnz] value of each entry, in column order                          */
+    const float   *y;        /* [N]                                                                 */
+    float         *w;        /* [D] in/out                                                          */
+    float         *grad;     /* [D] out                                                             */
+    float         *loss_hist;/* [hist_cap], written at hist_len .. hist_len + iters - 1             */
+    int64_t        N, D, nnz;/* 1 <= N, D < 2^31; 0 <= nnz                                          */
+    int32_t        loss;     /* glm_loss_t                                                          */
+    float          lambda, step;
+    int64_t        hist_len, hist_cap;
+} glm_sparse_job_t;
+
+/* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz only). */
+int glm_sparse_workspace_bytes(const glm_sparse_job_t *job /*HOST*/, size_t *out_bytes /*HOST*/);
+
+/* `iters` gradient-descent iterations of one sparse job: the same iteration as glm_step, with
+ * absent entries counting as zeros.  Reads each stored entry twice per iteration (once per
+ * layout).  The contents of the index arrays are trusted (they live on the device); sizes,
+ * pointers and hyper-parameters are validated as in glm_step, with the same error codes. */
+int glm_step_sparse(glm_sparse_job_t *job /*HOST*/, int32_t iters, void *ws /*DEVICE*/, size_t ws_bytes,
+                    void *hip_stream);
+
 /* ---- Scheduler-side steps that consume the loss histories (Sec. 2) ---------------------- */
 
 /* Convergence classes of Sec. 2 "Predicting Quality Improvement": class I, sublinear

@@ -318,6 +318,84 @@ int glm_sweep(const float *X, const float *y, int64_t N, int32_t D, int32_t M, i
     return GLM_OK;
 }
 
+namespace {
+struct SparseLayout { size_t seg0R, seg0C, closes, headless, slast, H, T, z, r, lossP, wwP, total; long long nch; };
+SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
+    SparseLayout L;
+    L.nch = (nnz + kSparseChunk - 1) / kSparseChunk;
+    const size_t nc = (size_t)L.nch;
+    size_t off = 0;
+    L.seg0R = off;    off = align_up(off + sizeof(int) * (nc + 1));
+    L.seg0C = off;    off = align_up(off + sizeof(int) * (nc + 1));
+    L.closes = off;   off = align_up(off + sizeof(int) * nc);
+    L.headless = off; off = align_up(off + sizeof(int) * nc);
+    L.slast = off;    off = align_up(off + sizeof(int) * nc);
+    L.H = off;        off = align_up(off + sizeof(float) * nc);
+    L.T = off;        off = align_up(off + sizeof(float) * nc);
+    L.z = off;        off = align_up(off + sizeof(float) * (size_t)(N + D));      // z [N] then gs [D]
+    L.r = off;        off = align_up(off + sizeof(float) * (size_t)N);
+    L.lossP = off;    off = align_up(off + sizeof(float) * (size_t)((N + 255) / 256));
+    L.wwP = off;      off = align_up(off + sizeof(double) * (size_t)((D + 255) / 256));
+    L.total = off;
+    return L;
+}
+int validate_sparse_shape(const glm_sparse_job_t &j) {
+    if (j.N < 1 || j.D < 1 || j.N >= (1LL << 31) || j.D >= (1LL << 31) || j.nnz < 0) return GLM_EINVAL;
+    if (j.nnz / kSparseChunk >= (1LL << 31) - 8) return GLM_EINVAL;
+    return GLM_OK;
+}
+}  // namespace
+
+int glm_sparse_workspace_bytes(const glm_sparse_job_t *job, size_t *out_bytes) {
+    if (!job || !out_bytes) return GLM_EINVAL;
+    if (validate_sparse_shape(*job) != GLM_OK) return GLM_EINVAL;
+    *out_bytes = make_sparse_layout(job->N, job->D, job->nnz).total;
+    return GLM_OK;
+}
+
+int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!job || iters < 0) return GLM_EINVAL;
+    const glm_sparse_job_t &j = *job;
+    if (validate_sparse_shape(j) != GLM_OK) return GLM_EINVAL;
+    if (!j.row_ptr || !j.col_ptr || !j.y || !j.w || !j.grad || !j.loss_hist) return GLM_EINVAL;
+    if (j.nnz > 0 && (!j.col_idx || !j.row_val || !j.row_idx || !j.col_val)) return GLM_EINVAL;
+    const void *p4[] = {j.col_idx, j.row_val, j.row_idx, j.col_val, j.y, j.w, j.grad, j.loss_hist};
+    for (const void *p : p4) if (reinterpret_cast<uintptr_t>(p) & 3u) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(j.row_ptr) & 7u) || (reinterpret_cast<uintptr_t>(j.col_ptr) & 7u)) return GLM_EINVAL;
+    if (j.loss < GLM_LOGISTIC || j.loss > GLM_SQUARED) return GLM_EINVAL;
+    if (!std::isfinite(j.lambda) || j.lambda < 0.0f || !std::isfinite(j.step) || j.step < 0.0f) return GLM_EINVAL;
+    if (j.hist_len < 0 || j.hist_cap < 0 || j.hist_len > j.hist_cap) return GLM_EINVAL;
+    if (j.hist_len + (int64_t)iters > j.hist_cap) return GLM_ENOSPC;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    const SparseLayout L = make_sparse_layout(j.N, j.D, j.nnz);
+    if (ws_bytes < L.total) return GLM_ENOSPC;
+    if (iters == 0) return GLM_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(ws);
+    SparseArgs a;
+    a.row_ptr = reinterpret_cast<const long long *>(j.row_ptr); a.col_idx = j.col_idx; a.row_val = j.row_val;
+    a.col_ptr = reinterpret_cast<const long long *>(j.col_ptr); a.row_idx = j.row_idx; a.col_val = j.col_val;
+    a.y = j.y; a.w = j.w; a.grad = j.grad; a.loss_out = j.loss_hist + j.hist_len;
+    a.N = j.N; a.D = j.D; a.nnz = j.nnz; a.nch = L.nch;
+    a.loss = j.loss; a.lambda = j.lambda; a.step = j.step;
+    a.seg0R = reinterpret_cast<int *>(base + L.seg0R); a.seg0C = reinterpret_cast<int *>(base + L.seg0C);
+    a.closes = reinterpret_cast<int *>(base + L.closes); a.headless = reinterpret_cast<int *>(base + L.headless);
+    a.slast = reinterpret_cast<int *>(base + L.slast);
+    a.H = reinterpret_cast<float *>(base + L.H); a.T = reinterpret_cast<float *>(base + L.T);
+    a.z = reinterpret_cast<float *>(base + L.z); a.gs = a.z + j.N;
+    a.r = reinterpret_cast<float *>(base + L.r);
+    a.lossP = reinterpret_cast<float *>(base + L.lossP); a.wwP = reinterpret_cast<double *>(base + L.wwP);
+    if (launch_sparse_setup(a, st) != hipSuccess) return GLM_EHIP;
+    for (int k = 0; k < iters; ++k) {
+        hipEvent_t *ev = nullptr;
+        if (g_prof.on && g_prof.used < g_prof.cap) { ev = &g_prof.ev[2 * g_prof.used]; g_prof.used += 1; }
+        if (launch_sparse_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
+    }
+    job->hist_len += iters;
+    return GLM_OK;
+}
+
 int glm_predict_workspace_bytes(int32_t J, size_t *out_bytes) {
     if (J < 1 || !out_bytes) return GLM_EINVAL;
     *out_bytes = align_up(sizeof(PredJob) * (size_t)J);

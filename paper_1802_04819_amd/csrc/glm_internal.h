@@ -99,4 +99,25 @@ hipError_t launch_predict(const PredJob *jobs, int J, double gamma, int window, 
                           double *pred, double *gain, double *fit, hipStream_t st);
 int allocate_greedy(const double *gain, int J, int H, long long capacity, int *alloc);
 
+// Sparse iteration (glm_sparse.hip).  All pointers are device pointers; the second block lives
+// in the caller's workspace.
+constexpr int kSparseChunk = 512;       // entries per wave of the segmented sums
+struct SparseArgs {
+    const long long *row_ptr; const int *col_idx; const float *row_val;
+    const long long *col_ptr; const int *row_idx; const float *col_val;
+    const float *y; float *w; float *grad; float *loss_out;
+    long long N, D, nnz, nch;           // nch = ceil(nnz / kSparseChunk)
+    int loss; float lambda, step;
+    int *seg0R, *seg0C;                 // [nch + 1] segment holding each chunk's first entry
+    int *closes, *headless, *slast;     // [nch] per-chunk leftovers of the pass in flight
+    float *H, *T;                       // [nch]
+    float *z;                           // [N] margins, immediately followed by
+    float *gs;                          // [D] column sums X^T r  (gs == z + N)
+    float *r;                           // [N] residuals
+    float *lossP;                       // [ceil(N / 256)]
+    double *wwP;                        // [ceil(D / 256)]
+};
+hipError_t launch_sparse_setup(const SparseArgs &a, hipStream_t st);
+hipError_t launch_sparse_iteration(const SparseArgs &a, int k, hipEvent_t *ev, hipStream_t st);
+
 }  // namespace slaqglm

@@ -1,0 +1,297 @@
+// GLM iteration on a sparse X held in CSR (rows) and CSC (columns) form.
+//
+// Both passes are the same deterministic segmented sum  out[s] = sum_{e in segment s} val[e] * vec[idx[e]]
+// (rows: vec = w, out = margins; columns: vec = residuals, out = X^T r).  Work is split by
+// ENTRIES, not by segments, so a few very long columns or rows cost no more than many short
+// ones: a wave owns a chunk of 512 consecutive entries, loads them coalesced, multiplies, and
+// reduces inside the chunk; segments that cross chunk borders are completed by a fix-up kernel
+// that adds the per-chunk pieces in chunk order.  No floating-point atomics: every sum has an
+// order fixed by the layout of the matrix alone.
+//
+// Inside a chunk: the segment starts that fall inside it are marked in LDS (integer counts, so
+// that empty segments advance the segment index too); lane l then walks entries 8 l .. 8 l + 7
+// in order.  A segment that starts and ends inside one lane is written directly.  The open
+// pieces at lane borders are combined by a segmented scan across the lanes (fixed shuffle tree).
+// Per chunk three things may remain: the piece of the segment that was already open at the chunk
+// start (H), the piece of the segment still open at the chunk end (T), or, if no segment starts
+// inside the chunk, the whole chunk as one piece (also T).
+#include "glm_internal.h"
+#include "glm_loss.h"
+
+namespace slaqglm {
+
+constexpr int kSpU = 8;                    // entries per lane
+constexpr int kSpChunk = 64 * kSpU;        // entries per wave
+static_assert(kSpChunk == kSparseChunk, "chunk size is part of the workspace layout");
+constexpr int kSpPad = kSpChunk + kSpChunk / 32;
+
+__device__ __forceinline__ int pad32(int p) { return p + (p >> 5); }   // breaks the stride-8 bank pattern
+
+// seg0[c] = last segment s < S whose start ptr[s] is <= c * chunk (the segment that holds the
+// chunk's first entry); seg0[nch] = S - 1.
+__global__ void seg_start_kernel(const long long *__restrict__ ptr, long long S, long long nch,
+                                 int *__restrict__ seg0) {
+    const long long c = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    if (c > nch) return;
+    if (c == nch) { seg0[c] = (int)(S - 1); return; }
+    const long long e = c * kSpChunk;
+    long long lo = 0, hi = S;              // invariant: ptr[lo] <= e (ptr[0] = 0), answer in [lo, hi)
+    while (hi - lo > 1) {
+        const long long mid = (lo + hi) >> 1;
+        if (ptr[mid] <= e) lo = mid; else hi = mid;
+    }
+    seg0[c] = (int)lo;
+}
+
+struct ChunkRec {                          // per-chunk leftovers, one array each (structure of arrays)
+    int *closes; int *headless; int *slast; float *H; float *T;
+};
+
+__global__ __launch_bounds__(256) void seg_sum_kernel(
+    const long long *__restrict__ ptr, const int *__restrict__ idx, const float *__restrict__ val,
+    const float *__restrict__ vec, long long E, long long nch, const int *__restrict__ seg0,
+    float *__restrict__ out, ChunkRec rec) {
+    __shared__ float prod_s[4][kSpPad];
+    __shared__ int flag_s[4][kSpPad];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const long long c = (long long)blockIdx.x * 4 + wave;
+    const bool active = c < nch;           // inactive waves still reach the barriers
+    float *prod = prod_s[wave];
+    int *flag = flag_s[wave];
+    const long long e0 = c * kSpChunk;
+    const long long e1 = active ? ((e0 + kSpChunk < E) ? e0 + kSpChunk : E) : e0;
+
+    for (int p = lane; p < kSpPad; p += 64) flag[p] = 0;
+    int s_lo = 0;
+    bool headless = false;
+    if (active) {
+#pragma unroll
+        for (int u = 0; u < kSpU; ++u) {
+            const long long e = e0 + u * 64 + lane;
+            float p = 0.0f;
+            if (e < e1) p = __builtin_nontemporal_load(val + e) * vec[__builtin_nontemporal_load(idx + e)];
+            prod[pad32(u * 64 + lane)] = p;
+        }
+        s_lo = seg0[c];
+        headless = ptr[s_lo] == e0;
+    }
+    __syncthreads();                       // flags are zero before anyone marks
+    if (active) {
+        const int s_up = seg0[c + 1];
+        for (int s = s_lo + 1 + lane; s <= s_up; s += 64) {
+            const long long pe = ptr[s];
+            if (pe < e1) atomicAdd(&flag[pad32((int)(pe - e0))], 1);    // integer count: order-free
+        }
+    }
+    __syncthreads();
+    if (!active) return;
+
+    // this lane's eight entries, and how many segment starts lie in them
+    float pv[kSpU]; int fv[kSpU];
+    int cnt = 0;
+#pragma unroll
+    for (int u = 0; u < kSpU; ++u) {
+        pv[u] = prod[pad32(lane * kSpU + u)];
+        fv[u] = flag[pad32(lane * kSpU + u)];
+        cnt += fv[u];
+    }
+    int incl = cnt;                        // inclusive prefix of the counts over the lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    int cur = s_lo + (incl - cnt);         // segment open when this lane starts
+    const int head_seg = cur;
+
+    const int nvalid = (int)(e1 - e0);
+    float acc = 0.0f, head = 0.0f;
+    bool started = false, lane_closes = false;
+#pragma unroll
+    for (int u = 0; u < kSpU; ++u) {
+        if (lane * kSpU + u < nvalid) {
+            if (fv[u] > 0) {
+                if (started) out[cur] = acc;                 // began and ended inside this lane
+                else { head = acc; lane_closes = true; }
+                cur += fv[u];
+                acc = 0.0f;
+                started = true;
+            }
+            acc += pv[u];
+        }
+    }
+    // segmented inclusive scan of the open pieces: a lane that closes starts a new run
+    float run = acc;
+    int runf = lane_closes ? 1 : 0;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float ov = __shfl_up(run, d, 64);
+        const int of = __shfl_up(runf, d, 64);
+        if (lane >= d) {
+            if (!runf) run = ov + run;
+            runf |= of;
+        }
+    }
+    float cin = __shfl_up(run, 1, 64);
+    int prevf = __shfl_up(runf, 1, 64);
+    if (lane == 0) { cin = 0.0f; prevf = 0; }
+    if (lane_closes) {
+        const float tot = cin + head;
+        if (prevf || headless) out[head_seg] = tot;          // the whole segment lies in this chunk
+        else rec.H[c] = tot;                                 // it was already open at the chunk start
+    }
+    const int last_lane = (nvalid - 1) / kSpU;
+    const int slast = __shfl(cur, last_lane, 64);
+    if (lane == 63) {
+        rec.closes[c] = runf;
+        rec.headless[c] = headless ? 1 : 0;
+        rec.slast[c] = slast;
+        rec.T[c] = run;
+    }
+}
+
+// Completes the segments that cross chunk borders.  The chunk in which such a segment starts
+// (it closes a segment, or begins exactly at a segment start) owns it: its T, then the T of the
+// following chunks that neither contain nor begin at a segment start, then the H of the chunk
+// that closes it.  One wave per chunk; long runs are consumed 64 chunks at a time.
+__global__ __launch_bounds__(256) void seg_fixup_kernel(long long nch, ChunkRec rec, float *__restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const long long c = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (c >= nch) return;
+    if (!(rec.closes[c] || rec.headless[c])) return;
+    double tot = (double)rec.T[c];
+    long long k0 = c + 1;
+    while (true) {
+        const long long k = k0 + lane;
+        const bool end = (k >= nch) || rec.headless[k];
+        const bool closing = !end && rec.closes[k];
+        const unsigned long long stop = __ballot(end || closing);
+        const int fs = stop ? (__ffsll((long long)stop) - 1) : 64;
+        double v = 0.0;
+        if (lane < fs) v = (double)rec.T[k];
+        else if (lane == fs && closing) v = (double)rec.H[k];
+        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+        tot += v;
+        if (fs < 64) break;
+        k0 += 64;
+    }
+    if (lane == 0) out[rec.slast[c]] = (float)tot;
+}
+
+__global__ void fill_zero_kernel(float *__restrict__ p, long long n) {
+    const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+// Rows: margins -> loss and residual; per-block loss sums in a fixed tree.
+__global__ __launch_bounds__(256) void sparse_row_epilogue(const float *__restrict__ z, const float *__restrict__ y,
+                                                           long long N, int loss, float *__restrict__ r,
+                                                           float *__restrict__ lossP) {
+    __shared__ float red[256];
+    const long long i = blockIdx.x * 256LL + threadIdx.x;
+    float l = 0.0f;
+    if (i < N) {
+        float rr;
+        loss_residual(loss, z[i], y[i], l, rr);
+        r[i] = rr;
+    }
+    red[threadIdx.x] = l;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] = red[threadIdx.x] + red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) lossP[blockIdx.x] = red[0];
+}
+
+// Columns: X^T r -> gradient, update; per-block sums of w^2 (entering iterate) in a fixed tree.
+__global__ __launch_bounds__(256) void sparse_col_epilogue(const float *__restrict__ gs, long long D, double invN,
+                                                           float lambda, float step, float *__restrict__ w,
+                                                           float *__restrict__ grad, double *__restrict__ wwP) {
+    __shared__ double red[256];
+    const long long j = blockIdx.x * 256LL + threadIdx.x;
+    double ww = 0.0;
+    if (j < D) {
+        const float wj = w[j];
+        const double g = (double)gs[j] * invN + (double)lambda * (double)wj;
+        grad[j] = (float)g;
+        ww = (double)wj * (double)wj;
+        if (step != 0.0f) w[j] = (float)((double)wj - (double)step * g);
+    }
+    red[threadIdx.x] = ww;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] = red[threadIdx.x] + red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) wwP[blockIdx.x] = red[0];
+}
+
+// loss_out = (sum lossP) / N + lambda / 2 * (sum wwP); thread t adds a contiguous run, then a fixed tree.
+__global__ __launch_bounds__(1024) void sparse_loss_kernel(const float *__restrict__ lossP, long long nR,
+                                                           const double *__restrict__ wwP, long long nC,
+                                                           double invN, float lambda, float *__restrict__ loss_out) {
+    __shared__ double redL[1024];
+    __shared__ double redW[1024];
+    const int t = threadIdx.x;
+    double a = 0.0, b = 0.0;
+    for (long long i = nR * t / 1024; i < nR * (t + 1) / 1024; ++i) a += (double)lossP[i];
+    for (long long i = nC * t / 1024; i < nC * (t + 1) / 1024; ++i) b += wwP[i];
+    redL[t] = a; redW[t] = b;
+    __syncthreads();
+    for (int s = 512; s >= 1; s >>= 1) {
+        if (t < s) { redL[t] += redL[t + s]; redW[t] += redW[t + s]; }
+        __syncthreads();
+    }
+    if (t == 0) *loss_out = (float)(redL[0] * invN + 0.5 * (double)lambda * redW[0]);
+}
+
+static hipError_t seg_pass(const long long *ptr, const int *idx, const float *val, const float *vec,
+                           long long S, long long E, long long nch, int *seg0, float *out, ChunkRec rec,
+                           hipStream_t st) {
+    if (nch == 0) return hipSuccess;
+    hipLaunchKernelGGL(seg_sum_kernel, dim3((unsigned)((nch + 3) / 4)), dim3(256), 0, st, ptr, idx, val, vec, E,
+                       nch, seg0, out, rec);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(seg_fixup_kernel, dim3((unsigned)((nch + 3) / 4)), dim3(256), 0, st, nch, rec, out);
+    (void)S;
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_setup(const SparseArgs &a, hipStream_t st) {
+    if (a.nch == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((a.nch + 1 + 255) / 256);
+    hipLaunchKernelGGL(seg_start_kernel, dim3(blocks), dim3(256), 0, st, a.row_ptr, a.N, a.nch, a.seg0R);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(seg_start_kernel, dim3(blocks), dim3(256), 0, st, a.col_ptr, a.D, a.nch, a.seg0C);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_iteration(const SparseArgs &a, int k, hipEvent_t *ev, hipStream_t st) {
+    hipError_t e;
+    ChunkRec rec{a.closes, a.headless, a.slast, a.H, a.T};
+    // z [N] and the column sums [D] are one allocation: clear both at once
+    const long long nz = a.N + a.D;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, a.z, nz);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
+    if ((e = seg_pass(a.row_ptr, a.col_idx, a.row_val, a.w, a.N, a.nnz, a.nch, a.seg0R, a.z, rec, st)) != hipSuccess)
+        return e;
+    const unsigned nbR = (unsigned)((a.N + 255) / 256), nbC = (unsigned)((a.D + 255) / 256);
+    hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = seg_pass(a.col_ptr, a.row_idx, a.col_val, a.r, a.D, a.nnz, a.nch, a.seg0C, a.gs, rec, st)) != hipSuccess)
+        return e;
+    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
+    hipLaunchKernelGGL(sparse_col_epilogue, dim3(nbC), dim3(256), 0, st, a.gs, a.D, 1.0 / (double)a.N, a.lambda,
+                       a.step, a.w, a.grad, a.wwP);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(sparse_loss_kernel, dim3(1), dim3(1024), 0, st, a.lossP, (long long)nbR, a.wwP,
+                       (long long)nbC, 1.0 / (double)a.N, a.lambda, a.loss_out + k);
+    return hipGetLastError();
+}
+
+}  // namespace slaqglm

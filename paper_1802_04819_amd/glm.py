@@ -23,6 +23,7 @@ EXPORTS = (
     "glm_workspace_bytes", "glm_step", "glm_step_batched", "glm_sweep", "glm_read_probe",
     "glm_read_probe_sink_floats", "glm_profile_begin", "glm_profile_end", "glm_strerror",
     "glm_predict_batched", "glm_predict_workspace_bytes", "glm_allocate_greedy",
+    "glm_sparse_workspace_bytes", "glm_step_sparse",
 )
 GLM_CURVE_SUBLINEAR, GLM_CURVE_LINEAR = 1, 2
 
@@ -34,6 +35,19 @@ class glm_job_t(ctypes.Structure):
         ("grad", ctypes.c_void_p), ("loss_hist", ctypes.c_void_p),
         ("N", ctypes.c_int64), ("D", ctypes.c_int32), ("loss", ctypes.c_int32),
         ("lambda_", ctypes.c_float), ("step", ctypes.c_float),
+        ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64),
+    ]
+
+
+class glm_sparse_job_t(ctypes.Structure):
+    """Mirror of the C struct glm_sparse_job_t."""
+    _fields_ = [
+        ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("row_val", ctypes.c_void_p),
+        ("col_ptr", ctypes.c_void_p), ("row_idx", ctypes.c_void_p), ("col_val", ctypes.c_void_p),
+        ("y", ctypes.c_void_p), ("w", ctypes.c_void_p), ("grad", ctypes.c_void_p),
+        ("loss_hist", ctypes.c_void_p),
+        ("N", ctypes.c_int64), ("D", ctypes.c_int64), ("nnz", ctypes.c_int64),
+        ("loss", ctypes.c_int32), ("lambda_", ctypes.c_float), ("step", ctypes.c_float),
         ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64),
     ]
 
@@ -88,6 +102,11 @@ def load():
     lib.glm_predict_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(sz)]
     lib.glm_allocate_greedy.restype = ctypes.c_int
     lib.glm_allocate_greedy.argtypes = [dbl, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, i32]
+    sjp = ctypes.POINTER(glm_sparse_job_t)
+    lib.glm_sparse_workspace_bytes.restype = ctypes.c_int
+    lib.glm_sparse_workspace_bytes.argtypes = [sjp, ctypes.POINTER(sz)]
+    lib.glm_step_sparse.restype = ctypes.c_int
+    lib.glm_step_sparse.argtypes = [sjp, ctypes.c_int32, vp, sz, vp]
     lib.glm_strerror.restype = ctypes.c_char_p
     lib.glm_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -221,6 +240,54 @@ def glm_sweep(X: torch.Tensor, y: torch.Tensor, loss: int, W: torch.Tensor, G: t
                           ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size(),
                           _stream_handle(stream))
     _check(rc, "glm_sweep")
+
+
+class SparseJob:
+    """A glm_sparse_job_t plus the tensors it points at."""
+
+    def __init__(self, row_ptr, col_idx, row_val, col_ptr, row_idx, col_val, y, w, loss: int, lam: float,
+                 step: float, hist_cap: int):
+        for t, dt in ((row_ptr, torch.int64), (col_ptr, torch.int64), (col_idx, torch.int32),
+                      (row_idx, torch.int32), (row_val, torch.float32), (col_val, torch.float32),
+                      (y, torch.float32), (w, torch.float32)):
+            if t.dtype != dt or not t.is_contiguous():
+                raise TypeError("sparse job tensors must be contiguous int64 / int32 / float32 as declared")
+        N, D, nnz = int(y.shape[0]), int(w.shape[0]), int(col_idx.shape[0])
+        if row_ptr.shape != (N + 1,) or col_ptr.shape != (D + 1,) or row_idx.shape != (nnz,) \
+                or row_val.shape != (nnz,) or col_val.shape != (nnz,):
+            raise ValueError("inconsistent sparse array shapes")
+        dev = y.device
+        self.tensors = (row_ptr, col_idx, row_val, col_ptr, row_idx, col_val, y)
+        self.w = w
+        self.grad = torch.zeros(D, dtype=torch.float32, device=dev)
+        self.loss_hist = torch.zeros(max(int(hist_cap), 1), dtype=torch.float32, device=dev)
+        self.c = glm_sparse_job_t(row_ptr.data_ptr(), col_idx.data_ptr(), row_val.data_ptr(),
+                                  col_ptr.data_ptr(), row_idx.data_ptr(), col_val.data_ptr(), y.data_ptr(),
+                                  w.data_ptr(), self.grad.data_ptr(), self.loss_hist.data_ptr(), N, D, nnz,
+                                  int(loss), float(lam), float(step), 0, int(hist_cap))
+
+    @property
+    def hist_len(self) -> int:
+        return int(self.c.hist_len)
+
+    def history(self) -> torch.Tensor:
+        return self.loss_hist[: self.hist_len]
+
+
+def glm_sparse_workspace_bytes(job: SparseJob) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().glm_sparse_workspace_bytes(ctypes.byref(job.c), ctypes.byref(out)), "glm_sparse_workspace_bytes")
+    return int(out.value)
+
+
+def alloc_sparse_workspace(job: SparseJob) -> torch.Tensor:
+    return torch.empty(max(glm_sparse_workspace_bytes(job), 256), dtype=torch.uint8, device=job.w.device)
+
+
+def glm_step_sparse(job: SparseJob, iters: int, ws: torch.Tensor, stream=None) -> None:
+    _require_gpu()
+    _check(load().glm_step_sparse(ctypes.byref(job.c), int(iters), ctypes.c_void_p(ws.data_ptr()), ws.numel(),
+                                  _stream_handle(stream)), "glm_step_sparse")
 
 
 def glm_predict_batched(jobs: Sequence[Job], curve, gamma: float, window: int, horizon: int,

@@ -1,0 +1,187 @@
+"""GPU tests of glm_step_sparse (CSR + CSC input, chunked deterministic segmented sums)."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import torch
+
+import oracle
+from paper_1802_04819_amd import glm, synth
+from _parity import REL_TOL, rel
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _job_from_problem(p, step=None, w=None, hist_cap=None, device="cuda"):
+    t = lambda x: x.to(device)
+    w0 = (p.w0 if w is None else w).to(device).clone()
+    return glm.SparseJob(t(p.row_ptr), t(p.col_idx), t(p.row_val), t(p.col_ptr), t(p.row_idx), t(p.col_val),
+                         t(p.y), w0, p.loss, p.lam, p.eta if step is None else step,
+                         p.K if hist_cap is None else hist_cap)
+
+
+def _job_from_scipy(A, y, loss, lam, step, hist_cap, w=None):
+    """A: scipy CSR (duplicates allowed, any order).  CSC = stable sort of the entries by column."""
+    A = sp.csr_matrix(A)
+    N, D = A.shape
+    rp = A.indptr.astype(np.int64); ci = A.indices.astype(np.int32); rv = A.data.astype(np.float32)
+    rows = np.repeat(np.arange(N, dtype=np.int32), np.diff(rp))
+    order = np.argsort(ci, kind="stable")
+    cp = np.concatenate([[0], np.cumsum(np.bincount(ci, minlength=D))]).astype(np.int64)
+    T = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    w0 = torch.zeros(D, device="cuda") if w is None else torch.from_numpy(np.asarray(w, np.float32)).cuda()
+    job = glm.SparseJob(T(rp), T(ci), T(rv), T(cp), T(rows[order]), T(rv[order]), T(np.asarray(y, np.float32)),
+                        w0, loss, lam, step, hist_cap)
+    return job, (rp, ci, rv)
+
+
+def _check_steps(job, csr, y, D, loss, lam, eta, iters, tag):
+    ws = glm.alloc_sparse_workspace(job)
+    rp, ci, rv = csr
+    for k in range(iters):
+        w_in = job.w.cpu().numpy().astype(np.float64)
+        glm.glm_step_sparse(job, 1, ws)
+        torch.cuda.synchronize()
+        L, g = oracle.sparse_loss_grad(loss, rp, ci, rv, np.asarray(y, np.float32), D, w_in, lam)
+        Lg = job.loss_hist[k].item()
+        gg = job.grad.cpu().numpy().astype(np.float64)
+        assert rel(Lg, L) <= REL_TOL, (tag, k, "loss", Lg, L)
+        gn = np.linalg.norm(g)
+        if gn > 0:
+            assert rel(np.linalg.norm(gg), gn) <= REL_TOL, (tag, k, "gnorm")
+        assert np.max(np.abs(gg - g)) <= REL_TOL * max(np.max(np.abs(g)), 1e-300), (tag, k, "grad entries")
+        w_ref = w_in - eta * g
+        scale = max(np.max(np.abs(w_ref)), eta * np.max(np.abs(g)), 1e-30)
+        assert np.max(np.abs(job.w.cpu().numpy() - w_ref)) <= REL_TOL * scale, (tag, k, "update")
+    assert job.hist_len == iters
+
+
+def _labels(loss, N, rng):
+    if loss == synth.LOGISTIC:
+        return (rng.random(N) > 0.5).astype(np.float32)
+    if loss == synth.HINGE:
+        return np.where(rng.random(N) > 0.5, 1.0, -1.0).astype(np.float32)
+    return rng.standard_normal(N).astype(np.float32)
+
+
+STRUCTURES = {
+    "random 3 percent": lambda rng: sp.random(700, 300, 0.03, format="csr", random_state=1, dtype=np.float32),
+    "one entry": lambda rng: sp.csr_matrix(([2.5], ([3], [1])), shape=(9, 4), dtype=np.float32),
+    "empty matrix": lambda rng: sp.csr_matrix((5, 7), dtype=np.float32),
+    "single row and column": lambda rng: sp.csr_matrix(np.array([[1.5]], np.float32)),
+    "dense block": lambda rng: sp.csr_matrix(rng.standard_normal((70, 33)).astype(np.float32)),
+    "one long column over many chunks": lambda rng: sp.csr_matrix(
+        (rng.standard_normal(5000).astype(np.float32), (np.arange(5000), np.full(5000, 7))), shape=(5000, 20)),
+    "one long row over many chunks": lambda rng: sp.csr_matrix(
+        (rng.standard_normal(3000).astype(np.float32), (np.full(3000, 2), np.arange(3000))), shape=(6, 3000)),
+    "rows of exactly one chunk": lambda rng: sp.csr_matrix(rng.standard_normal((5, 512)).astype(np.float32)),
+    "mostly empty rows and columns": lambda rng: sp.random(4000, 5000, 0.0003, format="csr", random_state=2, dtype=np.float32),
+    "short rows long columns": lambda rng: sp.csr_matrix(
+        (rng.standard_normal(20000).astype(np.float32),
+         (np.arange(20000) // 2, (rng.random(20000) ** 6 * 50).astype(int))), shape=(10000, 50)),
+}
+
+
+@pytest.mark.parametrize("loss", [synth.LOGISTIC, synth.HINGE, synth.SQUARED])
+@pytest.mark.parametrize("name", sorted(STRUCTURES))
+def test_each_step_matches_oracle_on_hand_built_structures(name, loss):
+    _say(f"[case] sparse per-step parity: {name}, loss {loss}")
+    rng = np.random.default_rng(5)
+    A = STRUCTURES[name](rng)
+    N, D = A.shape
+    y = _labels(loss, N, rng)
+    eta = {synth.LOGISTIC: 0.5, synth.HINGE: 0.05, synth.SQUARED: 0.02}[loss]
+    job, csr = _job_from_scipy(A, y, loss, 1e-3, eta, 3)
+    _check_steps(job, csr, y, D, loss, 1e-3, eta, 3, name)
+
+
+def test_duplicate_entries_add():
+    _say("[case] sparse: repeated (row, column) pairs add")
+    rows = np.array([0, 0, 0, 1, 2, 2]); cols = np.array([1, 1, 3, 0, 2, 2])
+    vals = np.array([1.0, 2.0, -1.0, 0.5, 4.0, -1.5], np.float32)
+    rp = np.array([0, 3, 4, 6], np.int64)
+    order = np.argsort(cols, kind="stable")
+    cp = np.concatenate([[0], np.cumsum(np.bincount(cols, minlength=4))]).astype(np.int64)
+    T = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    y = np.array([1.0, 0.0, 1.0], np.float32)
+    w = torch.tensor([0.3, -0.2, 0.1, 0.5], device="cuda")
+    job = glm.SparseJob(T(rp), T(cols.astype(np.int32)), T(vals), T(cp), T(rows[order].astype(np.int32)),
+                        T(vals[order]), T(y), w, synth.LOGISTIC, 0.1, 0.0, 1)
+    glm.glm_step_sparse(job, 1, glm.alloc_sparse_workspace(job))
+    torch.cuda.synchronize()
+    dense = np.zeros((3, 4), np.float32)
+    np.add.at(dense, (rows, cols), vals)
+    L, g = oracle.loss_grad(synth.LOGISTIC, dense, y, w.cpu().numpy().astype(np.float64), 0.1)
+    assert rel(job.loss_hist[0].item(), L) <= 1e-6
+    assert np.max(np.abs(job.grad.cpu().numpy() - g)) <= 1e-6
+
+
+@pytest.mark.parametrize("loss", [synth.LOGISTIC, synth.SQUARED])
+def test_trajectory_on_generated_data(loss):
+    _say(f"[case] sparse trajectory parity on generator data, loss {loss}")
+    eta = 0.5 if loss == synth.LOGISTIC else 0.1
+    p = synth.make_sparse_glm(loss, 20000, 5000, 30.0, seed=4, lam=1e-4, eta=eta, K=15)
+    job = _job_from_problem(p)
+    glm.glm_step_sparse(job, p.K, glm.alloc_sparse_workspace(job))
+    torch.cuda.synchronize()
+    lh, gh, wK, g_last = oracle.sparse_run(loss, p.row_ptr.numpy(), p.col_idx.numpy(), p.row_val.numpy(),
+                                           p.y.numpy(), p.D, np.zeros(p.D), p.lam, p.eta, p.K)
+    got = job.history().cpu().numpy()
+    assert all(rel(got[k], lh[k]) <= REL_TOL for k in range(p.K)), (got, lh)
+    assert rel(np.linalg.norm(job.grad.cpu().numpy().astype(np.float64)), gh[-1]) <= REL_TOL
+    assert np.max(np.abs(job.w.cpu().numpy() - wK)) <= REL_TOL * np.max(np.abs(wK))
+    assert got[-1] < got[0]
+
+
+def test_dense_matrix_as_sparse_agrees_with_dense_path():
+    _say("[case] a dense matrix stored sparsely gives the dense path's trajectory")
+    p = synth.make_glm(synth.LOGISTIC, 3000, 64, seed=2, lam=1e-3, eta=0.3, K=6)
+    job, _ = _job_from_scipy(sp.csr_matrix(p.X.numpy()), p.y.numpy(), p.loss, p.lam, p.eta, 6)
+    glm.glm_step_sparse(job, 6, glm.alloc_sparse_workspace(job))
+    d = glm.Job(p.X.cuda(), p.y.cuda(), p.w0.cuda(), p.loss, p.lam, p.eta, 6)
+    glm.glm_step(d, 6, glm.alloc_workspace([d]))
+    torch.cuda.synchronize()
+    a, b = job.history().cpu().numpy(), d.history().cpu().numpy()
+    assert np.max(np.abs(a - b) / b) <= 1e-5
+    assert torch.allclose(job.w, d.w, rtol=1e-4, atol=1e-6)
+
+
+def test_sparse_reruns_bit_identical_and_split_calls():
+    _say("[case] sparse rerun determinism and K = 3 + 4")
+    p = synth.make_sparse_glm(synth.HINGE, 50000, 20000, 40.0, seed=9, lam=1e-4, eta=0.05, K=7, device="cuda")
+    outs = []
+    for split in ((7,), (7,), (3, 4)):
+        job = _job_from_problem(p)
+        ws = glm.alloc_sparse_workspace(job)
+        for it in split:
+            glm.glm_step_sparse(job, it, ws)
+        torch.cuda.synchronize()
+        outs.append((job.history().clone(), job.w.clone(), job.grad.clone()))
+    for o in outs[1:]:
+        assert all(torch.equal(x, y) for x, y in zip(outs[0], o))
+
+
+def test_sparse_errors():
+    _say("[case] sparse error codes")
+    p = synth.make_sparse_glm(synth.LOGISTIC, 100, 50, 5.0, seed=1, lam=1e-3, eta=0.1, K=2)
+    job = _job_from_problem(p, hist_cap=2)
+    ws = glm.alloc_sparse_workspace(job)
+    with pytest.raises(glm.GlmError) as e:
+        glm.glm_step_sparse(job, 3, ws)
+    assert e.value.status == glm.GLM_ENOSPC
+    with pytest.raises(glm.GlmError) as e:
+        glm.glm_step_sparse(job, 1, ws[:256])
+    assert e.value.status == glm.GLM_ENOSPC
+    job.c.loss = 7
+    with pytest.raises(glm.GlmError) as e:
+        glm.glm_step_sparse(job, 1, ws)
+    assert e.value.status == glm.GLM_EINVAL
+    job.c.loss = 0
+    job.c.lambda_ = -1.0
+    with pytest.raises(glm.GlmError):
+        glm.glm_step_sparse(job, 1, ws)
+    torch.cuda.synchronize()
+    assert job.hist_len == 0 and job.w.abs().sum().item() == 0
