@@ -154,29 +154,43 @@ __global__ __launch_bounds__(256) void seg_sum_kernel(
 // Completes the segments that cross chunk borders.  The chunk in which such a segment starts
 // (it closes a segment, or begins exactly at a segment start) owns it: its T, then the T of the
 // following chunks that neither contain nor begin at a segment start, then the H of the chunk
-// that closes it.  One wave per chunk; long runs are consumed 64 chunks at a time.
+// that closes it.  One lane per chunk settles the common case (the segment ends in the next
+// chunk, or at its border); the owners of longer runs are then served one after another by the
+// whole wave, 64 chunks per step, so a segment of millions of entries takes a few dozen steps.
 __global__ __launch_bounds__(256) void seg_fixup_kernel(long long nch, ChunkRec rec, float *__restrict__ out) {
     const int lane = threadIdx.x & 63;
-    const long long c = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (c >= nch) return;
-    if (!(rec.closes[c] || rec.headless[c])) return;
-    double tot = (double)rec.T[c];
-    long long k0 = c + 1;
-    while (true) {
-        const long long k = k0 + lane;
-        const bool end = (k >= nch) || rec.headless[k];
-        const bool closing = !end && rec.closes[k];
-        const unsigned long long stop = __ballot(end || closing);
-        const int fs = stop ? (__ffsll((long long)stop) - 1) : 64;
-        double v = 0.0;
-        if (lane < fs) v = (double)rec.T[k];
-        else if (lane == fs && closing) v = (double)rec.H[k];
-        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-        tot += v;
-        if (fs < 64) break;
-        k0 += 64;
+    const long long c = blockIdx.x * 256LL + threadIdx.x;
+    bool pending = false;
+    if (c < nch && (rec.closes[c] || rec.headless[c])) {
+        const float t = rec.T[c];
+        const long long k = c + 1;
+        if (k >= nch || rec.headless[k]) out[rec.slast[c]] = t;
+        else if (rec.closes[k]) out[rec.slast[c]] = (float)((double)t + (double)rec.H[k]);
+        else pending = true;
     }
-    if (lane == 0) out[rec.slast[c]] = (float)tot;
+    unsigned long long todo = __ballot(pending);
+    while (todo) {
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const long long cs = c - lane + src;                  // the owner chunk being served
+        double tot = (double)rec.T[cs];
+        long long k0 = cs + 1;
+        while (true) {
+            const long long k = k0 + lane;
+            const bool end = (k >= nch) || rec.headless[k];
+            const bool cl = !end && rec.closes[k];
+            const unsigned long long stop = __ballot(end || cl);
+            const int fs = stop ? (__ffsll((long long)stop) - 1) : 64;
+            double v = 0.0;
+            if (lane < fs) v = (double)rec.T[k];
+            else if (lane == fs && cl) v = (double)rec.H[k];
+            for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+            tot += v;
+            if (fs < 64) break;
+            k0 += 64;
+        }
+        if (lane == src) out[rec.slast[cs]] = (float)tot;
+    }
 }
 
 __global__ void fill_zero_kernel(float *__restrict__ p, long long n) {
@@ -255,7 +269,7 @@ static hipError_t seg_pass(const long long *ptr, const int *idx, const float *va
                        nch, seg0, out, rec);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(seg_fixup_kernel, dim3((unsigned)((nch + 3) / 4)), dim3(256), 0, st, nch, rec, out);
+    hipLaunchKernelGGL(seg_fixup_kernel, dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, st, nch, rec, out);
     (void)S;
     return hipGetLastError();
 }

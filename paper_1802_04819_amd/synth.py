@@ -234,7 +234,8 @@ def make_sparse_glm(loss: int, N: int, D: int, mean_nnz: float, seed: int, *, la
     not stated.  Row i stores n_i entries, n_i = round(mean_nnz * exp(0.5 g_i - 0.125)), g_i ~ N(0,1)
     (log-normal lengths, a few rows empty or long); each entry's column is floor(D * u**skew),
     u ~ U(0,1) (a few columns are very popular, most are rare, many are empty); values ~ N(0,1)
-    scaled by 1/sqrt(mean_nnz) so margins stay O(1).  A column may repeat inside a row; repeated
+    scaled by 1/sqrt(mean_nnz) so margins stay O(1).  The columns of a row are stored in increasing
+    order (canonical CSR).  A column may repeat inside a row; repeated
     entries add, in both layouts.  The CSC arrays are the same entries sorted by column with a
     stable sort, so a column lists its rows in increasing order.  Labels as in make_glm from
     w* ~ N(0,1) and noise of variance 0.1.  Draw order: lengths, columns, values, w*, noise."""
@@ -251,6 +252,10 @@ def make_sparse_glm(loss: int, N: int, D: int, mean_nnz: float, seed: int, *, la
     u = torch.rand(nnz, generator=g, device=dev, dtype=torch.float32)
     col = torch.clamp((u.double() ** skew * D).to(torch.int64), max=D - 1)
     del u
+    # canonical CSR: the columns of a row in increasing order (values are i.i.d., so they stay put)
+    rows64 = torch.repeat_interleave(torch.arange(N, device=dev, dtype=torch.int64), counts)
+    col = torch.sort(rows64 * D + col).values - rows64 * D
+    del rows64
     val = torch.randn(nnz, generator=g, device=dev, dtype=torch.float32) / math.sqrt(max(mean_nnz, 1.0))
     w_star = torch.randn(D, generator=g, device=dev, dtype=torch.float32)
     noise = torch.randn(N, generator=g, device=dev, dtype=torch.float32) * math.sqrt(0.1)
@@ -278,3 +283,12 @@ def make_sparse_glm(loss: int, N: int, D: int, mean_nnz: float, seed: int, *, la
                             col.to(torch.int32).contiguous(), val.contiguous(), col_ptr, row_idx, col_val,
                             y.contiguous(), torch.zeros(D, dtype=torch.float32, device=dev), N, D,
                             float(lam), float(eta), int(K), int(seed))
+
+
+def sparse_config(scale: float = 1.0, device: str = "cpu") -> SparseGLMProblem:
+    """The sparse measurement workload: logistic regression on 2,000,000 x 1,000,000 with about
+    100 stored entries per row (about 2e8 entries, 1.6 GB per layout)."""
+    N = max(1000, int(2_000_000 * scale))
+    D = max(100, int(1_000_000 * scale))
+    return make_sparse_glm(LOGISTIC, N, D, 100.0, 0, lam=1e-5, eta=0.5, K=20, device=device,
+                           name=f"sparse_logistic_{N}x{D}")

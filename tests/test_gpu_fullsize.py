@@ -123,3 +123,28 @@ def test_config4_full_size_sampled_models():
         _say(f"[case] config 4: oracle for model {m} at iterate 4")
         check_step_against_oracle(p.loss, Xn, yn, W4[m].cpu().numpy(), float(sp.lams[m]), h[4, m],
                                   G[m].cpu().numpy(), chunks=_threads(), tag=f"cfg4 m={m}")
+
+
+def test_sparse_config_full_size_steps():
+    _say("[case] sparse configuration full size: logistic 2e6 x 1e6, ~2e8 entries, 6 iterations")
+    p = synth.sparse_config(device="cuda")
+    assert p.N == 2_000_000 and p.D == 1_000_000 and p.nnz > 150_000_000
+    K = 6
+    job = glm.SparseJob(p.row_ptr, p.col_idx, p.row_val, p.col_ptr, p.row_idx, p.col_val, p.y,
+                        p.w0.clone(), p.loss, p.lam, p.eta, K)
+    ws = glm.alloc_sparse_workspace(job)
+    rp, ci, rv = p.row_ptr.cpu().numpy(), p.col_idx.cpu().numpy(), p.row_val.cpu().numpy()
+    yn = p.y.cpu().numpy()
+    for k in range(K):
+        w_in = job.w.cpu().numpy().copy() if k in (0, 1, 5) else None
+        glm.glm_step_sparse(job, 1, ws)
+        torch.cuda.synchronize()
+        if w_in is not None:
+            _say(f"[case] sparse full size: oracle at iterate {k}")
+            L, g = oracle.sparse_loss_grad(p.loss, rp, ci, rv, yn, p.D, w_in.astype(np.float64), p.lam)
+            got_g = job.grad.cpu().numpy().astype(np.float64)
+            assert rel(job.loss_hist[k].item(), L) <= REL_TOL, (k, job.loss_hist[k].item(), L)
+            assert rel(np.linalg.norm(got_g), np.linalg.norm(g)) <= REL_TOL
+            assert np.max(np.abs(got_g - g)) <= REL_TOL * np.max(np.abs(g))
+    h = job.history().cpu().numpy()
+    assert abs(h[0] - np.log(2.0)) < 2e-6 and np.all(np.diff(h) < 0)
