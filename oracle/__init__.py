@@ -1,6 +1,6 @@
-"""fp64 CPU oracle for the GLM full-batch iteration (TEST INFRASTRUCTURE).
+"""fp64 CPU oracle for the GLM full-batch iteration and the K-Means iteration (TEST INFRASTRUCTURE).
 
-Thin ctypes wrapper over ``glm_oracle.c``.  Only tests, the smoke check and the
+Thin ctypes wrapper over ``glm_oracle.c`` and ``kmeans_oracle.c``.  Only tests, the smoke check and the
 benchmark's CPU-baseline leg may import this package; the GPU library never
 does.  Nothing here depends on the GPU package, and the GPU package does not
 depend on anything here.
@@ -25,16 +25,17 @@ LOGISTIC, HINGE, SQUARED = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "glm_oracle.c")
+_SRCS = [_SRC, os.path.join(_HERE, "kmeans_oracle.c")]
 _LIB_PATH = os.path.join(_HERE, "libglm_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile glm_oracle.c with gcc (OpenMP on) into libglm_oracle.so beside it."""
-    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
+    """Compile the C sources here with gcc (OpenMP on) into libglm_oracle.so beside them."""
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < max(os.path.getmtime(f) for f in _SRCS):
         tmp = _LIB_PATH + f".tmp{os.getpid()}"
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"]
+               "-Wall", "-Wextra", "-o", tmp] + _SRCS + ["-lm"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB_PATH)
     return _LIB_PATH
@@ -64,6 +65,10 @@ def _load():
         lib.oracle_sparse_run.restype = ctypes.c_int
         lib.oracle_sparse_run.argtypes = [ctypes.c_int, i64p, i32p, fp, fp, ctypes.c_int64, ctypes.c_int64,
                                           dp, ctypes.c_double, ctypes.c_double, ctypes.c_int32, dp, dp, dp]
+        lib.oracle_kmeans_assign.restype = ctypes.c_int
+        lib.oracle_kmeans_assign.argtypes = [fp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, i32p, dp, dp]
+        lib.oracle_kmeans_step.restype = ctypes.c_int
+        lib.oracle_kmeans_step.argtypes = [fp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, i32p, i64p, dp]
         lib.oracle_max_threads.restype = ctypes.c_int
         lib.oracle_max_threads.argtypes = []
         _lib = lib
@@ -199,3 +204,46 @@ def run_sweep(loss: int, X, y, W0, lams: Sequence[float], etas: Sequence[float],
         a, b, c, d = run(loss, X, y, W0[m], float(lams[m]), float(etas[m]), K, chunks)
         lh[:, m], gh[:, m], WK[m], GL[m] = a, b, c, d
     return lh, gh, WK, GL
+
+
+def kmeans_assign(X, C):
+    """(assign [N] int32, best [N], second [N]): nearest centroid (lowest index on ties), the
+    squared distance to it and to the nearest other centroid (-1 when K == 1), in fp64."""
+    X = _f32(X)
+    N, D = X.shape
+    C = np.ascontiguousarray(np.asarray(C, dtype=np.float64))
+    if C.ndim != 2 or C.shape[1] != D:
+        raise ValueError("C must have shape (K, D)")
+    K = C.shape[0]
+    a = np.empty(N, dtype=np.int32); b = np.empty(N); s = np.empty(N)
+    rc = _load().oracle_kmeans_assign(_fptr(X), N, D, _dptr(C), K, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                      _dptr(b), _dptr(s))
+    if rc != 0:
+        raise ValueError("oracle_kmeans_assign rejected its arguments")
+    return a, b, s
+
+
+def kmeans_step(X, C):
+    """One Lloyd iteration from centroids C [K, D]: returns (L, C_new, assign, counts) with L the
+    mean squared distance to the nearest ENTERING centroid; empty clusters keep their centroid."""
+    X = _f32(X)
+    N, D = X.shape
+    Cn = np.array(C, dtype=np.float64, copy=True, order="C")
+    if Cn.ndim != 2 or Cn.shape[1] != D:
+        raise ValueError("C must have shape (K, D)")
+    K = Cn.shape[0]
+    a = np.empty(N, dtype=np.int32); cnt = np.empty(K, dtype=np.int64); L = ctypes.c_double(0.0)
+    rc = _load().oracle_kmeans_step(_fptr(X), N, D, _dptr(Cn), K, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                    cnt.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), ctypes.byref(L))
+    if rc != 0:
+        raise ValueError("oracle_kmeans_step rejected its arguments")
+    return float(L.value), Cn, a, cnt
+
+
+def kmeans_run(X, C0, iters: int):
+    """`iters` Lloyd iterations: (loss_hist [iters], C_final, assign of the last iteration, counts)."""
+    C = np.array(C0, dtype=np.float64, copy=True)
+    hist = np.empty(iters); a = cnt = None
+    for k in range(iters):
+        hist[k], C, a, cnt = kmeans_step(X, C)
+    return hist, C, a, cnt

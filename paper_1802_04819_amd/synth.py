@@ -292,3 +292,58 @@ def sparse_config(scale: float = 1.0, device: str = "cpu") -> SparseGLMProblem:
     D = max(100, int(1_000_000 * scale))
     return make_sparse_glm(LOGISTIC, N, D, 100.0, 0, lam=1e-5, eta=0.5, K=20, device=device,
                            name=f"sparse_logistic_{N}x{D}")
+
+
+@dataclass
+class KMeansProblem:
+    """A clustering job: points X [N, D] fp32 and the starting centroids C0 [K, D] fp32."""
+    name: str
+    X: torch.Tensor
+    C0: torch.Tensor
+    iters: int
+    seed: int
+
+    @property
+    def N(self) -> int:
+        return int(self.X.shape[0])
+
+    @property
+    def D(self) -> int:
+        return int(self.X.shape[1])
+
+    @property
+    def K(self) -> int:
+        return int(self.C0.shape[0])
+
+
+def make_kmeans(N: int, D: int, K: int, seed: int, *, iters: int = 10, blobs: int = 0, spread: float = 3.0,
+                offset: float = 0.0, device: str = "cpu", name: str = "") -> KMeansProblem:
+    """Seeded Gaussian-mixture points: `blobs` (default K) true centres ~ N(0, (4 spread)^2 / D) per
+    coordinate (centre-to-centre distance about 5.7 spread whatever D is, against a noise radius of
+    sqrt(D)), uneven blob sizes (weights ~ u^2 + 0.05), unit-variance noise per coordinate, every
+    coordinate shifted by `offset`.  The starting
+    centroids are K distinct points of X picked by a seeded permutation (the random draw of the
+    usual initialisation is an input of the method, not part of it)."""
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    B = blobs if blobs > 0 else K
+    centres = torch.randn(B, D, generator=g, device=dev, dtype=torch.float32) * (spread / D ** 0.5) * 4.0
+    wts = torch.rand(B, generator=g, device=dev, dtype=torch.float32) ** 2 + 0.05
+    z = torch.multinomial(wts, N, replacement=True, generator=g)
+    X = torch.empty(N, D, device=dev, dtype=torch.float32)
+    step = max(1, (1 << 26) // max(D, 1))
+    for i0 in range(0, N, step):
+        i1 = min(N, i0 + step)
+        X[i0:i1] = centres[z[i0:i1]] + torch.randn(i1 - i0, D, generator=g, device=dev, dtype=torch.float32)
+    if offset != 0.0:
+        X += offset
+    pick = torch.randperm(N, generator=g, device=dev)[:K]
+    C0 = X[pick].clone()
+    return KMeansProblem(name or f"kmeans_{N}x{D}_k{K}", X, C0, iters, seed)
+
+
+def kmeans_config(scale: float = 1.0, device: str = "cpu") -> KMeansProblem:
+    """The clustering measurement workload: 4,000,000 points in 128 dimensions, 256 centroids."""
+    return make_kmeans(max(1024, int(4_000_000 * scale)), 128, 256, 0, iters=10, device=device,
+                       name=f"kmeans_{max(1024, int(4_000_000 * scale))}x128_k256")
