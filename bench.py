@@ -29,9 +29,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5, 6],
+    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5, 6, 7],
                     help="0-4: the benchmark configurations; 5: one scheduling decision (predict + "
-                         "allocate) for 4000 jobs and 16384 units; 6: one sparse job, 2e6 x 1e6 with ~2e8 entries")
+                         "allocate) for 4000 jobs and 16384 units; 6: one sparse job, 2e6 x 1e6 with ~2e8 entries; "
+                         "7: K-Means, 4e6 x 128 with 256 centroids")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only; the line says so)")
     ap.add_argument("--check", action="store_true", help="also compare against the oracle on the full data")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -479,6 +480,66 @@ def bench_sparse(args):
     return out
 
 
+def bench_kmeans(args):
+    """K-Means: 4,000,000 points in 128 dimensions, 256 centroids.  One step is one Lloyd iteration
+    (norms, assignment on the matrix cores, accumulation pass, finalize)."""
+    import numpy as np
+    import torch
+    from paper_1802_04819_amd import glm, synth
+
+    p = synth.kmeans_config(args.scale, device="cuda")
+    K = args.steps if args.steps is not None else p.iters
+    job = glm.KMeansJob(p.X, p.C0.clone(), max(K, args.warmup, 1))
+    ws = glm.alloc_kmeans_workspace(job)
+    if args.warmup > 0:
+        glm.glm_kmeans_step(job, args.warmup, ws)
+    torch.cuda.synchronize()
+    job.C.copy_(p.C0); job.c.hist_len = 0
+    glm.glm_profile_begin(2 * K)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    glm.glm_kmeans_step(job, K, ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = glm.glm_profile_end(2 * K)
+    hist = job.history().cpu().numpy().copy(); C1 = job.C.clone(); a1 = job.assign.clone()
+    job.C.copy_(p.C0); job.c.hist_len = 0
+    glm.glm_kmeans_step(job, K, ws)
+    torch.cuda.synchronize()
+    rerun_identical = bool(np.array_equal(hist, job.history().cpu().numpy()) and torch.equal(C1, job.C)
+                           and torch.equal(a1, job.assign))
+    sec = t1 - t0
+    asg_ms, acc_ms = float(np.mean(ms[0::2])), float(np.mean(ms[1::2]))
+    flop = 2.0 * p.N * p.D * p.K                    # the products x_i . c_k
+    x_bytes = 4.0 * p.N * p.D
+    achieved = flop / (asg_ms * 1e-3) / 1e12
+    out = {
+        "metric": "K-Means iterations/sec (matrix-core TFLOP/s of the assignment kernel in roofline)",
+        "value": K / sec, "unit": "iter/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": 1e3 * sec / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": p.name, "config_index": 7, "N": p.N, "D": p.D, "K": p.K,
+                   "flop_per_iteration": flop, "scale": args.scale},
+        "roofline": {"bound": "mfma", "kernel": "kmeans_assign_kernel", "achieved": achieved,
+                     "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS,
+                     "traffic": None, "assign_ms": asg_ms, "accumulate_ms": acc_ms,
+                     "accumulate_X_GBps": x_bytes / (acc_ms * 1e-3) / 1e9},
+        "rerun_bit_identical": rerun_identical, "loss_first": float(hist[0]), "loss_last": float(hist[-1]),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        n = min(p.N, 200_000)
+        Xs = p.X[:n].cpu().numpy(); C0 = p.C0.cpu().numpy()
+        t = time.perf_counter()
+        oracle.kmeans_step(Xs, C0)
+        dt = time.perf_counter() - t
+        out["cpu_baseline"] = {"value": 1.0 / (dt * p.N / n), "unit": "iter/s", "cores": oracle.max_threads(),
+                               "kind": "oracle",
+                               "sample": f"first {n} of {p.N} points, one oracle iteration ({dt:.2f} s), "
+                                         f"rate scaled by {n}/{p.N}"}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -504,8 +565,10 @@ def main():
         out = bench_sweep(args)
     elif args.config == 5:
         out = bench_sched(args)
-    else:
+    elif args.config == 6:
         out = bench_sparse(args)
+    else:
+        out = bench_kmeans(args)
     print(json.dumps(out))
 
 

@@ -123,6 +123,41 @@ int glm_sweep(const float *X /*DEVICE*/, const float *y /*DEVICE*/, int64_t N, i
               const float *lambdas /*HOST*/, const float *steps /*HOST*/, int32_t iters,
               float *loss_hist /*DEVICE*/, void *ws /*DEVICE*/, size_t ws_bytes, void *hip_stream);
 
+/* ---- K-Means ---------------------------------------------------------------------------- */
+
+/* A clustering job (K-Means is one of the unsupervised jobs of Sec. 3, "Setup"; it is an
+ * Expectation-Maximization iteration in the sense of Sec. 1, "ML training is typically
+ * iterative with diminishing returns").  One iteration, from centroids c_k:
+ *   a_i = the lowest k that minimises |x_i - c_k|^2,   L = (1/N) sum_i |x_i - c_{a_i}|^2,
+ *   c_k <- mean of the x_i with a_i = k (a centroid without points keeps its value).
+ * loss_hist[hist_len + k] receives L at the centroids that ENTER iteration k.  HOST struct; the
+ * arrays are DEVICE and owned by the caller. */
+typedef struct {
+    const float *X;         /* [N, D] row-major fp32, 16-byte aligned                           */
+    float       *C;         /* [K, D] centroids, in/out, 16-byte aligned                        */
+    int32_t     *assign;    /* [N] out: a_i of the last iteration run                           */
+    int32_t     *counts;    /* [K] out: cluster sizes of the last iteration run                 */
+    float       *loss_hist; /* [hist_cap]                                                       */
+    int64_t      N;         /* 1 <= N < 2^31                                                    */
+    int32_t      D;         /* multiple of 4, 4 <= D <= 1024                                    */
+    int32_t      K;         /* 1 <= K <= 1024                                                   */
+    int64_t      hist_len, hist_cap;
+} glm_kmeans_job_t;
+
+/* Workspace bytes for glm_kmeans_step on this shape (reads N, D, K only). */
+int glm_kmeans_workspace_bytes(const glm_kmeans_job_t *job /*HOST*/, size_t *out_bytes /*HOST*/);
+
+/* `iters` K-Means iterations, enqueued on hip_stream; returns without synchronising.  The
+ * products x_i . c_k run on the matrix cores in fp32; the nearest centroid is decided on
+ * |c_k|^2 - 2 x_i . c_k in fp32, so where two centroids are equally near to within fp32 rounding
+ * either may be chosen; the squared distance that enters L is recomputed from the definition.
+ * Sums use a fixed order (no floating-point atomics in global memory): reruns are bit-identical.
+ * Errors: GLM_EINVAL for bad pointers, alignment or shapes, GLM_ENOSPC if ws_bytes or the
+ * history capacity is too small, GLM_EHIP if a launch fails; nothing is enqueued on
+ * GLM_EINVAL / GLM_ENOSPC. */
+int glm_kmeans_step(glm_kmeans_job_t *job /*HOST*/, int32_t iters, void *ws /*DEVICE*/, size_t ws_bytes,
+                    void *hip_stream);
+
 /* ---- Sparse data ------------------------------------------------------------------------ */
 
 /* A job whose X is sparse (the paper's text and LIBSVM-style data sets, Sec. 3 "Setup").  The

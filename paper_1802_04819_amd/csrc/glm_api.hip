@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "glm_internal.h"
+#include "kmeans_internal.h"
 
 namespace slaqglm {
 
@@ -391,6 +392,70 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
         hipEvent_t *ev = nullptr;
         if (g_prof.on && g_prof.used < g_prof.cap) { ev = &g_prof.ev[2 * g_prof.used]; g_prof.used += 1; }
         if (launch_sparse_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
+    }
+    job->hist_len += iters;
+    return GLM_OK;
+}
+
+namespace {
+struct KmLayout { size_t cn, lossP, part, cntP, total; KmShape s; };
+KmLayout make_kmeans_layout(long long N, int D, int K) {
+    KmLayout L;
+    L.s = km_shape(N, D, K);
+    size_t off = 0;
+    L.cn = off;    off = align_up(off + sizeof(float) * (size_t)L.s.Kp);
+    L.lossP = off; off = align_up(off + sizeof(float) * (size_t)L.s.T);
+    L.part = off;  off = align_up(off + sizeof(float) * (size_t)L.s.P * K * D);
+    L.cntP = off;  off = align_up(off + sizeof(int) * (size_t)L.s.P * K);
+    L.total = off;
+    return L;
+}
+int validate_kmeans_shape(const glm_kmeans_job_t &j) {
+    if (j.N < 1 || j.N >= (1LL << 31)) return GLM_EINVAL;
+    if (j.D < 4 || j.D > kKmMaxD || (j.D & 3)) return GLM_EINVAL;
+    if (j.K < 1 || j.K > kKmMaxK) return GLM_EINVAL;
+    return GLM_OK;
+}
+}  // namespace
+
+int glm_kmeans_workspace_bytes(const glm_kmeans_job_t *job, size_t *out_bytes) {
+    if (!job || !out_bytes) return GLM_EINVAL;
+    if (validate_kmeans_shape(*job) != GLM_OK) return GLM_EINVAL;
+    *out_bytes = make_kmeans_layout(job->N, job->D, job->K).total;
+    return GLM_OK;
+}
+
+int glm_kmeans_step(glm_kmeans_job_t *job, int32_t iters, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!job || iters < 0) return GLM_EINVAL;
+    const glm_kmeans_job_t &j = *job;
+    if (validate_kmeans_shape(j) != GLM_OK) return GLM_EINVAL;
+    if (!j.X || !j.C || !j.assign || !j.counts || !j.loss_hist) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(j.X) & 15u) || (reinterpret_cast<uintptr_t>(j.C) & 15u)) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(j.assign) & 3u) || (reinterpret_cast<uintptr_t>(j.counts) & 3u) ||
+        (reinterpret_cast<uintptr_t>(j.loss_hist) & 3u))
+        return GLM_EINVAL;
+    if (j.hist_len < 0 || j.hist_cap < 0 || j.hist_len > j.hist_cap) return GLM_EINVAL;
+    if (j.hist_len + (int64_t)iters > j.hist_cap) return GLM_ENOSPC;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    const KmLayout L = make_kmeans_layout(j.N, j.D, j.K);
+    if (ws_bytes < L.total) return GLM_ENOSPC;
+    if (iters == 0) return GLM_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(ws);
+    KmArgs a;
+    a.X = j.X; a.C = j.C; a.assign = j.assign; a.counts = j.counts; a.loss_out = j.loss_hist + j.hist_len;
+    a.N = j.N; a.D = j.D; a.K = j.K;
+    a.cn = reinterpret_cast<float *>(base + L.cn); a.lossP = reinterpret_cast<float *>(base + L.lossP);
+    a.part = reinterpret_cast<float *>(base + L.part); a.cntP = reinterpret_cast<int *>(base + L.cntP);
+    a.s = L.s;
+    for (int k = 0; k < iters; ++k) {
+        hipEvent_t *ev = nullptr;
+        if (g_prof.on && g_prof.used + 2 <= g_prof.cap) {
+            ev = &g_prof.ev[2 * g_prof.used];
+            g_prof.used += 2;
+        }
+        if (launch_kmeans_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
     }
     job->hist_len += iters;
     return GLM_OK;

@@ -1,0 +1,366 @@
+// K-Means (Lloyd) iteration for gfx950.
+//
+//   norms      : cn[k] = |c_k|^2 (fp32), +inf for the padding slots past K.
+//   assign     : per tile of TR points held in LDS, the products x_i . c_k for 64 centroids at a
+//                time on the matrix cores (v_mfma_f32_32x32x2_f32, fp32 in, fp32 accumulate);
+//                the nearest centroid minimises cn[k] - 2 x_i . c_k (the |x_i|^2 term is common
+//                to all k), lowest index on equal values.  The squared distance that enters the
+//                loss is then recomputed for the chosen centroid as sum_j (x_ij - c_kj)^2, which
+//                has no cancellation.  Writes assign[i] and one loss partial per tile.
+//   accumulate : second pass over X.  A wave owns a slab of 64 columns, a contiguous range of
+//                rows and up to 32 clusters, keeps their sums in registers and adds the rows
+//                assigned to them in row order.  Partials go to part[split].
+//   finalize   : per centroid, adds the partials in split order (fp64), divides by the cluster
+//                size (an empty cluster keeps its centroid), and sums the loss partials.
+//
+// Lane layout of the 32x32x2 instruction (lane l of 64): A[i][k] from lane i + 32 k,
+// B[k][j] from lane j + 32 k, D[i][j] in lane j + 32 ((i / 4) % 2), register (i % 4) + 4 (i / 8).
+#include "kmeans_internal.h"
+
+#include <limits>
+
+namespace slaqglm {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWLd4 = 9;                   // LDS row stride of the centroid piece in float4 (32 + 4 floats)
+constexpr size_t kLdsBudget = 150 * 1024;  // of the 160 KB of a compute unit
+
+static size_t assign_lds_bytes(int TR, int Dp) {
+    return sizeof(f4) * ((size_t)TR * (Dp / 4 + 1) + kKmChunk * kWLd4) + sizeof(int) * TR + sizeof(float) * 8;
+}
+
+KmShape km_shape(long long N, int D, int K) {
+    KmShape s;
+    s.Dp = (D + 31) / 32 * 32;
+    s.Kp = (K + kKmChunk - 1) / kKmChunk * kKmChunk;
+    s.TR = 128;
+    while (s.TR > 32 && assign_lds_bytes(s.TR, s.Dp) > kLdsBudget) s.TR /= 2;
+    s.T = (N + s.TR - 1) / s.TR;
+    s.lds_assign = assign_lds_bytes(s.TR, s.Dp);
+    s.nslab = (D + 63) / 64;
+    s.G = (K + 31) / 32;
+    // row splits: at most 1024, at least 1024 rows each, and at most 1 GiB of partial sums
+    long long pmax = 1024;
+    const long long cap = (1LL << 28) / ((long long)K * D);
+    if (pmax > cap) pmax = cap < 1 ? 1 : cap;
+    long long rps = (N + pmax - 1) / pmax;
+    if (rps < 1024) rps = 1024;
+    rps = (rps + 63) / 64 * 64;
+    s.rows_per_split = rps;
+    s.P = (int)((N + rps - 1) / rps);
+    return s;
+}
+
+__device__ __forceinline__ floatx16 km_mfma(float a, float b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(256) void kmeans_norms_kernel(const float *__restrict__ C, int D, int K, int Kp,
+                                                           float *__restrict__ cn) {
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (k >= Kp) return;
+    float s = 0.0f;
+    if (k < K)
+        for (int j = lane; j < D; j += 64) {
+            const float c = C[(size_t)k * D + j];
+            s = __builtin_fmaf(c, c, s);
+        }
+    for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) cn[k] = k < K ? s : std::numeric_limits<float>::infinity();
+}
+
+template <int TR>
+__global__ __launch_bounds__(TR * 2) void kmeans_assign_kernel(
+    const float *__restrict__ X, const float *__restrict__ C, const float *__restrict__ cn, long long N, int D,
+    int K, int Dp, int Kp, int *__restrict__ assign, float *__restrict__ lossP) {
+    constexpr int NT = TR * 2;             // threads: one wave per 32 rows
+    constexpr int NW = TR / 32;
+    constexpr int Q = kKmChunk * 8 / NT;   // float4 of a 64 x 32 centroid piece staged per thread
+    extern __shared__ f4 km_smem[];
+    const int ldx4 = Dp / 4 + 1;           // odd stride in float4: rows fall in different banks
+    f4 *Xs4 = km_smem;                     // [TR][ldx4]
+    f4 *Ws4 = Xs4 + (size_t)TR * ldx4;     // [64][9]
+    int *rowk = reinterpret_cast<int *>(Ws4 + kKmChunk * kWLd4);   // [TR]
+    float *wsum = reinterpret_cast<float *>(rowk + TR);            // [NW]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, lh = lane >> 5;
+    const long long r0 = (long long)blockIdx.x * TR;
+    const int D4 = D >> 2, Dp4 = Dp >> 2;
+    const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X);
+    const f4 *__restrict__ C4 = reinterpret_cast<const f4 *>(C);
+
+    // the tile of points, zero beyond D and beyond N
+    for (int idx = tid; idx < TR * Dp4; idx += NT) {
+        const int row = idx / Dp4, c4 = idx - row * Dp4;
+        const long long r = r0 + row;
+        f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (r < N && c4 < D4) v = __builtin_nontemporal_load(X4 + r * D4 + c4);
+        Xs4[row * ldx4 + c4] = v;
+    }
+
+    const int nK = Dp / 32, nC = Kp / kKmChunk;
+    const int steps = nC * nK;
+    floatx16 acc0 = {0}, acc1 = {0};
+    float bv[16]; int bk[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { bv[r] = std::numeric_limits<float>::infinity(); bk[r] = 0; }
+
+    // piece (c, kc) = centroids 64 c .. 64 c + 63, columns 32 kc .. 32 kc + 31; slots outside
+    // [K, D] read a valid address and are multiplied by zero
+#define SLAQ_KM_FETCH(CC, KC)                                                                \
+    {                                                                                        \
+        _Pragma("unroll") for (int q = 0; q < Q; ++q) {                                      \
+            const int idx = tid + NT * q;                                                    \
+            const int cent = (CC) * kKmChunk + (idx >> 3);                                   \
+            const int col4 = (KC) * 8 + (idx & 7);                                           \
+            const bool ok = cent < K && col4 < D4;                                           \
+            wm[q] = ok ? 1.0f : 0.0f;                                                        \
+            wr[q] = C4[(size_t)(cent < K ? cent : 0) * D4 + (col4 < D4 ? col4 : 0)];         \
+        }                                                                                    \
+    }
+#define SLAQ_KM_STASH()                                                                      \
+    {                                                                                        \
+        _Pragma("unroll") for (int q = 0; q < Q; ++q) {                                      \
+            const int idx = tid + NT * q;                                                    \
+            Ws4[(idx >> 3) * kWLd4 + (idx & 7)] = wr[q] * wm[q];                             \
+        }                                                                                    \
+    }
+    {
+        f4 wr[Q]; float wm[Q];
+        SLAQ_KM_FETCH(0, 0)
+        SLAQ_KM_STASH()
+    }
+    __syncthreads();
+
+    int c = 0, kc = 0;
+    for (int step = 0; step < steps; ++step) {
+        int c2 = c, kc2 = kc + 1;
+        if (kc2 == nK) { kc2 = 0; c2 = c + 1; }
+        if (step + 1 >= steps) { c2 = c; kc2 = kc; }    // last trip re-reads its own piece (cache hit)
+        f4 wr[Q]; float wm[Q];
+        SLAQ_KM_FETCH(c2, kc2)
+        __builtin_amdgcn_sched_barrier(0);              // keep the prefetch ahead of the matrix ops
+        const f4 *arow = Xs4 + (wave * 32 + li) * ldx4 + kc * 8 + lh;
+        const f4 *b0row = Ws4 + li * kWLd4 + lh;
+        const f4 *b1row = Ws4 + (32 + li) * kWLd4 + lh;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {                // 8 columns: lanes lh = 0 take 0..3, lh = 1 take 4..7
+            const f4 a = arow[2 * kb];
+            const f4 b0 = b0row[2 * kb];
+            const f4 b1 = b1row[2 * kb];
+            acc0 = km_mfma(a.x, b0.x, acc0); acc1 = km_mfma(a.x, b1.x, acc1);
+            acc0 = km_mfma(a.y, b0.y, acc0); acc1 = km_mfma(a.y, b1.y, acc1);
+            acc0 = km_mfma(a.z, b0.z, acc0); acc1 = km_mfma(a.z, b1.z, acc1);
+            acc0 = km_mfma(a.w, b0.w, acc0); acc1 = km_mfma(a.w, b1.w, acc1);
+        }
+        if (kc == nK - 1) {
+            // chunk c is complete: this lane holds centroids 64 c + li (acc0) and 64 c + 32 + li
+            // (acc1) for 16 of the wave's rows; chunks arrive in increasing index order and the
+            // comparisons are strict, so equal values keep the lower index
+            const int k0 = c * kKmChunk + li, k1 = k0 + 32;
+            const float cn0 = cn[k0], cn1 = cn[k1];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float v0 = __builtin_fmaf(-2.0f, acc0[r], cn0);
+                const float v1 = __builtin_fmaf(-2.0f, acc1[r], cn1);
+                if (v0 < bv[r]) { bv[r] = v0; bk[r] = k0; }
+                if (v1 < bv[r]) { bv[r] = v1; bk[r] = k1; }
+                acc0[r] = 0.0f; acc1[r] = 0.0f;
+            }
+        }
+        __syncthreads();
+        SLAQ_KM_STASH()
+        __syncthreads();
+        c = c2; kc = kc2;
+    }
+#undef SLAQ_KM_FETCH
+#undef SLAQ_KM_STASH
+
+    // nearest centroid of each row: minimum over the 32 lanes that share lh, lower index on ties
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float v = bv[r]; int k = bk[r];
+#pragma unroll
+        for (int o = 1; o <= 16; o <<= 1) {
+            const float ov = __shfl_xor(v, o, 64);
+            const int ok = __shfl_xor(k, o, 64);
+            if (ov < v || (ov == v && ok < k)) { v = ov; k = ok; }
+        }
+        if (li == 0) rowk[wave * 32 + 8 * (r >> 2) + 4 * lh + (r & 3)] = k;
+    }
+    __syncthreads();
+
+    // squared distance to the chosen centroid, straight from the definition; two threads per row
+    const int row = tid >> 1, half = tid & 1;
+    const int a = rowk[row];
+    float d = 0.0f;
+    for (int j4 = half * (Dp4 / 2); j4 < (half + 1) * (Dp4 / 2); ++j4) {
+        const f4 x = Xs4[row * ldx4 + j4];
+        f4 cc = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (j4 < D4) cc = C4[(size_t)a * D4 + j4];
+        const f4 t = x - cc;
+        d = __builtin_fmaf(t.x, t.x, d); d = __builtin_fmaf(t.y, t.y, d);
+        d = __builtin_fmaf(t.z, t.z, d); d = __builtin_fmaf(t.w, t.w, d);
+    }
+    d = d + __shfl_xor(d, 1, 64);
+    const bool valid = r0 + row < N;
+    if (half == 0 && valid) assign[r0 + row] = a;
+    float v = (half == 0 && valid) ? d : 0.0f;
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    if (lane == 0) wsum[wave] = v;
+    __syncthreads();
+    if (tid == 0) {
+        float s = wsum[0];
+        for (int w = 1; w < NW; ++w) s += wsum[w];
+        lossP[blockIdx.x] = s;
+    }
+}
+
+// One wave = (row split p, slab of 64 columns, owner group w).  Cluster k belongs to group k % G
+// and is that group's local cluster k / G (< 32); a wave keeps the sums of its 32 local clusters
+// for its column in registers and reads from X only the rows assigned to them, in row order, so
+// every sum has a fixed order and no two waves add into the same place.  The cluster index of a
+// row is wave-uniform, hence the register array is indexed by a scalar.
+typedef float floatx32 __attribute__((ext_vector_type(32)));
+constexpr int kAccJ = 8;                   // rows gathered per round
+
+__global__ __launch_bounds__(256) void kmeans_accumulate_kernel(
+    const float *__restrict__ X, const int *__restrict__ assign, long long N, int D, int K, int G, int nslab,
+    long long rows_per_split, long long total_waves, float *__restrict__ part, int *__restrict__ cntP) {
+    const int lane = threadIdx.x & 63;
+    const long long wg = blockIdx.x * 4LL + (threadIdx.x >> 6);
+    if (wg >= total_waves) return;
+    const int w = (int)(wg % G);
+    const long long t = wg / G;
+    const int slab = (int)(t % nslab);
+    const long long p = t / nslab;
+    const int col = slab * 64 + lane;
+    const bool active = col < D;
+    const long long rb = p * rows_per_split;
+    const long long re = rb + rows_per_split < N ? rb + rows_per_split : N;
+    const float *__restrict__ xc = X + (active ? col : 0);
+
+    floatx32 acc = {0};
+    int size = 0;                          // lane l counts the rows of local cluster l
+    for (long long r = rb; r < re; r += 64) {
+        const long long row = r + lane;
+        const int av = row < re ? assign[row] : -1;
+        const int local = av / G;
+        unsigned long long mask = __ballot(av >= 0 && av - local * G == w);
+        while (mask) {
+            float v[kAccJ]; int a[kAccJ];
+#pragma unroll
+            for (int j = 0; j < kAccJ; ++j) {
+                a[j] = -1; v[j] = 0.0f;
+                if (mask) {
+                    const int u = __builtin_ctzll(mask);
+                    mask &= mask - 1;
+                    a[j] = __builtin_amdgcn_readlane(local, u);
+                    v[j] = __builtin_nontemporal_load(xc + (r + u) * D);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kAccJ; ++j)
+                if (a[j] >= 0) {
+                    acc[a[j]] += v[j];
+                    size += lane == a[j] ? 1 : 0;
+                }
+        }
+    }
+#pragma unroll
+    for (int l = 0; l < 32; ++l) {
+        const int k = l * G + w;
+        if (k < K && active) part[((size_t)p * K + k) * D + col] = acc[l];
+    }
+    if (slab == 0 && lane < 32 && lane * G + w < K) cntP[(size_t)p * K + lane * G + w] = size;
+}
+
+__global__ __launch_bounds__(256) void kmeans_finalize_kernel(
+    const float *__restrict__ part, const int *__restrict__ cntP, const float *__restrict__ lossP, long long T,
+    int P, long long N, int D, int K, float *__restrict__ C, int *__restrict__ counts, float *__restrict__ loss_out) {
+    __shared__ int redi[256];
+    __shared__ double redd[256];
+    const int k = blockIdx.x, tid = threadIdx.x;
+    int n = 0;
+    for (int p = tid; p < P; p += 256) n += cntP[(size_t)p * K + k];
+    redi[tid] = n;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if (tid < s) redi[tid] += redi[tid + s];
+        __syncthreads();
+    }
+    const int size = redi[0];
+    if (tid == 0) counts[k] = size;
+    for (int d = tid; d < D; d += 256) {
+        const float *__restrict__ pp = part + (size_t)k * D + d;
+        const size_t stride = (size_t)K * D;
+        double tot = 0.0;
+        int p = 0;
+        for (; p + 16 <= P; p += 16) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = pp[(size_t)(p + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) tot += (double)v[u];
+        }
+        for (; p < P; ++p) tot += (double)pp[(size_t)p * stride];
+        if (size > 0) C[(size_t)k * D + d] = (float)(tot / (double)size);
+    }
+    if (k == 0) {
+        // loss: thread t adds a contiguous run of the tile partials, then a fixed tree
+        double s = 0.0;
+        for (long long t = T * tid / 256; t < T * (tid + 1) / 256; ++t) s += (double)lossP[t];
+        redd[tid] = s;
+        __syncthreads();
+        for (int h = 128; h >= 1; h >>= 1) {
+            if (tid < h) redd[tid] += redd[tid + h];
+            __syncthreads();
+        }
+        if (tid == 0) *loss_out = (float)(redd[0] / (double)N);
+    }
+}
+
+template <int TR>
+static hipError_t launch_assign(const KmArgs &a, hipStream_t st) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&kmeans_assign_kernel<TR>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.s.lds_assign);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kmeans_assign_kernel<TR>, dim3((unsigned)a.s.T), dim3(TR * 2), a.s.lds_assign, st, a.X, a.C,
+                       a.cn, a.N, a.D, a.K, a.s.Dp, a.s.Kp, a.assign, a.lossP);
+    return hipGetLastError();
+}
+
+hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipStream_t st) {
+    hipError_t e;
+    int dev = 0, lds_max = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev)) != hipSuccess) return e;
+    if ((size_t)lds_max < a.s.lds_assign) return hipErrorInvalidValue;
+
+    hipLaunchKernelGGL(kmeans_norms_kernel, dim3((unsigned)((a.s.Kp + 3) / 4)), dim3(256), 0, st, a.C, a.D, a.K,
+                       a.s.Kp, a.cn);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
+    if (a.s.TR == 128) e = launch_assign<128>(a, st);
+    else if (a.s.TR == 64) e = launch_assign<64>(a, st);
+    else e = launch_assign<32>(a, st);
+    if (e != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
+    const long long waves = (long long)a.s.P * a.s.nslab * a.s.G;
+    hipLaunchKernelGGL(kmeans_accumulate_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, a.X, a.assign,
+                       a.N, a.D, a.K, a.s.G, a.s.nslab, a.s.rows_per_split, waves, a.part, a.cntP);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
+    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((unsigned)a.K), dim3(256), 0, st, a.part, a.cntP, a.lossP, a.s.T,
+                       a.s.P, a.N, a.D, a.K, a.C, a.counts, a.loss_out + k);
+    return hipGetLastError();
+}
+
+}  // namespace slaqglm

@@ -1,0 +1,40 @@
+// Internal declarations of the K-Means iteration (kmeans.hip, driven from glm_api.hip).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace slaqglm {
+
+constexpr int kKmMaxD = 1024;           // the X tile of the assignment kernel must fit in LDS
+constexpr int kKmMaxK = 1024;           // 32 owner groups of 32 clusters in the accumulation pass
+constexpr int kKmChunk = 64;            // centroids per matrix-core chunk
+
+// Shapes derived from (N, D, K) alone, so that every call on the same problem runs the same
+// launches and adds in the same order.
+struct KmShape {
+    int TR;              // rows per assignment tile (128, 64 or 32)
+    int Dp;              // D rounded up to a multiple of 32
+    long long T;         // assignment tiles
+    int Kp;              // K rounded up to a multiple of 64
+    int nslab;           // accumulation slabs of 64 columns
+    int G;               // owner groups of the accumulation pass: cluster k belongs to group k % G
+    long long rows_per_split;
+    int P;               // row splits of the accumulation kernel
+    size_t lds_assign;
+};
+KmShape km_shape(long long N, int D, int K);
+
+struct KmArgs {
+    const float *X; float *C; int *assign; int *counts; float *loss_out;
+    long long N; int D, K;
+    float *cn;           // [Kp] squared centroid norms, +inf past K
+    float *lossP;        // [T]  per-tile sums of the squared distances
+    float *part;         // [P, K, D] per-split column sums
+    int *cntP;           // [P, K]    per-split cluster sizes
+    KmShape s;
+};
+hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipStream_t st);
+
+}  // namespace slaqglm

@@ -24,6 +24,7 @@ EXPORTS = (
     "glm_read_probe_sink_floats", "glm_profile_begin", "glm_profile_end", "glm_strerror",
     "glm_predict_batched", "glm_predict_workspace_bytes", "glm_allocate_greedy",
     "glm_sparse_workspace_bytes", "glm_step_sparse",
+    "glm_kmeans_workspace_bytes", "glm_kmeans_step",
 )
 GLM_CURVE_SUBLINEAR, GLM_CURVE_LINEAR = 1, 2
 
@@ -48,6 +49,16 @@ class glm_sparse_job_t(ctypes.Structure):
         ("loss_hist", ctypes.c_void_p),
         ("N", ctypes.c_int64), ("D", ctypes.c_int64), ("nnz", ctypes.c_int64),
         ("loss", ctypes.c_int32), ("lambda_", ctypes.c_float), ("step", ctypes.c_float),
+        ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64),
+    ]
+
+
+class glm_kmeans_job_t(ctypes.Structure):
+    """Mirror of the C struct glm_kmeans_job_t."""
+    _fields_ = [
+        ("X", ctypes.c_void_p), ("C", ctypes.c_void_p), ("assign", ctypes.c_void_p),
+        ("counts", ctypes.c_void_p), ("loss_hist", ctypes.c_void_p),
+        ("N", ctypes.c_int64), ("D", ctypes.c_int32), ("K", ctypes.c_int32),
         ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64),
     ]
 
@@ -107,6 +118,11 @@ def load():
     lib.glm_sparse_workspace_bytes.argtypes = [sjp, ctypes.POINTER(sz)]
     lib.glm_step_sparse.restype = ctypes.c_int
     lib.glm_step_sparse.argtypes = [sjp, ctypes.c_int32, vp, sz, vp]
+    kjp = ctypes.POINTER(glm_kmeans_job_t)
+    lib.glm_kmeans_workspace_bytes.restype = ctypes.c_int
+    lib.glm_kmeans_workspace_bytes.argtypes = [kjp, ctypes.POINTER(sz)]
+    lib.glm_kmeans_step.restype = ctypes.c_int
+    lib.glm_kmeans_step.argtypes = [kjp, ctypes.c_int32, vp, sz, vp]
     lib.glm_strerror.restype = ctypes.c_char_p
     lib.glm_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -288,6 +304,48 @@ def glm_step_sparse(job: SparseJob, iters: int, ws: torch.Tensor, stream=None) -
     _require_gpu()
     _check(load().glm_step_sparse(ctypes.byref(job.c), int(iters), ctypes.c_void_p(ws.data_ptr()), ws.numel(),
                                   _stream_handle(stream)), "glm_step_sparse")
+
+
+class KMeansJob:
+    """A glm_kmeans_job_t plus the tensors it points at."""
+
+    def __init__(self, X: torch.Tensor, C: torch.Tensor, hist_cap: int):
+        for t in (X, C):
+            if t.dtype != torch.float32 or not t.is_contiguous() or t.dim() != 2:
+                raise TypeError("X and C must be contiguous 2-D float32 tensors")
+        if X.shape[1] != C.shape[1]:
+            raise ValueError("X and C differ in the number of columns")
+        N, D, K = int(X.shape[0]), int(X.shape[1]), int(C.shape[0])
+        dev = X.device
+        self.X, self.C = X, C
+        self.assign = torch.zeros(N, dtype=torch.int32, device=dev)
+        self.counts = torch.zeros(K, dtype=torch.int32, device=dev)
+        self.loss_hist = torch.zeros(max(int(hist_cap), 1), dtype=torch.float32, device=dev)
+        self.c = glm_kmeans_job_t(X.data_ptr(), C.data_ptr(), self.assign.data_ptr(), self.counts.data_ptr(),
+                                  self.loss_hist.data_ptr(), N, D, K, 0, int(hist_cap))
+
+    @property
+    def hist_len(self) -> int:
+        return int(self.c.hist_len)
+
+    def history(self) -> torch.Tensor:
+        return self.loss_hist[: self.hist_len]
+
+
+def glm_kmeans_workspace_bytes(job: KMeansJob) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().glm_kmeans_workspace_bytes(ctypes.byref(job.c), ctypes.byref(out)), "glm_kmeans_workspace_bytes")
+    return int(out.value)
+
+
+def alloc_kmeans_workspace(job: KMeansJob) -> torch.Tensor:
+    return torch.empty(max(glm_kmeans_workspace_bytes(job), 256), dtype=torch.uint8, device=job.X.device)
+
+
+def glm_kmeans_step(job: KMeansJob, iters: int, ws: torch.Tensor, stream=None) -> None:
+    _require_gpu()
+    _check(load().glm_kmeans_step(ctypes.byref(job.c), int(iters), ctypes.c_void_p(ws.data_ptr()), ws.numel(),
+                                  _stream_handle(stream)), "glm_kmeans_step")
 
 
 def glm_predict_batched(jobs: Sequence[Job], curve, gamma: float, window: int, horizon: int,

@@ -148,3 +148,22 @@ def test_sparse_config_full_size_steps():
             assert np.max(np.abs(got_g - g)) <= REL_TOL * np.max(np.abs(g))
     h = job.history().cpu().numpy()
     assert abs(h[0] - np.log(2.0)) < 2e-6 and np.all(np.diff(h) < 0)
+
+
+def test_kmeans_config_full_size_steps():
+    _say("[case] K-Means configuration full size: 4e6 x 128, 256 centroids, 5 iterations")
+    from test_gpu_kmeans import check_kmeans_step
+    p = synth.kmeans_config(device="cuda")
+    assert p.N == 4_000_000 and p.D == 128 and p.K == 256
+    job = glm.KMeansJob(p.X, p.C0.clone(), 5)
+    ws = glm.alloc_kmeans_workspace(job)
+    Xn = p.X.cpu().numpy()
+    for k in range(5):
+        C_in = job.C.cpu().numpy().copy() if k in (0, 4) else None
+        glm.glm_kmeans_step(job, 1, ws)
+        torch.cuda.synchronize()
+        if C_in is not None:
+            _say(f"[case] K-Means full size: oracle at iterate {k}")
+            check_kmeans_step(Xn, C_in, job, k, f"kmeans full k={k}")
+    h = job.history().cpu().numpy()
+    assert np.all(np.diff(h) < 0)

@@ -1,0 +1,191 @@
+"""GPU parity of the K-Means iteration against the fp64 oracle.
+
+Every iteration is checked at the very fp32 centroids it started from: the loss to rel 1e-4, the
+cluster sizes exactly against the library's own assignments, the assignments exactly wherever the
+oracle's margin between the nearest and the second-nearest centroid exceeds what fp32 rounding of
+|c|^2 - 2 x.c can move, and as valid near-ties elsewhere; the updated centroids to 1e-4 of the
+data scale (plus the shift a near-tie row can cause).
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1802_04819_amd import glm, synth
+from _parity import REL_TOL, rel
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _job(X, C0, cap):
+    job = glm.KMeansJob(X.cuda().contiguous(), C0.cuda().contiguous().clone(), cap)
+    return job, glm.alloc_kmeans_workspace(job)
+
+
+def check_kmeans_step(Xn, C_in32, job, k, tag):
+    """One iteration that started from C_in32 (the library's fp32 centroids) against the oracle."""
+    C_in = C_in32.astype(np.float64)
+    L, C_new, a_ref, cnt_ref = oracle.kmeans_step(Xn, C_in)
+    _, best, second = oracle.kmeans_assign(Xn, C_in)
+    a = job.assign.cpu().numpy()
+    cnt = job.counts.cpu().numpy()
+    K = C_in.shape[0]
+    assert a.min() >= 0 and a.max() < K, tag
+    assert np.array_equal(cnt, np.bincount(a, minlength=K)), tag       # sizes are exact integers
+    got_L = job.loss_hist[k].item()
+    assert rel(got_L, L) <= REL_TOL or abs(got_L - L) <= 1e-6 * float(np.abs(Xn).max()) ** 2, (tag, got_L, L)
+    # assignments
+    X64 = Xn.astype(np.float64)
+    xx = (X64 ** 2).sum(1)
+    slack = 1e-5 * (xx + (C_in ** 2).sum(1).max())
+    diff = np.nonzero(a != a_ref)[0]
+    if K > 1:
+        clear = (second - best) > slack
+        assert np.array_equal(a[clear], a_ref[clear]), (tag, "clear-cut assignment differs")
+    for i in diff:                                                     # near-ties: the choice must be as good
+        d_i = ((X64[i] - C_in[a[i]]) ** 2).sum()
+        assert d_i <= best[i] + slack[i], (tag, i, d_i, best[i])
+    assert len(diff) <= max(2, Xn.shape[0] // 1000), (tag, len(diff))
+    # centroids
+    C_got = job.C.cpu().numpy().astype(np.float64)
+    scale = max(float(np.abs(C_new).max()), 1e-30)
+    span = 2.0 * float(np.abs(X64).max())
+    moved = np.zeros(K)
+    for i in diff:
+        moved[a[i]] += 1; moved[a_ref[i]] += 1
+    tol = REL_TOL * scale + moved * span / np.maximum(cnt_ref, 1)
+    err = np.abs(C_got - C_new).max(axis=1)
+    assert np.all(err <= tol), (tag, int(np.argmax(err - tol)), err.max())
+    empty = cnt_ref == 0
+    if empty.any() and not len(diff):
+        assert np.array_equal(C_got[empty].astype(np.float32), C_in32[empty]), (tag, "empty cluster moved")
+    return len(diff)
+
+
+def run_checked(p, iters, tag):
+    Xn = p.X.numpy() if p.X.device.type == "cpu" else p.X.cpu().numpy()
+    job, ws = _job(p.X, p.C0, iters)
+    for k in range(iters):
+        C_in = job.C.cpu().numpy().copy()
+        glm.glm_kmeans_step(job, 1, ws)
+        torch.cuda.synchronize()
+        check_kmeans_step(Xn, C_in, job, k, f"{tag} k={k}")
+    return job
+
+
+SHAPES = [
+    # N, D, K: tiles, ragged tails, every tile height and slab width
+    (5000, 128, 64), (4097, 32, 7), (300, 4, 3), (2500, 36, 65), (1111, 260, 20), (700, 1024, 9),
+    (6000, 64, 300), (3000, 16, 1024), (129, 8, 1), (64, 128, 64),
+]
+
+
+@pytest.mark.parametrize("N,D,K", SHAPES)
+def test_each_iteration_matches_oracle(N, D, K):
+    _say(f"[case] kmeans per-step parity N={N} D={D} K={K}")
+    p = synth.make_kmeans(N, D, min(K, N), seed=N + D + K, blobs=max(2, min(K, 40)))
+    run_checked(p, 4, f"N={N} D={D} K={K}")
+
+
+def test_trajectory_matches_oracle_trajectory():
+    _say("[case] kmeans trajectory 20000 x 48, K = 12, 15 iterations")
+    p = synth.make_kmeans(20000, 48, 12, seed=5)
+    job, ws = _job(p.X, p.C0, 15)
+    glm.glm_kmeans_step(job, 15, ws)
+    torch.cuda.synchronize()
+    hist, C_end, a_end, cnt_end = oracle.kmeans_run(p.X.numpy(), p.C0.numpy(), 15)
+    got = job.history().cpu().numpy()
+    for k in range(15):
+        assert rel(got[k], hist[k]) <= REL_TOL, (k, got[k], hist[k])
+    assert np.all(np.diff(got) <= 1e-6 * got[0])
+    assert np.abs(job.C.cpu().numpy() - C_end).max() <= 1e-3 * np.abs(C_end).max()
+    assert np.mean(job.assign.cpu().numpy() == a_end) > 0.999
+
+
+def test_shifted_data_keeps_the_loss_accurate():
+    _say("[case] kmeans on data far from the origin (|x|^2 >> cluster spread)")
+    p = synth.make_kmeans(8000, 32, 10, seed=9, offset=40.0)
+    run_checked(p, 3, "offset 40")
+
+
+def test_duplicate_centroids_empty_clusters_and_exact_ties():
+    _say("[case] kmeans degenerate centroids")
+    p = synth.make_kmeans(3000, 16, 6, seed=2)
+    C0 = p.C0.clone()
+    C0[3] = C0[1]                          # identical centroids: the lower index takes every point
+    C0[5] = 1000.0                         # far away: stays empty and must not move
+    job, ws = _job(p.X, C0, 2)
+    C_in = job.C.cpu().numpy().copy()
+    glm.glm_kmeans_step(job, 1, ws)
+    torch.cuda.synchronize()
+    check_kmeans_step(p.X.numpy(), C_in, job, 0, "degenerate")
+    cnt = job.counts.cpu().numpy()
+    assert cnt[3] == 0 and cnt[5] == 0 and cnt.sum() == 3000
+    assert not (job.assign.cpu().numpy() == 3).any()
+    assert torch.equal(job.C[5].cpu(), C0[5]) and torch.equal(job.C[3].cpu(), C0[3])
+
+
+def test_every_point_its_own_centroid():
+    _say("[case] kmeans K = N: zero loss, nothing moves")
+    p = synth.make_kmeans(200, 12, 200, seed=4)
+    X = p.X
+    job, ws = _job(X, X.clone(), 2)
+    glm.glm_kmeans_step(job, 2, ws)
+    torch.cuda.synchronize()
+    assert job.history().cpu().tolist() == [0.0, 0.0]
+    assert job.assign.cpu().tolist() == list(range(200))
+    assert torch.equal(job.C.cpu(), X)
+
+
+def test_reruns_bit_identical_and_split_calls():
+    _say("[case] kmeans rerun determinism and 3 + 4 iterations = 7")
+    p = synth.make_kmeans(50000, 64, 33, seed=8)
+    outs = []
+    for split in ((7,), (7,), (3, 4)):
+        job, ws = _job(p.X, p.C0, 7)
+        for n in split:
+            glm.glm_kmeans_step(job, n, ws)
+        torch.cuda.synchronize()
+        outs.append((job.history().cpu().clone(), job.C.cpu().clone(), job.assign.cpu().clone(), job.counts.cpu().clone()))
+    for o in outs[1:]:
+        for x, y in zip(outs[0], o):
+            assert torch.equal(x, y)
+
+
+def test_kmeans_errors():
+    _say("[case] kmeans error codes")
+    p = synth.make_kmeans(1000, 16, 4, seed=1)
+    job, ws = _job(p.X, p.C0, 2)
+    lib = glm.load()
+    wsp, wsn = ctypes.c_void_p(ws.data_ptr()), ws.numel()
+
+    def call(j, iters=1, w=wsp, n=wsn):
+        return lib.glm_kmeans_step(ctypes.byref(j), iters, w, n, None)
+
+    def variant(**kw):
+        c = glm.glm_kmeans_job_t.from_buffer_copy(job.c)
+        for k, v in kw.items():
+            setattr(c, k, v)
+        return c
+    assert call(variant(D=18)) == glm.GLM_EINVAL
+    assert call(variant(D=2048)) == glm.GLM_EINVAL
+    assert call(variant(K=0)) == glm.GLM_EINVAL
+    assert call(variant(K=2000)) == glm.GLM_EINVAL
+    assert call(variant(N=0)) == glm.GLM_EINVAL
+    assert call(variant(X=job.X.data_ptr() + 4)) == glm.GLM_EINVAL
+    assert call(variant(C=None)) == glm.GLM_EINVAL
+    assert call(variant(), iters=-1) == glm.GLM_EINVAL
+    assert call(variant(), iters=3) == glm.GLM_ENOSPC
+    assert call(variant(), n=wsn - 257) == glm.GLM_ENOSPC
+    assert call(variant(), w=ctypes.c_void_p(ws.data_ptr() + 16)) == glm.GLM_EINVAL
+    assert call(variant(), iters=0) == glm.GLM_OK
+    out = ctypes.c_size_t()
+    assert lib.glm_kmeans_workspace_bytes(None, ctypes.byref(out)) == glm.GLM_EINVAL
+    torch.cuda.synchronize()
+    assert job.hist_len == 0 and torch.equal(job.C.cpu(), p.C0)          # nothing was enqueued
