@@ -33,10 +33,11 @@ static size_t assign_lds_bytes(int TR, int Dp) {
 
 KmShape km_shape(long long N, int D, int K) {
     KmShape s;
-    s.Dp = (D + 31) / 32 * 32;
+    s.split = D <= kKmSplitMaxD;
+    s.Dp = s.split ? (D + 63) / 64 * 64 : (D + 31) / 32 * 32;
     s.Kp = (K + kKmChunk - 1) / kKmChunk * kKmChunk;
     s.TR = 128;
-    while (s.TR > 32 && assign_lds_bytes(s.TR, s.Dp) > kLdsBudget) s.TR /= 2;
+    while (!s.split && s.TR > 32 && assign_lds_bytes(s.TR, s.Dp) > kLdsBudget) s.TR /= 2;
     s.T = (N + s.TR - 1) / s.TR;
     s.lds_assign = assign_lds_bytes(s.TR, s.Dp);
     s.nslab = (D + 63) / 64;
@@ -222,6 +223,227 @@ __global__ __launch_bounds__(TR * 2) void kmeans_assign_kernel(
     }
 }
 
+// ---- Assignment with split operands (D <= 128) ---------------------------------------------
+//
+// An fp32 value is the exact sum of three bfloat16 values (8 + 8 + 8 significant bits, same
+// exponent range), x = xh + xm + xl.  The product x . c is then the sum of nine bfloat16 products,
+// of which the six largest (xh ch, xm ch, xh cm, xl ch, xm cm, xh cl) carry everything down to
+// 2^-24 relative: the same accuracy class as an fp32 dot product.  Each of them is exact in fp32
+// and accumulates in fp32 on the matrix cores with v_mfma_f32_32x32x16_bf16, whose rate is 16
+// times that of the fp32 instruction, so the six cost 3/8 of one fp32 product.
+// Lane layout of the instruction (checked on the device): A[i][8 g .. 8 g + 7] in lane i + 32 g,
+// B[8 g .. 8 g + 7][j] in lane j + 32 g, D as for the other 32x32 variants.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSpK = 64;                   // columns per staged piece
+constexpr int kSpRowB = 2 * kSpK + 16;     // bytes per centroid row of a piece in LDS (padded)
+constexpr int kSpArrB = kKmChunk * kSpRowB;          // one of the three split arrays of a piece
+constexpr int kSpBufB = 3 * kSpArrB;                 // a piece
+
+// bfloat16 bit patterns (in the high halves) of the three parts of x
+__device__ __forceinline__ void split3(float x, unsigned &h, unsigned &m, unsigned &l) {
+    h = __float_as_uint(x) & 0xFFFF0000u;
+    const float r = x - __uint_as_float(h);            // exact
+    m = __float_as_uint(r) & 0xFFFF0000u;
+    const float r2 = r - __uint_as_float(m);           // exact, at most 8 significant bits
+    l = __float_as_uint(r2) & 0xFFFF0000u;
+}
+
+// Cs[part][k][j] (bfloat16 bits), part = 0, 1, 2; zero for k >= K or j >= D
+__global__ __launch_bounds__(256) void kmeans_split_kernel(const float *__restrict__ C, int D, int K, int Kp, int Dp,
+                                                           unsigned short *__restrict__ Cs) {
+    const long long idx = blockIdx.x * 256LL + threadIdx.x;
+    if (idx >= (long long)Kp * Dp) return;
+    const int k = (int)(idx / Dp), j = (int)(idx - (long long)k * Dp);
+    const float c = (k < K && j < D) ? C[(size_t)k * D + j] : 0.0f;
+    unsigned h, m, l;
+    split3(c, h, m, l);
+    const size_t plane = (size_t)Kp * Dp;
+    Cs[idx] = (unsigned short)(h >> 16);
+    Cs[plane + idx] = (unsigned short)(m >> 16);
+    Cs[2 * plane + idx] = (unsigned short)(l >> 16);
+}
+
+__device__ __forceinline__ floatx16 km_mfma_bf16(u4 a, u4 b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// NKP = pieces of 64 columns per centroid chunk (Dp = 64 NKP).  128 rows per block, 32 per wave,
+// held in registers as split operands for the whole kernel.
+template <int NKP>
+__global__ __launch_bounds__(256, 2) void kmeans_assign_split_kernel(
+    const float *__restrict__ X, const float *__restrict__ C, const unsigned short *__restrict__ Cs,
+    const float *__restrict__ cn, long long N, int D, int K, int Kp, int *__restrict__ assign,
+    float *__restrict__ lossP) {
+    constexpr int Dp = kSpK * NKP;
+    constexpr int NS = 4 * NKP;            // 16-column steps
+    __shared__ __attribute__((aligned(16))) unsigned char Ws[2 * kSpBufB];
+    __shared__ int rowk[128];
+    __shared__ float wsum[4];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, g = lane >> 5;
+    const long long r0 = (long long)blockIdx.x * 128;
+    const long long myrow = r0 + wave * 32 + li;
+    const int D4 = D >> 2;
+    const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X);
+    const f4 *__restrict__ C4 = reinterpret_cast<const f4 *>(C);
+
+    // this lane's part of its row: columns 16 s + 8 g .. + 7 for every step s, split three ways
+    u4 xa[NS][3];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        float x[8];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int c4 = 4 * s + 2 * g + q;
+            f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (myrow < N && c4 < D4) v = __builtin_nontemporal_load(X4 + myrow * D4 + c4);
+            x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            unsigned h0, m0, l0, h1, m1, l1;
+            split3(x[2 * e], h0, m0, l0);
+            split3(x[2 * e + 1], h1, m1, l1);
+            unsigned wh = (h0 >> 16) | h1, wm = (m0 >> 16) | m1, wl = (l0 >> 16) | l1;
+            // only the packed words stay live: the optimiser must not keep the fp32 values around
+            // for the distance pass at the end (they are rebuilt there from the words)
+            asm volatile("" : "+v"(wh), "+v"(wm), "+v"(wl));
+            xa[s][0][e] = wh; xa[s][1][e] = wm; xa[s][2][e] = wl;
+        }
+    }
+
+    const int nC = Kp / kKmChunk;
+    const int steps = nC * NKP;
+    const u4 *__restrict__ Cs16 = reinterpret_cast<const u4 *>(Cs);       // 8 bfloat16 per element
+    const size_t plane16 = (size_t)Kp * Dp / 8;
+    // piece (c, kp): for each split array, centroids 64 c .. + 63, columns 64 kp .. + 63:
+    // 3 x 64 x 8 elements of 16 bytes = 1536, six per thread
+#define SLAQ_SP_FETCH(STEP)                                                                  \
+    {                                                                                        \
+        const int c_ = (STEP) / NKP, kp_ = (STEP) - c_ * NKP;                                \
+        _Pragma("unroll") for (int q = 0; q < 6; ++q) {                                      \
+            const int idx = tid + 256 * q;                                                   \
+            const int arr = idx >> 9, rem = idx & 511;                                       \
+            wr[q] = Cs16[arr * plane16 + ((size_t)(c_ * kKmChunk + (rem >> 3)) * Dp + kp_ * kSpK) / 8 + (rem & 7)]; \
+        }                                                                                    \
+    }
+#define SLAQ_SP_STASH(BUF)                                                                   \
+    {                                                                                        \
+        _Pragma("unroll") for (int q = 0; q < 6; ++q) {                                      \
+            const int idx = tid + 256 * q;                                                   \
+            const int arr = idx >> 9, rem = idx & 511;                                       \
+            *reinterpret_cast<u4 *>(Ws + (BUF) * kSpBufB + arr * kSpArrB + (rem >> 3) * kSpRowB + (rem & 7) * 16) = wr[q]; \
+        }                                                                                    \
+    }
+    floatx16 acc0 = {0}, acc1 = {0};
+    float bv[16]; int bk[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { bv[r] = std::numeric_limits<float>::infinity(); bk[r] = 0; }
+
+    u4 wr[6];
+    SLAQ_SP_FETCH(0)
+    SLAQ_SP_STASH(0)
+    if (steps > 1) SLAQ_SP_FETCH(1)
+    __syncthreads();
+    for (int c = 0; c < nC; ++c) {
+#pragma unroll
+        for (int kp = 0; kp < NKP; ++kp) {
+            const int step = c * NKP + kp;
+            const int cur = step & 1;
+            // the other buffer was last read in the previous step, which every wave has left
+            if (step + 1 < steps) SLAQ_SP_STASH(cur ^ 1)
+            if (step + 2 < steps) SLAQ_SP_FETCH(step + 2)
+            __builtin_amdgcn_sched_barrier(0);
+            const unsigned char *b0 = Ws + cur * kSpBufB + li * kSpRowB + g * 16;
+            const unsigned char *b1 = b0 + 32 * kSpRowB;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const int s = kp * 4 + ks;
+                const u4 ch0 = *reinterpret_cast<const u4 *>(b0 + ks * 32);
+                const u4 cm0 = *reinterpret_cast<const u4 *>(b0 + kSpArrB + ks * 32);
+                const u4 cl0 = *reinterpret_cast<const u4 *>(b0 + 2 * kSpArrB + ks * 32);
+                const u4 ch1 = *reinterpret_cast<const u4 *>(b1 + ks * 32);
+                const u4 cm1 = *reinterpret_cast<const u4 *>(b1 + kSpArrB + ks * 32);
+                const u4 cl1 = *reinterpret_cast<const u4 *>(b1 + 2 * kSpArrB + ks * 32);
+                // smallest terms first
+                acc0 = km_mfma_bf16(xa[s][0], cl0, acc0); acc1 = km_mfma_bf16(xa[s][0], cl1, acc1);
+                acc0 = km_mfma_bf16(xa[s][1], cm0, acc0); acc1 = km_mfma_bf16(xa[s][1], cm1, acc1);
+                acc0 = km_mfma_bf16(xa[s][2], ch0, acc0); acc1 = km_mfma_bf16(xa[s][2], ch1, acc1);
+                acc0 = km_mfma_bf16(xa[s][0], cm0, acc0); acc1 = km_mfma_bf16(xa[s][0], cm1, acc1);
+                acc0 = km_mfma_bf16(xa[s][1], ch0, acc0); acc1 = km_mfma_bf16(xa[s][1], ch1, acc1);
+                acc0 = km_mfma_bf16(xa[s][0], ch0, acc0); acc1 = km_mfma_bf16(xa[s][0], ch1, acc1);
+            }
+            if (kp == NKP - 1) {
+                const int k0 = c * kKmChunk + li, k1 = k0 + 32;
+                const float cn0 = cn[k0], cn1 = cn[k1];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v0 = __builtin_fmaf(-2.0f, acc0[r], cn0);
+                    const float v1 = __builtin_fmaf(-2.0f, acc1[r], cn1);
+                    if (v0 < bv[r]) { bv[r] = v0; bk[r] = k0; }
+                    if (v1 < bv[r]) { bv[r] = v1; bk[r] = k1; }
+                    acc0[r] = 0.0f; acc1[r] = 0.0f;
+                }
+            }
+            __syncthreads();
+        }
+    }
+#undef SLAQ_SP_FETCH
+#undef SLAQ_SP_STASH
+
+    // nearest centroid of each row: minimum over the 32 lanes that share g, lower index on ties
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float v = bv[r]; int k = bk[r];
+#pragma unroll
+        for (int o = 1; o <= 16; o <<= 1) {
+            const float ov = __shfl_xor(v, o, 64);
+            const int ok = __shfl_xor(k, o, 64);
+            if (ov < v || (ov == v && ok < k)) { v = ov; k = ok; }
+        }
+        if (li == 0) rowk[wave * 32 + 8 * (r >> 2) + 4 * g + (r & 3)] = k;
+    }
+    __syncthreads();
+
+    // squared distance to the chosen centroid from the definition; x is rebuilt exactly from its
+    // three parts, the lane pair (i, 0), (i, 1) shares row i
+    const int a = rowk[wave * 32 + li];
+    float d = 0.0f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const unsigned h = xa[s][0][e], m = xa[s][1][e], l = xa[s][2][e];
+            x[2 * e] = (__uint_as_float(h << 16) + __uint_as_float(m << 16)) + __uint_as_float(l << 16);
+            x[2 * e + 1] = (__uint_as_float(h & 0xFFFF0000u) + __uint_as_float(m & 0xFFFF0000u)) +
+                           __uint_as_float(l & 0xFFFF0000u);
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int c4 = 4 * s + 2 * g + q;
+            f4 cc = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (c4 < D4) cc = C4[(size_t)a * D4 + c4];
+            const float t0 = x[4 * q] - cc.x, t1 = x[4 * q + 1] - cc.y, t2 = x[4 * q + 2] - cc.z, t3 = x[4 * q + 3] - cc.w;
+            d = __builtin_fmaf(t0, t0, d); d = __builtin_fmaf(t1, t1, d);
+            d = __builtin_fmaf(t2, t2, d); d = __builtin_fmaf(t3, t3, d);
+        }
+    }
+    d = d + __shfl_xor(d, 32, 64);
+    const bool valid = myrow < N;
+    if (g == 0 && valid) assign[myrow] = a;
+    float v = (g == 0 && valid) ? d : 0.0f;
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    if (lane == 0) wsum[wave] = v;
+    __syncthreads();
+    if (tid == 0) lossP[blockIdx.x] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+}
+
 // One wave = (row split p, slab of 64 columns, owner group w).  Cluster k belongs to group k % G
 // and is that group's local cluster k / G (< 32); a wave keeps the sums of its 32 local clusters
 // for its column in registers and reads from X only the rows assigned to them, in row order, so
@@ -346,8 +568,22 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
     hipLaunchKernelGGL(kmeans_norms_kernel, dim3((unsigned)((a.s.Kp + 3) / 4)), dim3(256), 0, st, a.C, a.D, a.K,
                        a.s.Kp, a.cn);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (a.s.split) {
+        const long long n = (long long)a.s.Kp * a.s.Dp;
+        hipLaunchKernelGGL(kmeans_split_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.C, a.D, a.K,
+                           a.s.Kp, a.s.Dp, a.Cs);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
-    if (a.s.TR == 128) e = launch_assign<128>(a, st);
+    if (a.s.split) {
+        if (a.s.Dp == 64)
+            hipLaunchKernelGGL(kmeans_assign_split_kernel<1>, dim3((unsigned)a.s.T), dim3(256), 0, st, a.X, a.C, a.Cs,
+                               a.cn, a.N, a.D, a.K, a.s.Kp, a.assign, a.lossP);
+        else
+            hipLaunchKernelGGL(kmeans_assign_split_kernel<2>, dim3((unsigned)a.s.T), dim3(256), 0, st, a.X, a.C, a.Cs,
+                               a.cn, a.N, a.D, a.K, a.s.Kp, a.assign, a.lossP);
+        e = hipGetLastError();
+    } else if (a.s.TR == 128) e = launch_assign<128>(a, st);
     else if (a.s.TR == 64) e = launch_assign<64>(a, st);
     else e = launch_assign<32>(a, st);
     if (e != hipSuccess) return e;

@@ -9,13 +9,15 @@ namespace slaqglm {
 
 constexpr int kKmMaxD = 1024;           // the X tile of the assignment kernel must fit in LDS
 constexpr int kKmMaxK = 1024;           // 32 owner groups of 32 clusters in the accumulation pass
+constexpr int kKmSplitMaxD = 128;       // up to here a row's split operands fit in a lane pair's registers
 constexpr int kKmChunk = 64;            // centroids per matrix-core chunk
 
 // Shapes derived from (N, D, K) alone, so that every call on the same problem runs the same
 // launches and adds in the same order.
 struct KmShape {
+    bool split;          // D <= 128: assignment with three-way bfloat16 operands
     int TR;              // rows per assignment tile (128, 64 or 32)
-    int Dp;              // D rounded up to a multiple of 32
+    int Dp;              // D rounded up to a multiple of 64 (split) or 32
     long long T;         // assignment tiles
     int Kp;              // K rounded up to a multiple of 64
     int nslab;           // accumulation slabs of 64 columns
@@ -30,6 +32,7 @@ struct KmArgs {
     const float *X; float *C; int *assign; int *counts; float *loss_out;
     long long N; int D, K;
     float *cn;           // [Kp] squared centroid norms, +inf past K
+    unsigned short *Cs;  // [3, Kp, Dp] bfloat16 parts of the centroids (split path)
     float *lossP;        // [T]  per-tile sums of the squared distances
     float *part;         // [P, K, D] per-split column sums
     int *cntP;           // [P, K]    per-split cluster sizes
