@@ -398,14 +398,15 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
 }
 
 namespace {
-struct KmLayout { size_t cn, Cs, lossP, part, cntP, total; KmShape s; };
+struct KmLayout { size_t cn, Cs, lossP, bestv, part, cntP, total; KmShape s; };
 KmLayout make_kmeans_layout(long long N, int D, int K) {
     KmLayout L;
     L.s = km_shape(N, D, K);
     size_t off = 0;
     L.cn = off;    off = align_up(off + sizeof(float) * (size_t)L.s.Kp);
     L.Cs = off;    off = align_up(off + sizeof(unsigned short) * 3 * (size_t)L.s.Kp * L.s.Dp);
-    L.lossP = off; off = align_up(off + sizeof(float) * (size_t)L.s.T);
+    L.lossP = off; off = align_up(off + sizeof(float) * (size_t)L.s.lossN);
+    L.bestv = off; off = align_up(off + (L.s.split && L.s.Kp > 256 ? sizeof(float) * (size_t)N : 0));
     L.part = off;  off = align_up(off + sizeof(float) * (size_t)L.s.P * K * D);
     L.cntP = off;  off = align_up(off + sizeof(int) * (size_t)L.s.P * K);
     L.total = off;
@@ -448,6 +449,7 @@ int glm_kmeans_step(glm_kmeans_job_t *job, int32_t iters, void *ws, size_t ws_by
     a.X = j.X; a.C = j.C; a.assign = j.assign; a.counts = j.counts; a.loss_out = j.loss_hist + j.hist_len;
     a.N = j.N; a.D = j.D; a.K = j.K;
     a.Cs = reinterpret_cast<unsigned short *>(base + L.Cs);
+    a.bestv = reinterpret_cast<float *>(base + L.bestv);
     a.cn = reinterpret_cast<float *>(base + L.cn); a.lossP = reinterpret_cast<float *>(base + L.lossP);
     a.part = reinterpret_cast<float *>(base + L.part); a.cntP = reinterpret_cast<int *>(base + L.cntP);
     a.s = L.s;

@@ -35,11 +35,15 @@ KmShape km_shape(long long N, int D, int K) {
     KmShape s;
     s.split = D <= kKmSplitMaxD;
     s.Dp = s.split ? (D + 63) / 64 * 64 : (D + 31) / 32 * 32;
-    s.Kp = (K + kKmChunk - 1) / kKmChunk * kKmChunk;
-    s.TR = 128;
+    s.Kp = s.split ? (K + 255) / 256 * 256 : (K + kKmChunk - 1) / kKmChunk * kKmChunk;
+    s.TR = s.split ? 32 : 128;
     while (!s.split && s.TR > 32 && assign_lds_bytes(s.TR, s.Dp) > kLdsBudget) s.TR /= 2;
     s.T = (N + s.TR - 1) / s.TR;
-    s.lds_assign = assign_lds_bytes(s.TR, s.Dp);
+    s.lds_assign = s.split ? 0 : assign_lds_bytes(s.TR, s.Dp);
+    // split path: a fixed grid of persistent blocks (one per compute unit), contiguous tile ranges
+    s.tiles_per_block = (s.T + 255) / 256;
+    s.stream_blocks = (int)((s.T + s.tiles_per_block - 1) / s.tiles_per_block);     // no block without tiles
+    s.lossN = s.split ? (long long)s.stream_blocks * 8 : s.T;
     s.nslab = (D + 63) / 64;
     s.G = (K + 31) / 32;
     // row splits: at most 1024, at least 1024 rows each, and at most 1 GiB of partial sums
@@ -269,179 +273,218 @@ __device__ __forceinline__ floatx16 km_mfma_bf16(u4 a, u4 b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// NKP = pieces of 64 columns per centroid chunk (Dp = 64 NKP).  128 rows per block, 32 per wave,
-// held in registers as split operands for the whole kernel.
+// The centroids stay put and the points stream: a block of 8 waves holds one group of 256
+// centroids (32 per wave, as split A operands in registers, for the whole kernel) and walks over
+// its share of the points in tiles of 32 rows.  The 512 threads load the next tile, split it and
+// store the three parts in LDS as B operands; every wave multiplies its 32 centroids with the 32
+// rows; the nearest centroid of a row is the minimum over a lane's 16 registers, its partner lane
+// and the 8 waves (through LDS).  One barrier per tile: the tile after the next is in flight
+// from HBM, the next tile is being written to LDS, and the distance of the previous tile's rows to
+// their chosen centroids (rebuilt exactly from the parts still in LDS) is computed while the
+// matrix cores work on the current one.  With more than 256 centroids the kernel runs once per
+// group and carries the best value and index of every row in global memory.
+// NKP = Dp / 64.
+constexpr int kStWaves = 8;
+constexpr int kStRows = 32;
+constexpr int kStGroup = 32 * kStWaves;    // centroids per launch
+
 template <int NKP>
-__global__ __launch_bounds__(256, 2) void kmeans_assign_split_kernel(
+__global__ __launch_bounds__(512) void kmeans_assign_stream_kernel(
     const float *__restrict__ X, const float *__restrict__ C, const unsigned short *__restrict__ Cs,
-    const float *__restrict__ cn, long long N, int D, int K, int Kp, int *__restrict__ assign,
-    float *__restrict__ lossP) {
+    const float *__restrict__ cn, long long N, int D, int Kp, int gbase, int first, int last,
+    long long tiles, long long tiles_per_block, int *__restrict__ assign, float *__restrict__ bestv,
+    float *__restrict__ lossW) {
     constexpr int Dp = kSpK * NKP;
     constexpr int NS = 4 * NKP;            // 16-column steps
-    __shared__ __attribute__((aligned(16))) unsigned char Ws[2 * kSpBufB];
-    __shared__ int rowk[128];
-    __shared__ float wsum[4];
+    constexpr int RowB = 2 * Dp + 16;      // bytes per row of one part in LDS (padded: rows fall in different banks)
+    constexpr int PartB = kStRows * RowB;
+    constexpr int BufB = 3 * PartB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char st_smem[];
+    unsigned char *Xb = st_smem;                                          // [4][BufB]
+    float2 *red = reinterpret_cast<float2 *>(st_smem + 4 * BufB);         // [2][8][32] (value, index bits)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, g = lane >> 5;
-    const long long r0 = (long long)blockIdx.x * 128;
-    const long long myrow = r0 + wave * 32 + li;
     const int D4 = D >> 2;
     const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X);
     const f4 *__restrict__ C4 = reinterpret_cast<const f4 *>(C);
+    const long long t0 = blockIdx.x * tiles_per_block;
+    const long long t1 = t0 + tiles_per_block < tiles ? t0 + tiles_per_block : tiles;
+    const int n = (int)(t1 - t0);
 
-    // this lane's part of its row: columns 16 s + 8 g .. + 7 for every step s, split three ways
-    u4 xa[NS][3];
+    // this wave's centroids as A operands: lane (li, g) holds columns 16 s + 8 g .. + 7 of centroid cbase + li
+    const int cbase = gbase + 32 * wave;
+    u4 ca[NS][3];
+    {
+        const u4 *__restrict__ Cs16 = reinterpret_cast<const u4 *>(Cs);
+        const size_t plane16 = (size_t)Kp * Dp / 8;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        float x[8];
+        for (int s = 0; s < NS; ++s)
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int c4 = 4 * s + 2 * g + q;
-            f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (myrow < N && c4 < D4) v = __builtin_nontemporal_load(X4 + myrow * D4 + c4);
-            x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            unsigned h0, m0, l0, h1, m1, l1;
-            split3(x[2 * e], h0, m0, l0);
-            split3(x[2 * e + 1], h1, m1, l1);
-            unsigned wh = (h0 >> 16) | h1, wm = (m0 >> 16) | m1, wl = (l0 >> 16) | l1;
-            // only the packed words stay live: the optimiser must not keep the fp32 values around
-            // for the distance pass at the end (they are rebuilt there from the words)
-            asm volatile("" : "+v"(wh), "+v"(wm), "+v"(wl));
-            xa[s][0][e] = wh; xa[s][1][e] = wm; xa[s][2][e] = wl;
-        }
+            for (int p = 0; p < 3; ++p) ca[s][p] = Cs16[p * plane16 + ((size_t)(cbase + li) * Dp + 16 * s + 8 * g) / 8];
     }
+    float cnr[16];                         // |c|^2 of the centroid behind accumulator register r
+#pragma unroll
+    for (int r = 0; r < 16; ++r) cnr[r] = cn[cbase + 8 * (r >> 2) + 4 * g + (r & 3)];
 
-    const int nC = Kp / kKmChunk;
-    const int steps = nC * NKP;
-    const u4 *__restrict__ Cs16 = reinterpret_cast<const u4 *>(Cs);       // 8 bfloat16 per element
-    const size_t plane16 = (size_t)Kp * Dp / 8;
-    // piece (c, kp): for each split array, centroids 64 c .. + 63, columns 64 kp .. + 63:
-    // 3 x 64 x 8 elements of 16 bytes = 1536, six per thread
-#define SLAQ_SP_FETCH(STEP)                                                                  \
+    // loader role: row lr of the tile, columns 8 seg .. + 7
+    const int lr = tid >> 4, seg = tid & 15;
+    const bool loads = seg < Dp / 8;
+    // distance role: row 4 wave + rl of the tile, columns 8 part .. + 7
+    const int rl = lane >> 4, part = lane & 15;
+    const int erow = 4 * wave + rl;
+
+#define SLAQ_ST_LOAD(T)                                                                      \
     {                                                                                        \
-        const int c_ = (STEP) / NKP, kp_ = (STEP) - c_ * NKP;                                \
-        _Pragma("unroll") for (int q = 0; q < 6; ++q) {                                      \
-            const int idx = tid + 256 * q;                                                   \
-            const int arr = idx >> 9, rem = idx & 511;                                       \
-            wr[q] = Cs16[arr * plane16 + ((size_t)(c_ * kKmChunk + (rem >> 3)) * Dp + kp_ * kSpK) / 8 + (rem & 7)]; \
+        const long long row_ = (T) * kStRows + lr;                                           \
+        xr0 = f4{0.0f, 0.0f, 0.0f, 0.0f}; xr1 = xr0;                                         \
+        if (loads && row_ < N) {                                                             \
+            if (2 * seg < D4) xr0 = __builtin_nontemporal_load(X4 + row_ * D4 + 2 * seg);    \
+            if (2 * seg + 1 < D4) xr1 = __builtin_nontemporal_load(X4 + row_ * D4 + 2 * seg + 1); \
         }                                                                                    \
     }
-#define SLAQ_SP_STASH(BUF)                                                                   \
-    {                                                                                        \
-        _Pragma("unroll") for (int q = 0; q < 6; ++q) {                                      \
-            const int idx = tid + 256 * q;                                                   \
-            const int arr = idx >> 9, rem = idx & 511;                                       \
-            *reinterpret_cast<u4 *>(Ws + (BUF) * kSpBufB + arr * kSpArrB + (rem >> 3) * kSpRowB + (rem & 7) * 16) = wr[q]; \
+#define SLAQ_ST_STASH(B)                                                                     \
+    if (loads) {                                                                             \
+        const float x_[8] = {xr0.x, xr0.y, xr0.z, xr0.w, xr1.x, xr1.y, xr1.z, xr1.w};        \
+        u4 wh_, wm_, wl_;                                                                    \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                      \
+            unsigned h0, m0, l0, h1, m1, l1;                                                 \
+            split3(x_[2 * e], h0, m0, l0);                                                   \
+            split3(x_[2 * e + 1], h1, m1, l1);                                               \
+            wh_[e] = (h0 >> 16) | h1; wm_[e] = (m0 >> 16) | m1; wl_[e] = (l0 >> 16) | l1;    \
+        }                                                                                    \
+        unsigned char *dst_ = Xb + (B) * BufB + lr * RowB + seg * 16;                        \
+        *reinterpret_cast<u4 *>(dst_) = wh_;                                                 \
+        *reinterpret_cast<u4 *>(dst_ + PartB) = wm_;                                         \
+        *reinterpret_cast<u4 *>(dst_ + 2 * PartB) = wl_;                                     \
+    }
+
+    // The four pieces of work of one trip i (between two barriers):
+    //   NEAREST(j): rows of tile j: minimum over the 8 waves' results (ascending index, strict),
+    //               merge with earlier centroid groups, start loading the chosen centroid
+    //   MATRIX(i) : tile i on the matrix cores, this wave's nearest centroid per row to LDS
+    //   DISTANCE(j): squared distance of tile j's rows to their centroids, from the definition
+    //   FEED(i)   : tile i + 1 into LDS, tile i + 2 from HBM
+    // None of them depends on another one of the same trip, so the two waves that share a SIMD
+    // run them in different orders: while one is on the matrix cores the other does vector work.
+#define SLAQ_ST_NEAREST(J)                                                                   \
+    if ((J) >= 0 && (J) < n) {                                                               \
+        const long long prow_ = (t0 + (J)) * kStRows + erow;                                 \
+        const float2 *rp_ = red + ((J) & 1) * (kStWaves * kStRows) + erow;                   \
+        float v_ = rp_[0].x; int k_ = __float_as_int(rp_[0].y);                              \
+        _Pragma("unroll") for (int w_ = 1; w_ < kStWaves; ++w_) {                            \
+            const float2 o_ = rp_[w_ * kStRows];                                             \
+            if (o_.x < v_) { v_ = o_.x; k_ = __float_as_int(o_.y); }                         \
+        }                                                                                    \
+        if (!first && prow_ < N) {          /* earlier groups hold lower indices: they win ties */ \
+            const float pv_ = bestv[prow_];                                                  \
+            if (pv_ <= v_) { v_ = pv_; k_ = assign[prow_]; }                                 \
+        }                                                                                    \
+        ek = k_;                                                                             \
+        if (!last) {                                                                         \
+            if (part == 0 && prow_ < N) { bestv[prow_] = v_; assign[prow_] = k_; }           \
+        } else {                                                                             \
+            ec0 = f4{0.0f, 0.0f, 0.0f, 0.0f}; ec1 = ec0;                                     \
+            if (2 * part < D4) ec0 = C4[(size_t)k_ * D4 + 2 * part];                         \
+            if (2 * part + 1 < D4) ec1 = C4[(size_t)k_ * D4 + 2 * part + 1];                 \
         }                                                                                    \
     }
-    floatx16 acc0 = {0}, acc1 = {0};
-    float bv[16]; int bk[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { bv[r] = std::numeric_limits<float>::infinity(); bk[r] = 0; }
+#define SLAQ_ST_MATRIX(I)                                                                    \
+    if ((I) < n) {                                                                           \
+        floatx16 accA = {0}, accB = {0};                                                     \
+        const unsigned char *bp_ = Xb + ((I) & 3) * BufB + li * RowB + g * 16;               \
+        _Pragma("unroll") for (int s_ = 0; s_ < NS; ++s_) {                                  \
+            const u4 xh_ = *reinterpret_cast<const u4 *>(bp_ + s_ * 32);                     \
+            const u4 xm_ = *reinterpret_cast<const u4 *>(bp_ + PartB + s_ * 32);             \
+            const u4 xl_ = *reinterpret_cast<const u4 *>(bp_ + 2 * PartB + s_ * 32);         \
+            accA = km_mfma_bf16(ca[s_][0], xl_, accA);                                       \
+            accB = km_mfma_bf16(ca[s_][1], xm_, accB);                                       \
+            accA = km_mfma_bf16(ca[s_][2], xh_, accA);                                       \
+            accB = km_mfma_bf16(ca[s_][0], xm_, accB);                                       \
+            accA = km_mfma_bf16(ca[s_][1], xh_, accA);                                       \
+            accB = km_mfma_bf16(ca[s_][0], xh_, accB);                                       \
+        }                                                                                    \
+        /* registers in ascending centroid order, then the partner lane */                   \
+        float v_ = std::numeric_limits<float>::infinity(); int k_ = cbase;                   \
+        _Pragma("unroll") for (int r_ = 0; r_ < 16; ++r_) {                                  \
+            const float val_ = __builtin_fmaf(-2.0f, accA[r_] + accB[r_], cnr[r_]);          \
+            if (val_ < v_) { v_ = val_; k_ = cbase + 8 * (r_ >> 2) + 4 * g + (r_ & 3); }     \
+        }                                                                                    \
+        const float ov_ = __shfl_xor(v_, 32, 64);                                            \
+        const int ok_ = __shfl_xor(k_, 32, 64);                                              \
+        if (ov_ < v_ || (ov_ == v_ && ok_ < k_)) { v_ = ov_; k_ = ok_; }                     \
+        if (g == 0) red[((I) & 1) * (kStWaves * kStRows) + wave * kStRows + li] = float2{v_, __int_as_float(k_)}; \
+    }
+#define SLAQ_ST_DISTANCE(J)                                                                  \
+    if (last && (J) >= 0 && (J) < n) {                                                       \
+        const long long prow_ = (t0 + (J)) * kStRows + erow;                                 \
+        const unsigned char *xp_ = Xb + ((J) & 3) * BufB + erow * RowB + part * 16;          \
+        u4 ph_ = {0, 0, 0, 0}, pm_ = ph_, pl_ = ph_;                                         \
+        if (part < Dp / 8) {                                                                 \
+            ph_ = *reinterpret_cast<const u4 *>(xp_);                                        \
+            pm_ = *reinterpret_cast<const u4 *>(xp_ + PartB);                                \
+            pl_ = *reinterpret_cast<const u4 *>(xp_ + 2 * PartB);                            \
+        }                                                                                    \
+        const float cc_[8] = {ec0.x, ec0.y, ec0.z, ec0.w, ec1.x, ec1.y, ec1.z, ec1.w};       \
+        float d_ = 0.0f;                                                                     \
+        _Pragma("unroll") for (int e_ = 0; e_ < 4; ++e_) {                                   \
+            const float xa0_ = (__uint_as_float(ph_[e_] << 16) + __uint_as_float(pm_[e_] << 16)) + __uint_as_float(pl_[e_] << 16); \
+            const float xa1_ = (__uint_as_float(ph_[e_] & 0xFFFF0000u) + __uint_as_float(pm_[e_] & 0xFFFF0000u)) + \
+                               __uint_as_float(pl_[e_] & 0xFFFF0000u);                       \
+            const float u0_ = xa0_ - cc_[2 * e_], u1_ = xa1_ - cc_[2 * e_ + 1];              \
+            d_ = __builtin_fmaf(u0_, u0_, d_); d_ = __builtin_fmaf(u1_, u1_, d_);            \
+        }                                                                                    \
+        _Pragma("unroll") for (int o_ = 1; o_ <= 8; o_ <<= 1) d_ += __shfl_xor(d_, o_, 64);  \
+        if (part == 0 && prow_ < N) { assign[prow_] = ek; dsum += d_; }                      \
+    }
+#define SLAQ_ST_FEED(I)                                                                      \
+    {                                                                                        \
+        if ((I) + 1 < n) SLAQ_ST_STASH(((I) + 1) & 3)                                        \
+        if ((I) + 2 < n) SLAQ_ST_LOAD(t0 + (I) + 2)                                          \
+    }
 
-    u4 wr[6];
-    SLAQ_SP_FETCH(0)
-    SLAQ_SP_STASH(0)
-    if (steps > 1) SLAQ_SP_FETCH(1)
+    f4 xr0, xr1;
+    float dsum = 0.0f;                     // this lane's rows, in tile order (distance role, part 0)
+    if (n > 0) {
+        SLAQ_ST_LOAD(t0)
+        SLAQ_ST_STASH(0)
+        if (n > 1) SLAQ_ST_LOAD(t0 + 1)
+    }
     __syncthreads();
-    for (int c = 0; c < nC; ++c) {
-#pragma unroll
-        for (int kp = 0; kp < NKP; ++kp) {
-            const int step = c * NKP + kp;
-            const int cur = step & 1;
-            // the other buffer was last read in the previous step, which every wave has left
-            if (step + 1 < steps) SLAQ_SP_STASH(cur ^ 1)
-            if (step + 2 < steps) SLAQ_SP_FETCH(step + 2)
-            __builtin_amdgcn_sched_barrier(0);
-            const unsigned char *b0 = Ws + cur * kSpBufB + li * kSpRowB + g * 16;
-            const unsigned char *b1 = b0 + 32 * kSpRowB;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const int s = kp * 4 + ks;
-                const u4 ch0 = *reinterpret_cast<const u4 *>(b0 + ks * 32);
-                const u4 cm0 = *reinterpret_cast<const u4 *>(b0 + kSpArrB + ks * 32);
-                const u4 cl0 = *reinterpret_cast<const u4 *>(b0 + 2 * kSpArrB + ks * 32);
-                const u4 ch1 = *reinterpret_cast<const u4 *>(b1 + ks * 32);
-                const u4 cm1 = *reinterpret_cast<const u4 *>(b1 + kSpArrB + ks * 32);
-                const u4 cl1 = *reinterpret_cast<const u4 *>(b1 + 2 * kSpArrB + ks * 32);
-                // smallest terms first
-                acc0 = km_mfma_bf16(xa[s][0], cl0, acc0); acc1 = km_mfma_bf16(xa[s][0], cl1, acc1);
-                acc0 = km_mfma_bf16(xa[s][1], cm0, acc0); acc1 = km_mfma_bf16(xa[s][1], cm1, acc1);
-                acc0 = km_mfma_bf16(xa[s][2], ch0, acc0); acc1 = km_mfma_bf16(xa[s][2], ch1, acc1);
-                acc0 = km_mfma_bf16(xa[s][0], cm0, acc0); acc1 = km_mfma_bf16(xa[s][0], cm1, acc1);
-                acc0 = km_mfma_bf16(xa[s][1], ch0, acc0); acc1 = km_mfma_bf16(xa[s][1], ch1, acc1);
-                acc0 = km_mfma_bf16(xa[s][0], ch0, acc0); acc1 = km_mfma_bf16(xa[s][0], ch1, acc1);
-            }
-            if (kp == NKP - 1) {
-                const int k0 = c * kKmChunk + li, k1 = k0 + 32;
-                const float cn0 = cn[k0], cn1 = cn[k1];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float v0 = __builtin_fmaf(-2.0f, acc0[r], cn0);
-                    const float v1 = __builtin_fmaf(-2.0f, acc1[r], cn1);
-                    if (v0 < bv[r]) { bv[r] = v0; bk[r] = k0; }
-                    if (v1 < bv[r]) { bv[r] = v1; bk[r] = k1; }
-                    acc0[r] = 0.0f; acc1[r] = 0.0f;
-                }
-            }
+
+    int ek = 0; f4 ec0 = {0.0f, 0.0f, 0.0f, 0.0f}, ec1 = ec0;      // distance role: chosen centroid and its columns
+    // In trip i the buffers of tiles i - 2, i - 1 and i are read and that of tile i + 1 is
+    // written: four buffers.  The results of tile i (red) are written in trip i and read in i + 1.
+    if (wave < kStWaves / 2) {
+        for (int i = 0; i <= n + 1; ++i) {
+            SLAQ_ST_DISTANCE(i - 2)        // its centroid was requested in the previous trip
+            SLAQ_ST_FEED(i)
+            SLAQ_ST_NEAREST(i - 1)
+            SLAQ_ST_MATRIX(i)
+            __syncthreads();
+        }
+    } else {
+        for (int i = 0; i <= n + 1; ++i) {
+            SLAQ_ST_NEAREST(i - 1)
+            SLAQ_ST_MATRIX(i)              // hides the latency of the centroid request
+            SLAQ_ST_DISTANCE(i - 1)
+            SLAQ_ST_FEED(i)
             __syncthreads();
         }
     }
-#undef SLAQ_SP_FETCH
-#undef SLAQ_SP_STASH
-
-    // nearest centroid of each row: minimum over the 32 lanes that share g, lower index on ties
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        float v = bv[r]; int k = bk[r];
-#pragma unroll
-        for (int o = 1; o <= 16; o <<= 1) {
-            const float ov = __shfl_xor(v, o, 64);
-            const int ok = __shfl_xor(k, o, 64);
-            if (ov < v || (ov == v && ok < k)) { v = ov; k = ok; }
-        }
-        if (li == 0) rowk[wave * 32 + 8 * (r >> 2) + 4 * g + (r & 3)] = k;
+#undef SLAQ_ST_NEAREST
+#undef SLAQ_ST_MATRIX
+#undef SLAQ_ST_DISTANCE
+#undef SLAQ_ST_FEED
+#undef SLAQ_ST_LOAD
+#undef SLAQ_ST_STASH
+    if (last) {
+        // the wave's four row lanes (part 0 of each quarter), fixed order
+        const float s0 = __shfl(dsum, 0, 64), s1 = __shfl(dsum, 16, 64), s2 = __shfl(dsum, 32, 64), s3 = __shfl(dsum, 48, 64);
+        if (lane == 0) lossW[blockIdx.x * kStWaves + wave] = ((s0 + s1) + s2) + s3;
     }
-    __syncthreads();
-
-    // squared distance to the chosen centroid from the definition; x is rebuilt exactly from its
-    // three parts, the lane pair (i, 0), (i, 1) shares row i
-    const int a = rowk[wave * 32 + li];
-    float d = 0.0f;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const unsigned h = xa[s][0][e], m = xa[s][1][e], l = xa[s][2][e];
-            x[2 * e] = (__uint_as_float(h << 16) + __uint_as_float(m << 16)) + __uint_as_float(l << 16);
-            x[2 * e + 1] = (__uint_as_float(h & 0xFFFF0000u) + __uint_as_float(m & 0xFFFF0000u)) +
-                           __uint_as_float(l & 0xFFFF0000u);
-        }
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int c4 = 4 * s + 2 * g + q;
-            f4 cc = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (c4 < D4) cc = C4[(size_t)a * D4 + c4];
-            const float t0 = x[4 * q] - cc.x, t1 = x[4 * q + 1] - cc.y, t2 = x[4 * q + 2] - cc.z, t3 = x[4 * q + 3] - cc.w;
-            d = __builtin_fmaf(t0, t0, d); d = __builtin_fmaf(t1, t1, d);
-            d = __builtin_fmaf(t2, t2, d); d = __builtin_fmaf(t3, t3, d);
-        }
-    }
-    d = d + __shfl_xor(d, 32, 64);
-    const bool valid = myrow < N;
-    if (g == 0 && valid) assign[myrow] = a;
-    float v = (g == 0 && valid) ? d : 0.0f;
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-    if (lane == 0) wsum[wave] = v;
-    __syncthreads();
-    if (tid == 0) lossP[blockIdx.x] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
 }
 
 // One wave = (row split p, slab of 64 columns, owner group w).  Cluster k belongs to group k % G
@@ -576,13 +619,23 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
     }
     if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
     if (a.s.split) {
-        if (a.s.Dp == 64)
-            hipLaunchKernelGGL(kmeans_assign_split_kernel<1>, dim3((unsigned)a.s.T), dim3(256), 0, st, a.X, a.C, a.Cs,
-                               a.cn, a.N, a.D, a.K, a.s.Kp, a.assign, a.lossP);
-        else
-            hipLaunchKernelGGL(kmeans_assign_split_kernel<2>, dim3((unsigned)a.s.T), dim3(256), 0, st, a.X, a.C, a.Cs,
-                               a.cn, a.N, a.D, a.K, a.s.Kp, a.assign, a.lossP);
-        e = hipGetLastError();
+        const size_t lds = (size_t)4 * 3 * kStRows * (2 * a.s.Dp + 16) + 2 * kStWaves * kStRows * sizeof(float2);
+        const void *fn = a.s.Dp == 64 ? reinterpret_cast<const void *>(&kmeans_assign_stream_kernel<1>)
+                                      : reinterpret_cast<const void *>(&kmeans_assign_stream_kernel<2>);
+        if ((e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
+        const int groups = a.s.Kp / kStGroup;
+        for (int gi = 0; gi < groups && e == hipSuccess; ++gi) {
+            const int first = gi == 0, last = gi == groups - 1;
+            if (a.s.Dp == 64)
+                hipLaunchKernelGGL(kmeans_assign_stream_kernel<1>, dim3((unsigned)a.s.stream_blocks), dim3(512), lds, st,
+                                   a.X, a.C, a.Cs, a.cn, a.N, a.D, a.s.Kp, gi * kStGroup, first, last, a.s.T,
+                                   a.s.tiles_per_block, a.assign, a.bestv, a.lossP);
+            else
+                hipLaunchKernelGGL(kmeans_assign_stream_kernel<2>, dim3((unsigned)a.s.stream_blocks), dim3(512), lds, st,
+                                   a.X, a.C, a.Cs, a.cn, a.N, a.D, a.s.Kp, gi * kStGroup, first, last, a.s.T,
+                                   a.s.tiles_per_block, a.assign, a.bestv, a.lossP);
+            e = hipGetLastError();
+        }
     } else if (a.s.TR == 128) e = launch_assign<128>(a, st);
     else if (a.s.TR == 64) e = launch_assign<64>(a, st);
     else e = launch_assign<32>(a, st);
@@ -594,7 +647,7 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
                        a.N, a.D, a.K, a.s.G, a.s.nslab, a.s.rows_per_split, waves, a.part, a.cntP);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
-    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((unsigned)a.K), dim3(256), 0, st, a.part, a.cntP, a.lossP, a.s.T,
+    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((unsigned)a.K), dim3(256), 0, st, a.part, a.cntP, a.lossP, a.s.lossN,
                        a.s.P, a.N, a.D, a.K, a.C, a.counts, a.loss_out + k);
     return hipGetLastError();
 }

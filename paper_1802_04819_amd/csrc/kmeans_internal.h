@@ -19,7 +19,10 @@ struct KmShape {
     int TR;              // rows per assignment tile (128, 64 or 32)
     int Dp;              // D rounded up to a multiple of 64 (split) or 32
     long long T;         // assignment tiles
-    int Kp;              // K rounded up to a multiple of 64
+    int stream_blocks;   // split path: persistent blocks
+    long long tiles_per_block;
+    long long lossN;     // loss partials written by the assignment kernel
+    int Kp;              // K rounded up to a multiple of 64 (256 on the split path)
     int nslab;           // accumulation slabs of 64 columns
     int G;               // owner groups of the accumulation pass: cluster k belongs to group k % G
     long long rows_per_split;
@@ -33,7 +36,8 @@ struct KmArgs {
     long long N; int D, K;
     float *cn;           // [Kp] squared centroid norms, +inf past K
     unsigned short *Cs;  // [3, Kp, Dp] bfloat16 parts of the centroids (split path)
-    float *lossP;        // [T]  per-tile sums of the squared distances
+    float *lossP;        // [lossN] partial sums of the squared distances
+    float *bestv;        // [N] best value so far (split path with more than 256 centroids)
     float *part;         // [P, K, D] per-split column sums
     int *cntP;           // [P, K]    per-split cluster sizes
     KmShape s;
