@@ -253,8 +253,8 @@ def bench_batched(args):
     return out
 
 
-MFMA_F32_PEAK_TFLOPS = 157.3
-MFMA_BF16_PEAK_TFLOPS = 2500.0    # MI355X published dense fp32 matrix rate
+MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X published dense fp32 matrix rate
+MFMA_BF16_PEAK_TFLOPS = 2500.0    # MI355X published dense bfloat16 matrix rate
 
 
 def bench_sweep(args):

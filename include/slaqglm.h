@@ -148,9 +148,11 @@ typedef struct {
 int glm_kmeans_workspace_bytes(const glm_kmeans_job_t *job /*HOST*/, size_t *out_bytes /*HOST*/);
 
 /* `iters` K-Means iterations, enqueued on hip_stream; returns without synchronising.  The
- * products x_i . c_k run on the matrix cores in fp32; the nearest centroid is decided on
- * |c_k|^2 - 2 x_i . c_k in fp32, so where two centroids are equally near to within fp32 rounding
- * either may be chosen; the squared distance that enters L is recomputed from the definition.
+ * products x_i . c_k run on the matrix cores with fp32-equivalent accuracy (for D <= 128 as six
+ * bfloat16 products of three-way split operands, else in fp32); the nearest centroid is decided
+ * on |c_k|^2 - 2 x_i . c_k in fp32, so where two centroids are equally near to within fp32
+ * rounding either may be chosen; the squared distance that enters L is recomputed from the
+ * definition.
  * Sums use a fixed order (no floating-point atomics in global memory): reruns are bit-identical.
  * Errors: GLM_EINVAL for bad pointers, alignment or shapes, GLM_ENOSPC if ws_bytes or the
  * history capacity is too small, GLM_EHIP if a launch fails; nothing is enqueued on
