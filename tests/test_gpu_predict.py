@@ -80,6 +80,7 @@ def _curves():
     out.append(("increasing", 1, 1.0 + 0.01 * k))
     out.append(("large offset", 1, 1e4 + 1.0 / (0.1 * k + 1.0)))
     out.append(("tiny scale", 2, 1e-6 * 0.8 ** k + 1e-7))
+    out.append(("largest change is an increase", 1, 1.0 / (0.01 * k + 0.5) + 2.0 + 4.0 * (k >= 3)))
     return out
 
 

@@ -17,6 +17,13 @@ def test_normalized_changes_hand_example():
     assert norm == 4.0
     nu, norm = so.normalized_changes([2.0, 2.0, 2.0])
     assert np.all(nu == 0) and norm == 0.0
+    # the largest change counts by magnitude, also when it is an increase
+    nu, norm = so.normalized_changes([5.0, 4.0, 8.0, 7.0])
+    np.testing.assert_allclose(nu, [1.0, -1.0, 0.25], rtol=1e-15)
+    assert norm == 4.0
+    pred, gain, fit = so.predict_job([5.0, 4.5, 9.0, 8.5, 8.1, 7.8, 7.6, 7.5], horizon=3)
+    prev = np.concatenate([[so.fitted_value_at_last(fit)], pred[:-1]])
+    np.testing.assert_allclose(gain, (prev - pred) / 4.5, rtol=1e-12)
 
 
 def test_first_normalized_change_is_one_and_values_stay_in_unit_interval():
