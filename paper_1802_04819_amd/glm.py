@@ -348,6 +348,17 @@ def glm_kmeans_step(job: KMeansJob, iters: int, ws: torch.Tensor, stream=None) -
                                   _stream_handle(stream)), "glm_kmeans_step")
 
 
+class HistoryView:
+    """The loss history of any job (dense, sparse or K-Means) in the shape the predictor reads:
+    a glm_job_t of which only loss_hist and hist_len are set."""
+
+    def __init__(self, job):
+        self.job = job
+        self.c = glm_job_t()
+        self.c.loss_hist = job.loss_hist.data_ptr()
+        self.c.hist_len = int(job.c.hist_len)
+
+
 def glm_predict_batched(jobs: Sequence[Job], curve, gamma: float, window: int, horizon: int,
                         pred: torch.Tensor, gain: torch.Tensor, fit: torch.Tensor,
                         ws: Optional[torch.Tensor] = None, stream=None) -> None:
