@@ -123,6 +123,35 @@ int glm_sweep(const float *X /*DEVICE*/, const float *y /*DEVICE*/, int64_t N, i
               const float *lambdas /*HOST*/, const float *steps /*HOST*/, int32_t iters,
               float *loss_hist /*DEVICE*/, void *ws /*DEVICE*/, size_t ws_bytes, void *hip_stream);
 
+/* ---- L-BFGS ----------------------------------------------------------------------------- */
+
+/* State of an L-BFGS run between calls (L-BFGS is the paper's example of a solver with linear or
+ * superlinear convergence, Sec. 2 "Predicting Quality Improvement").  HOST struct owned by the
+ * caller: zero it to start a run from job->w; keep it, the workspace and the job unchanged
+ * between calls to continue the run. */
+typedef struct {
+    int32_t started;  /* set by the library once the objective has been evaluated at job->w       */
+    int32_t memory;   /* curvature pairs kept, fixed by the first call                            */
+    int64_t evals;    /* evaluations of the objective so far; each is one pass over X             */
+    double  f;        /* loss at job->w                                                           */
+} glm_lbfgs_state_t;
+
+/* Workspace bytes for glm_lbfgs on this job with this memory (reads N, D only). */
+int glm_lbfgs_workspace_bytes(const glm_job_t *job /*HOST*/, int32_t memory, size_t *out_bytes /*HOST*/);
+
+/* `iters` L-BFGS iterations on the objective of glm_step (job->step is ignored): two-loop recursion
+ * over the last `memory` (0 .. 32) curvature pairs scaled by s.y / y.y of the newest, then a
+ * backtracking line search: the first trial step is 1 (min(1, 1/|g|) while no pair is stored) and is
+ * halved, at most 30 times, until f(w + a p) <= f(w) + 1e-4 a g.p + 1e-6 |f(w)|; a pair with
+ * s.y <= 1e-10 y.y is not stored.  Every evaluation is one row pass with step = 0.
+ * loss_hist[hist_len + k] receives the loss at the iterate that enters iteration k; job->w and
+ * job->grad are the current iterate and its gradient when the call returns.  The call synchronises
+ * with hip_stream once per evaluation (it reads the loss back to decide the line search).
+ * Errors as glm_step; GLM_EINVAL also for memory outside 0 .. 32 or a memory that differs from the
+ * one the run was started with. */
+int glm_lbfgs(glm_job_t *job /*HOST*/, glm_lbfgs_state_t *state /*HOST*/, int32_t iters, int32_t memory,
+              void *ws /*DEVICE*/, size_t ws_bytes, void *hip_stream);
+
 /* ---- K-Means ---------------------------------------------------------------------------- */
 
 /* A clustering job (K-Means is one of the unsupervised jobs of Sec. 3, "Setup"; it is an

@@ -8,6 +8,7 @@
 
 #include "glm_internal.h"
 #include "kmeans_internal.h"
+#include "lbfgs_internal.h"
 
 namespace slaqglm {
 
@@ -460,6 +461,110 @@ int glm_kmeans_step(glm_kmeans_job_t *job, int32_t iters, void *ws, size_t ws_by
             g_prof.used += 2;
         }
         if (launch_kmeans_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
+    }
+    job->hist_len += iters;
+    return GLM_OK;
+}
+
+namespace {
+struct LbLayout { size_t dense, S, Y, rho, yy, ring, p, wt, gt, scal, fslot, total; };
+LbLayout make_lbfgs_layout(const glm_job_t &job, int memory) {
+    LbLayout L;
+    const size_t D = (size_t)job.D, m = (size_t)memory;
+    size_t off = 0;
+    L.dense = off; off = align_up(off + make_layout(&job, 1).total);
+    L.S = off;     off = align_up(off + sizeof(float) * m * D);
+    L.Y = off;     off = align_up(off + sizeof(float) * m * D);
+    L.rho = off;   off = align_up(off + sizeof(double) * (m ? m : 1));
+    L.yy = off;    off = align_up(off + sizeof(double) * (m ? m : 1));
+    L.ring = off;  off = align_up(off + sizeof(int) * 2);
+    L.p = off;     off = align_up(off + sizeof(float) * D);
+    L.wt = off;    off = align_up(off + sizeof(float) * D);
+    L.gt = off;    off = align_up(off + sizeof(float) * D);
+    L.scal = off;  off = align_up(off + sizeof(double) * kLbScalars);
+    L.fslot = off; off = align_up(off + sizeof(float));
+    L.total = off;
+    return L;
+}
+
+// Pinned landing area for the scalars read back after every evaluation.
+struct LbHost { std::mutex mu; void *buf = nullptr; };
+LbHost g_lb;
+}  // namespace
+
+int glm_lbfgs_workspace_bytes(const glm_job_t *job, int32_t memory, size_t *out_bytes) {
+    if (!job || !out_bytes || memory < 0 || memory > kLbMaxMemory) return GLM_EINVAL;
+    if (validate_shape(job->N, job->D) != GLM_OK) return GLM_EINVAL;
+    *out_bytes = make_lbfgs_layout(*job, memory).total;
+    return GLM_OK;
+}
+
+int glm_lbfgs(glm_job_t *job, glm_lbfgs_state_t *state, int32_t iters, int32_t memory, void *ws, size_t ws_bytes,
+              void *hip_stream) {
+    if (!job || !state || iters < 0 || memory < 0 || memory > kLbMaxMemory) return GLM_EINVAL;
+    const int rc = validate_job(*job);
+    if (rc != GLM_OK) return rc;
+    if (state->started && state->memory != memory) return GLM_EINVAL;
+    if (job->hist_len + (int64_t)iters > job->hist_cap) return GLM_ENOSPC;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    const LbLayout L = make_lbfgs_layout(*job, memory);
+    if (ws_bytes < L.total) return GLM_ENOSPC;
+    if (iters == 0) return GLM_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(ws);
+    LbArgs a;
+    a.S = reinterpret_cast<float *>(base + L.S); a.Y = reinterpret_cast<float *>(base + L.Y);
+    a.rho = reinterpret_cast<double *>(base + L.rho); a.yy = reinterpret_cast<double *>(base + L.yy);
+    a.ring = reinterpret_cast<int *>(base + L.ring);
+    a.p = reinterpret_cast<float *>(base + L.p); a.wt = reinterpret_cast<float *>(base + L.wt);
+    a.gt = reinterpret_cast<float *>(base + L.gt);
+    a.scal = reinterpret_cast<double *>(base + L.scal); a.fslot = reinterpret_cast<float *>(base + L.fslot);
+    a.memory = memory; a.D = job->D;
+
+    std::lock_guard<std::mutex> lock(g_lb.mu);
+    if (!g_lb.buf && hipHostMalloc(&g_lb.buf, 256, hipHostMallocDefault) != hipSuccess) return GLM_EHIP;
+    float *h_f = static_cast<float *>(g_lb.buf);
+    double *h_scal = reinterpret_cast<double *>(static_cast<char *>(g_lb.buf) + 64);
+
+    // one evaluation: loss and gradient at w_at (step = 0 leaves w_at untouched), loss read back
+    auto evaluate = [&](float *w_at, float *g_out, bool with_scalars) -> int {
+        glm_job_t tmp = *job;
+        tmp.w = w_at; tmp.grad = g_out; tmp.loss_hist = a.fslot; tmp.hist_len = 0; tmp.hist_cap = 1; tmp.step = 0.0f;
+        const int one = 1;
+        if (run_rounds(&tmp, 1, &one, base + L.dense, st) != hipSuccess) return GLM_EHIP;
+        if (hipMemcpyAsync(h_f, a.fslot, sizeof(float), hipMemcpyDeviceToHost, st) != hipSuccess) return GLM_EHIP;
+        if (with_scalars &&
+            hipMemcpyAsync(h_scal, a.scal, sizeof(double) * kLbScalars, hipMemcpyDeviceToHost, st) != hipSuccess)
+            return GLM_EHIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return GLM_EHIP;
+        state->evals += 1;
+        return GLM_OK;
+    };
+
+    const bool fresh = !state->started;
+    if (fresh) {
+        const int e = evaluate(job->w, job->grad, false);
+        if (e != GLM_OK) return e;
+        state->f = (double)*h_f;
+        state->memory = memory;
+        state->started = 1;
+    }
+    for (int k = 0; k < iters; ++k) {
+        if (launch_lbfgs_direction(a, job->grad, fresh && k == 0, (float)state->f,
+                                   job->loss_hist + job->hist_len + k, st) != hipSuccess)
+            return GLM_EHIP;
+        double ft = state->f;
+        for (int h = 0; h <= 30; ++h) {
+            if (launch_lbfgs_trial(a, job->w, h, st) != hipSuccess) return GLM_EHIP;
+            const int e = evaluate(a.wt, a.gt, true);
+            if (e != GLM_OK) return e;
+            ft = (double)*h_f;
+            const double alpha = std::ldexp(h_scal[2], -h);
+            if (ft <= state->f + 1e-4 * alpha * h_scal[0] + 1e-6 * std::fabs(state->f) || h == 30) break;
+        }
+        if (launch_lbfgs_accept(a, job->w, job->grad, st) != hipSuccess) return GLM_EHIP;
+        state->f = ft;
     }
     job->hist_len += iters;
     return GLM_OK;

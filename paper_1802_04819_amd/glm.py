@@ -25,6 +25,7 @@ EXPORTS = (
     "glm_predict_batched", "glm_predict_workspace_bytes", "glm_allocate_greedy",
     "glm_sparse_workspace_bytes", "glm_step_sparse",
     "glm_kmeans_workspace_bytes", "glm_kmeans_step",
+    "glm_lbfgs_workspace_bytes", "glm_lbfgs",
 )
 GLM_CURVE_SUBLINEAR, GLM_CURVE_LINEAR = 1, 2
 
@@ -61,6 +62,12 @@ class glm_kmeans_job_t(ctypes.Structure):
         ("N", ctypes.c_int64), ("D", ctypes.c_int32), ("K", ctypes.c_int32),
         ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64),
     ]
+
+
+class glm_lbfgs_state_t(ctypes.Structure):
+    """Mirror of the C struct glm_lbfgs_state_t (zero-initialised = a new run)."""
+    _fields_ = [("started", ctypes.c_int32), ("memory", ctypes.c_int32), ("evals", ctypes.c_int64),
+                ("f", ctypes.c_double)]
 
 
 class GlmError(RuntimeError):
@@ -118,6 +125,11 @@ def load():
     lib.glm_sparse_workspace_bytes.argtypes = [sjp, ctypes.POINTER(sz)]
     lib.glm_step_sparse.restype = ctypes.c_int
     lib.glm_step_sparse.argtypes = [sjp, ctypes.c_int32, vp, sz, vp]
+    lib.glm_lbfgs_workspace_bytes.restype = ctypes.c_int
+    lib.glm_lbfgs_workspace_bytes.argtypes = [ctypes.POINTER(glm_job_t), ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.glm_lbfgs.restype = ctypes.c_int
+    lib.glm_lbfgs.argtypes = [ctypes.POINTER(glm_job_t), ctypes.POINTER(glm_lbfgs_state_t), ctypes.c_int32,
+                              ctypes.c_int32, vp, sz, vp]
     kjp = ctypes.POINTER(glm_kmeans_job_t)
     lib.glm_kmeans_workspace_bytes.restype = ctypes.c_int
     lib.glm_kmeans_workspace_bytes.argtypes = [kjp, ctypes.POINTER(sz)]
@@ -346,6 +358,23 @@ def glm_kmeans_step(job: KMeansJob, iters: int, ws: torch.Tensor, stream=None) -
     _require_gpu()
     _check(load().glm_kmeans_step(ctypes.byref(job.c), int(iters), ctypes.c_void_p(ws.data_ptr()), ws.numel(),
                                   _stream_handle(stream)), "glm_kmeans_step")
+
+
+def glm_lbfgs_workspace_bytes(job: Job, memory: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().glm_lbfgs_workspace_bytes(ctypes.byref(job.c), int(memory), ctypes.byref(out)),
+           "glm_lbfgs_workspace_bytes")
+    return int(out.value)
+
+
+def alloc_lbfgs_workspace(job: Job, memory: int) -> torch.Tensor:
+    return torch.empty(max(glm_lbfgs_workspace_bytes(job, memory), 256), dtype=torch.uint8, device=job.w.device)
+
+
+def glm_lbfgs(job: Job, state: glm_lbfgs_state_t, iters: int, memory: int, ws: torch.Tensor, stream=None) -> None:
+    _require_gpu()
+    _check(load().glm_lbfgs(ctypes.byref(job.c), ctypes.byref(state), int(iters), int(memory),
+                            ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream_handle(stream)), "glm_lbfgs")
 
 
 class HistoryView:
