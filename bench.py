@@ -29,10 +29,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5, 6, 7],
+    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5, 6, 7, 8],
                     help="0-4: the benchmark configurations; 5: one scheduling decision (predict + "
                          "allocate) for 4000 jobs and 16384 units; 6: one sparse job, 2e6 x 1e6 with ~2e8 entries; "
-                         "7: K-Means, 4e6 x 128 with 256 centroids")
+                         "7: K-Means, 4e6 x 128 with 256 centroids; 8: L-BFGS on the workload of 2")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only; the line says so)")
     ap.add_argument("--check", action="store_true", help="also compare against the oracle on the full data")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -558,6 +558,74 @@ def bench_kmeans(args):
     return out
 
 
+def bench_lbfgs(args):
+    """L-BFGS (memory 10) on the default workload: one step is one L-BFGS iteration, i.e. the
+    direction, a line search of one or more objective evaluations (each a full row pass) and the
+    pair update."""
+    import numpy as np
+    import torch
+    from paper_1802_04819_amd import glm, synth
+
+    p = synth.config2(args.scale, device="cuda")
+    K = args.steps if args.steps is not None else p.K
+    memory = 10
+    job = glm.Job(p.X, p.y, p.w0.clone(), p.loss, p.lam, 0.0, max(K, args.warmup, 1))
+    ws = glm.alloc_lbfgs_workspace(job, memory)
+
+    def run(n):
+        job.w.zero_(); job.c.hist_len = 0
+        st = glm.glm_lbfgs_state_t()
+        glm.glm_lbfgs(job, st, n, memory, ws)
+        torch.cuda.synchronize()
+        return st
+
+    if args.warmup > 0:
+        run(args.warmup)
+    glm.glm_profile_begin(40 * K + 8)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    st = run(K)
+    t1 = time.perf_counter()
+    ms = glm.glm_profile_end(40 * K + 8)
+    hist = job.history().cpu().numpy().copy(); w1 = job.w.clone()
+    st2 = run(K)
+    rerun_identical = bool(np.array_equal(hist, job.history().cpu().numpy()) and torch.equal(w1, job.w)
+                           and st.evals == st2.evals)
+    sec = t1 - t0
+    bytes_per_launch = 4.0 * p.N * p.D + 4.0 * p.N
+    avg_ms = float(np.mean(ms))
+    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "L-BFGS iterations/sec (each one or more full-batch evaluations; achieved HBM GB/s in roofline)",
+        "value": K / sec, "unit": "iter/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": 1e3 * sec / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": p.name + "_lbfgs", "config_index": 8, "N": p.N, "D": p.D, "memory": memory,
+                   "loss": synth.LOSS_NAMES[p.loss], "lambda": p.lam, "evaluations": int(st.evals),
+                   "bytes_per_evaluation": bytes_per_launch, "scale": args.scale},
+        "roofline": {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": avg_ms,
+                     "launches": len(ms), "whole_run_GBps": bytes_per_launch * st.evals / sec / 1e9},
+        "rerun_bit_identical": rerun_identical, "loss_first": float(hist[0]), "loss_last": float(st.f),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle import lbfgs_oracle
+        n = min(p.N, 400_000)
+        Xs, ys = p.X[:n].cpu().numpy(), p.y[:n].cpu().numpy()
+        its, evals, dt = 0, 0, 0.0
+        while its == 0 or dt < 10.0:
+            t = time.perf_counter()
+            _, _, info = lbfgs_oracle.run(p.loss, Xs, ys, np.zeros(p.D), p.lam, K, memory, chunks=oracle.max_threads())
+            dt += time.perf_counter() - t
+            its += K; evals += info["evals"]
+        out["cpu_baseline"] = {"value": its / (dt * p.N / n), "unit": "iter/s", "cores": oracle.max_threads(),
+                               "kind": "oracle",
+                               "sample": f"first {n} of {p.N} rows, {its} oracle iterations ({evals} evaluations) in "
+                                         f"{dt:.1f} s, rate scaled by {n}/{p.N}"}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -585,8 +653,10 @@ def main():
         out = bench_sched(args)
     elif args.config == 6:
         out = bench_sparse(args)
-    else:
+    elif args.config == 7:
         out = bench_kmeans(args)
+    else:
+        out = bench_lbfgs(args)
     print(json.dumps(out))
 
 
