@@ -1,0 +1,261 @@
+// C-ABI entry points of the job kinds other than the dense GLM step: sparse GLM step, K-Means,
+// L-BFGS.  Validation happens before anything is enqueued; see include/slaqglm.h.
+#include <cmath>
+#include <cstring>
+#include <mutex>
+
+#include "api_internal.h"
+#include "glm_internal.h"
+#include "kmeans_internal.h"
+#include "lbfgs_internal.h"
+
+using namespace slaqglm;
+
+extern "C" {
+
+namespace {
+struct SparseLayout { size_t seg0R, seg0C, closes, headless, slast, H, T, z, r, lossP, wwP, total; long long nch; };
+SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
+    SparseLayout L;
+    L.nch = (nnz + kSparseChunk - 1) / kSparseChunk;
+    const size_t nc = (size_t)L.nch;
+    size_t off = 0;
+    L.seg0R = off;    off = api_align_up(off + sizeof(int) * (nc + 1));
+    L.seg0C = off;    off = api_align_up(off + sizeof(int) * (nc + 1));
+    L.closes = off;   off = api_align_up(off + sizeof(int) * nc);
+    L.headless = off; off = api_align_up(off + sizeof(int) * nc);
+    L.slast = off;    off = api_align_up(off + sizeof(int) * nc);
+    L.H = off;        off = api_align_up(off + sizeof(float) * nc);
+    L.T = off;        off = api_align_up(off + sizeof(float) * nc);
+    L.z = off;        off = api_align_up(off + sizeof(float) * (size_t)(N + D));      // z [N] then gs [D]
+    L.r = off;        off = api_align_up(off + sizeof(float) * (size_t)N);
+    L.lossP = off;    off = api_align_up(off + sizeof(float) * (size_t)((N + 255) / 256));
+    L.wwP = off;      off = api_align_up(off + sizeof(double) * (size_t)((D + 255) / 256));
+    L.total = off;
+    return L;
+}
+int validate_sparse_shape(const glm_sparse_job_t &j) {
+    if (j.N < 1 || j.D < 1 || j.N >= (1LL << 31) || j.D >= (1LL << 31) || j.nnz < 0) return GLM_EINVAL;
+    if (j.nnz / kSparseChunk >= (1LL << 31) - 8) return GLM_EINVAL;
+    return GLM_OK;
+}
+}  // namespace
+
+int glm_sparse_workspace_bytes(const glm_sparse_job_t *job, size_t *out_bytes) {
+    if (!job || !out_bytes) return GLM_EINVAL;
+    if (validate_sparse_shape(*job) != GLM_OK) return GLM_EINVAL;
+    *out_bytes = make_sparse_layout(job->N, job->D, job->nnz).total;
+    return GLM_OK;
+}
+
+int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!job || iters < 0) return GLM_EINVAL;
+    const glm_sparse_job_t &j = *job;
+    if (validate_sparse_shape(j) != GLM_OK) return GLM_EINVAL;
+    if (!j.row_ptr || !j.col_ptr || !j.y || !j.w || !j.grad || !j.loss_hist) return GLM_EINVAL;
+    if (j.nnz > 0 && (!j.col_idx || !j.row_val || !j.row_idx || !j.col_val)) return GLM_EINVAL;
+    const void *p4[] = {j.col_idx, j.row_val, j.row_idx, j.col_val, j.y, j.w, j.grad, j.loss_hist};
+    for (const void *p : p4) if (reinterpret_cast<uintptr_t>(p) & 3u) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(j.row_ptr) & 7u) || (reinterpret_cast<uintptr_t>(j.col_ptr) & 7u)) return GLM_EINVAL;
+    if (j.loss < GLM_LOGISTIC || j.loss > GLM_SQUARED) return GLM_EINVAL;
+    if (!std::isfinite(j.lambda) || j.lambda < 0.0f || !std::isfinite(j.step) || j.step < 0.0f) return GLM_EINVAL;
+    if (j.hist_len < 0 || j.hist_cap < 0 || j.hist_len > j.hist_cap) return GLM_EINVAL;
+    if (j.hist_len + (int64_t)iters > j.hist_cap) return GLM_ENOSPC;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    const SparseLayout L = make_sparse_layout(j.N, j.D, j.nnz);
+    if (ws_bytes < L.total) return GLM_ENOSPC;
+    if (iters == 0) return GLM_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(ws);
+    SparseArgs a;
+    a.row_ptr = reinterpret_cast<const long long *>(j.row_ptr); a.col_idx = j.col_idx; a.row_val = j.row_val;
+    a.col_ptr = reinterpret_cast<const long long *>(j.col_ptr); a.row_idx = j.row_idx; a.col_val = j.col_val;
+    a.y = j.y; a.w = j.w; a.grad = j.grad; a.loss_out = j.loss_hist + j.hist_len;
+    a.N = j.N; a.D = j.D; a.nnz = j.nnz; a.nch = L.nch;
+    a.loss = j.loss; a.lambda = j.lambda; a.step = j.step;
+    a.seg0R = reinterpret_cast<int *>(base + L.seg0R); a.seg0C = reinterpret_cast<int *>(base + L.seg0C);
+    a.closes = reinterpret_cast<int *>(base + L.closes); a.headless = reinterpret_cast<int *>(base + L.headless);
+    a.slast = reinterpret_cast<int *>(base + L.slast);
+    a.H = reinterpret_cast<float *>(base + L.H); a.T = reinterpret_cast<float *>(base + L.T);
+    a.z = reinterpret_cast<float *>(base + L.z); a.gs = a.z + j.N;
+    a.r = reinterpret_cast<float *>(base + L.r);
+    a.lossP = reinterpret_cast<float *>(base + L.lossP); a.wwP = reinterpret_cast<double *>(base + L.wwP);
+    if (launch_sparse_setup(a, st) != hipSuccess) return GLM_EHIP;
+    for (int k = 0; k < iters; ++k) {
+        hipEvent_t *ev = api_profile_take(1);
+        if (launch_sparse_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
+    }
+    job->hist_len += iters;
+    return GLM_OK;
+}
+
+namespace {
+struct KmLayout { size_t cn, Cs, lossP, bestv, part, cntP, total; KmShape s; };
+KmLayout make_kmeans_layout(long long N, int D, int K) {
+    KmLayout L;
+    L.s = km_shape(N, D, K);
+    size_t off = 0;
+    L.cn = off;    off = api_align_up(off + sizeof(float) * (size_t)L.s.Kp);
+    L.Cs = off;    off = api_align_up(off + sizeof(unsigned short) * 3 * (size_t)L.s.Kp * L.s.Dp);
+    L.lossP = off; off = api_align_up(off + sizeof(float) * (size_t)L.s.lossN);
+    L.bestv = off; off = api_align_up(off + (L.s.split && L.s.Kp > 256 ? sizeof(float) * (size_t)N : 0));
+    L.part = off;  off = api_align_up(off + sizeof(float) * (size_t)L.s.P * K * D);
+    L.cntP = off;  off = api_align_up(off + sizeof(int) * (size_t)L.s.P * K);
+    L.total = off;
+    return L;
+}
+int validate_kmeans_shape(const glm_kmeans_job_t &j) {
+    if (j.N < 1 || j.N >= (1LL << 31)) return GLM_EINVAL;
+    if (j.D < 4 || j.D > kKmMaxD || (j.D & 3)) return GLM_EINVAL;
+    if (j.K < 1 || j.K > kKmMaxK) return GLM_EINVAL;
+    return GLM_OK;
+}
+}  // namespace
+
+int glm_kmeans_workspace_bytes(const glm_kmeans_job_t *job, size_t *out_bytes) {
+    if (!job || !out_bytes) return GLM_EINVAL;
+    if (validate_kmeans_shape(*job) != GLM_OK) return GLM_EINVAL;
+    *out_bytes = make_kmeans_layout(job->N, job->D, job->K).total;
+    return GLM_OK;
+}
+
+int glm_kmeans_step(glm_kmeans_job_t *job, int32_t iters, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!job || iters < 0) return GLM_EINVAL;
+    const glm_kmeans_job_t &j = *job;
+    if (validate_kmeans_shape(j) != GLM_OK) return GLM_EINVAL;
+    if (!j.X || !j.C || !j.assign || !j.counts || !j.loss_hist) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(j.X) & 15u) || (reinterpret_cast<uintptr_t>(j.C) & 15u)) return GLM_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(j.assign) & 3u) || (reinterpret_cast<uintptr_t>(j.counts) & 3u) ||
+        (reinterpret_cast<uintptr_t>(j.loss_hist) & 3u))
+        return GLM_EINVAL;
+    if (j.hist_len < 0 || j.hist_cap < 0 || j.hist_len > j.hist_cap) return GLM_EINVAL;
+    if (j.hist_len + (int64_t)iters > j.hist_cap) return GLM_ENOSPC;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    const KmLayout L = make_kmeans_layout(j.N, j.D, j.K);
+    if (ws_bytes < L.total) return GLM_ENOSPC;
+    if (iters == 0) return GLM_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(ws);
+    KmArgs a;
+    a.X = j.X; a.C = j.C; a.assign = j.assign; a.counts = j.counts; a.loss_out = j.loss_hist + j.hist_len;
+    a.N = j.N; a.D = j.D; a.K = j.K;
+    a.Cs = reinterpret_cast<unsigned short *>(base + L.Cs);
+    a.bestv = reinterpret_cast<float *>(base + L.bestv);
+    a.cn = reinterpret_cast<float *>(base + L.cn); a.lossP = reinterpret_cast<float *>(base + L.lossP);
+    a.part = reinterpret_cast<float *>(base + L.part); a.cntP = reinterpret_cast<int *>(base + L.cntP);
+    a.s = L.s;
+    for (int k = 0; k < iters; ++k) {
+        hipEvent_t *ev = api_profile_take(2);
+        if (launch_kmeans_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
+    }
+    job->hist_len += iters;
+    return GLM_OK;
+}
+
+namespace {
+struct LbLayout { size_t dense, S, Y, rho, yy, ring, p, wt, gt, scal, fslot, total; };
+LbLayout make_lbfgs_layout(const glm_job_t &job, int memory) {
+    LbLayout L;
+    const size_t D = (size_t)job.D, m = (size_t)memory;
+    size_t off = 0;
+    L.dense = off; off = api_align_up(off + api_dense_workspace_bytes(job));
+    L.S = off;     off = api_align_up(off + sizeof(float) * m * D);
+    L.Y = off;     off = api_align_up(off + sizeof(float) * m * D);
+    L.rho = off;   off = api_align_up(off + sizeof(double) * (m ? m : 1));
+    L.yy = off;    off = api_align_up(off + sizeof(double) * (m ? m : 1));
+    L.ring = off;  off = api_align_up(off + sizeof(int) * 2);
+    L.p = off;     off = api_align_up(off + sizeof(float) * D);
+    L.wt = off;    off = api_align_up(off + sizeof(float) * D);
+    L.gt = off;    off = api_align_up(off + sizeof(float) * D);
+    L.scal = off;  off = api_align_up(off + sizeof(double) * kLbScalars);
+    L.fslot = off; off = api_align_up(off + sizeof(float));
+    L.total = off;
+    return L;
+}
+
+// Pinned landing area for the scalars read back after every evaluation.
+struct LbHost { std::mutex mu; void *buf = nullptr; };
+LbHost g_lb;
+}  // namespace
+
+int glm_lbfgs_workspace_bytes(const glm_job_t *job, int32_t memory, size_t *out_bytes) {
+    if (!job || !out_bytes || memory < 0 || memory > kLbMaxMemory) return GLM_EINVAL;
+    if (api_validate_shape(job->N, job->D) != GLM_OK) return GLM_EINVAL;
+    *out_bytes = make_lbfgs_layout(*job, memory).total;
+    return GLM_OK;
+}
+
+int glm_lbfgs(glm_job_t *job, glm_lbfgs_state_t *state, int32_t iters, int32_t memory, void *ws, size_t ws_bytes,
+              void *hip_stream) {
+    if (!job || !state || iters < 0 || memory < 0 || memory > kLbMaxMemory) return GLM_EINVAL;
+    const int rc = api_validate_job(*job);
+    if (rc != GLM_OK) return rc;
+    if (state->started && state->memory != memory) return GLM_EINVAL;
+    if (job->hist_len + (int64_t)iters > job->hist_cap) return GLM_ENOSPC;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
+    const LbLayout L = make_lbfgs_layout(*job, memory);
+    if (ws_bytes < L.total) return GLM_ENOSPC;
+    if (iters == 0) return GLM_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(ws);
+    LbArgs a;
+    a.S = reinterpret_cast<float *>(base + L.S); a.Y = reinterpret_cast<float *>(base + L.Y);
+    a.rho = reinterpret_cast<double *>(base + L.rho); a.yy = reinterpret_cast<double *>(base + L.yy);
+    a.ring = reinterpret_cast<int *>(base + L.ring);
+    a.p = reinterpret_cast<float *>(base + L.p); a.wt = reinterpret_cast<float *>(base + L.wt);
+    a.gt = reinterpret_cast<float *>(base + L.gt);
+    a.scal = reinterpret_cast<double *>(base + L.scal); a.fslot = reinterpret_cast<float *>(base + L.fslot);
+    a.memory = memory; a.D = job->D;
+
+    std::lock_guard<std::mutex> lock(g_lb.mu);
+    if (!g_lb.buf && hipHostMalloc(&g_lb.buf, 256, hipHostMallocDefault) != hipSuccess) return GLM_EHIP;
+    float *h_f = static_cast<float *>(g_lb.buf);
+    double *h_scal = reinterpret_cast<double *>(static_cast<char *>(g_lb.buf) + 64);
+
+    // one evaluation: loss and gradient at w_at (step = 0 leaves w_at untouched), loss read back
+    auto evaluate = [&](float *w_at, float *g_out, bool with_scalars) -> int {
+        glm_job_t tmp = *job;
+        tmp.w = w_at; tmp.grad = g_out; tmp.loss_hist = a.fslot; tmp.hist_len = 0; tmp.hist_cap = 1; tmp.step = 0.0f;
+        const int one = 1;
+        if (api_run_rounds(&tmp, 1, &one, base + L.dense, st) != hipSuccess) return GLM_EHIP;
+        if (hipMemcpyAsync(h_f, a.fslot, sizeof(float), hipMemcpyDeviceToHost, st) != hipSuccess) return GLM_EHIP;
+        if (with_scalars &&
+            hipMemcpyAsync(h_scal, a.scal, sizeof(double) * kLbScalars, hipMemcpyDeviceToHost, st) != hipSuccess)
+            return GLM_EHIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return GLM_EHIP;
+        state->evals += 1;
+        return GLM_OK;
+    };
+
+    const bool fresh = !state->started;
+    if (fresh) {
+        const int e = evaluate(job->w, job->grad, false);
+        if (e != GLM_OK) return e;
+        state->f = (double)*h_f;
+        state->memory = memory;
+        state->started = 1;
+    }
+    for (int k = 0; k < iters; ++k) {
+        if (launch_lbfgs_direction(a, job->grad, fresh && k == 0, (float)state->f,
+                                   job->loss_hist + job->hist_len + k, st) != hipSuccess)
+            return GLM_EHIP;
+        double ft = state->f;
+        for (int h = 0; h <= 30; ++h) {
+            if (launch_lbfgs_trial(a, job->w, h, st) != hipSuccess) return GLM_EHIP;
+            const int e = evaluate(a.wt, a.gt, true);
+            if (e != GLM_OK) return e;
+            ft = (double)*h_f;
+            const double alpha = std::ldexp(h_scal[2], -h);
+            if (ft <= state->f + 1e-4 * alpha * h_scal[0] + 1e-6 * std::fabs(state->f) || h == 30) break;
+        }
+        if (launch_lbfgs_accept(a, job->w, job->grad, st) != hipSuccess) return GLM_EHIP;
+        state->f = ft;
+    }
+    job->hist_len += iters;
+    return GLM_OK;
+}
+
+}  // extern "C"
