@@ -112,3 +112,34 @@ def test_mixed_jobs_closed_loop():
     _say(f"  mean normalised loss: equal shares {mean_norm(fair):.4f}, quality-driven {mean_norm(greedy):.4f}; "
          f"allocations {[a.tolist() for a in allocs]}")
     assert mean_norm(greedy) <= mean_norm(fair), (mean_norm(greedy), mean_norm(fair))
+
+
+def test_normalised_loss_changes_fall_from_one_towards_zero_for_every_kind_of_job():
+    # Sec. 2, "Normalizing Quality Metrics" (and the figure it refers to): whatever the range of the
+    # loss, the change per iteration, divided by the largest change seen so far, starts at 1 and
+    # decays towards 0 for the common algorithms.  Checked on the library's own histories.
+    _say("[case] normalised loss changes of GD (logistic, hinge, squared), sparse GD, L-BFGS and K-Means")
+    d = "cuda"
+    K = 40
+    hists = {}
+    for name, p in (("logistic", synth.make_glm(synth.LOGISTIC, 20000, 64, 11, lam=1e-4, eta=0.5, K=K, device=d)),
+                    ("hinge", synth.make_glm(synth.HINGE, 20000, 64, 12, lam=1e-4, eta=0.05, K=K, device=d)),
+                    ("squared", synth.make_glm(synth.SQUARED, 20000, 64, 13, lam=1e-3, eta=0.05, K=K, device=d))):
+        j = _Dense(p, K); j.step(K); hists[name] = j.job
+    # the sparse problem is badly conditioned (power-law column popularity): it needs more iterations
+    s = _Sparse(synth.make_sparse_glm(synth.LOGISTIC, 30000, 5000, 20.0, 14, lam=1e-5, eta=2.0, K=K, device=d), 8 * K)
+    s.step(8 * K); hists["sparse logistic"] = s.job
+    km = _KMeans(synth.make_kmeans(40000, 32, 24, 15, blobs=12, device=d), K)
+    km.step(K); hists["kmeans"] = km.job
+    p = synth.make_glm(synth.LOGISTIC, 20000, 64, 16, lam=1e-4, eta=0.0, K=K, device=d)
+    lj = glm.Job(p.X, p.y, p.w0.clone(), p.loss, p.lam, 0.0, K)
+    glm.glm_lbfgs(lj, glm.glm_lbfgs_state_t(), K, 10, glm.alloc_lbfgs_workspace(lj, 10))
+    hists["lbfgs"] = lj
+    torch.cuda.synchronize()
+    for name, job in hists.items():
+        h = job.history().cpu().numpy().astype(np.float64)
+        nu, norm = so.normalized_changes(h)
+        assert nu[0] == 1.0 and np.all(np.abs(nu) <= 1.0) and norm > 0, name
+        head, tail = np.abs(nu[:5]).mean(), np.abs(nu[-5:]).mean()
+        _say(f"  {name:16s} loss {h[0]:.4g} -> {h[-1]:.4g}; mean |normalised change| first 5: {head:.3f}, last 5: {tail:.4f}")
+        assert tail < 0.25 * head and tail < 0.2, (name, head, tail)
