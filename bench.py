@@ -138,6 +138,19 @@ def bench_single(args, cfg):
     bytes_per_launch = 4.0 * p.N * p.D + 4.0 * p.N
     avg_ms = float(np.mean(k1_ms)) if k1_ms else float("nan")
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+
+    # the streaming-read ceiling of this device on the very same buffer: a kernel that only reads
+    # X with non-temporal 128-bit loads (median of 9 launches, events on the launching stream)
+    sink = torch.zeros(glm.glm_read_probe_sink_floats(), device="cuda")
+    xs = p.X.reshape(-1)
+    for _ in range(2):
+        glm.glm_read_probe(xs, sink)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(10)]
+    for i in range(9):
+        evs[i].record(); glm.glm_read_probe(xs, sink)
+    evs[9].record(); torch.cuda.synchronize()
+    probe_ms = float(np.median([evs[i].elapsed_time(evs[i + 1]) for i in range(9)]))
+    ceiling = 4.0 * p.N * p.D / (probe_ms * 1e-3) / 1e9
     out = {
         "metric": "GD iterations/sec (full-batch GLM step; achieved HBM GB/s in roofline)",
         "value": K / sec, "unit": "iter/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
@@ -150,8 +163,9 @@ def bench_single(args, cfg):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": (traffic_from_counters("row_pass_cfg2_hbm_counters.md")
                                  if cfg == 2 and args.scale == 1.0 else None),
-                     "avg_launch_ms": avg_ms, "launches": len(k1_ms),
-                     "whole_step_GBps": bytes_per_launch * K / sec / 1e9},
+                     "avg_launch_ms": avg_ms, "median_launch_ms": float(np.median(k1_ms)) if k1_ms else None,
+                     "launches": len(k1_ms), "whole_step_GBps": bytes_per_launch * K / sec / 1e9,
+                     "read_ceiling_GBps": ceiling, "frac_of_read_ceiling": achieved / ceiling},
         "rerun_bit_identical": rerun_identical,
         "loss_first": float(hist[0]), "loss_last": float(hist[-1]),
     }

@@ -432,16 +432,19 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const f4 *__restrict__ 
                                                          float *__restrict__ sink) {
     __shared__ float red[256];
     float acc = 0.0f;
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 7 * stride < n4; i += 8 * stride) {
+    // a block reads one contiguous span, as a block of the row pass reads its rows
+    const size_t span = (n4 + gridDim.x - 1) / gridDim.x;
+    const size_t b0 = (size_t)blockIdx.x * span;
+    const size_t b1 = b0 + span < n4 ? b0 + span : n4;
+    size_t i = b0 + threadIdx.x;
+    for (; i + 7 * 256 < b1; i += 8 * 256) {
         f4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = stream_load(src + i + u * stride);
+        for (int u = 0; u < 8; ++u) v[u] = stream_load(src + i + u * 256);
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += (v[u].x + v[u].y) + (v[u].z + v[u].w);
     }
-    for (; i < n4; i += stride) {
+    for (; i < b1; i += 256) {
         const f4 v = stream_load(src + i);
         acc += (v.x + v.y) + (v.z + v.w);
     }
