@@ -71,7 +71,7 @@ def traffic_from_counters(summary_name):
     return float(val.group(1))
 
 
-def cpu_baseline_single(p, target_rows):
+def cpu_baseline_single(p, target_rows, one_core=False):
     """The oracle as it stands, timed on the host cores on the first `target_rows` rows of the
     same workload; the rate is scaled to whole-data iterations per second."""
     import numpy as np
@@ -91,9 +91,19 @@ def cpu_baseline_single(p, target_rows):
         reps += 1
     per_iter_sample = t_tot / reps
     per_iter_full = per_iter_sample * (p.N / n)
-    return {"value": 1.0 / per_iter_full, "unit": "iter/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {n} of {p.N} rows, {reps} oracle iterations of {per_iter_sample:.3f} s, "
-                      f"rate scaled by {n}/{p.N}"}
+    out = {"value": 1.0 / per_iter_full, "unit": "iter/s", "cores": threads, "kind": "oracle",
+           "sample": f"first {n} of {p.N} rows, {reps} oracle iterations of {per_iter_sample:.3f} s, "
+                     f"rate scaled by {n}/{p.N}"}
+    if one_core:
+        # the strictly sequential evaluation (one core, rows in index order)
+        r1, t1 = 0, 0.0
+        while r1 < 2 or (t1 < 3.0 and r1 < 500):
+            t0 = time.perf_counter()
+            oracle.loss_grad(p.loss, Xs, ys, w, p.lam)
+            t1 += time.perf_counter() - t0
+            r1 += 1
+        out["value_one_core"] = 1.0 / (t1 / r1 * (p.N / n))
+    return out
 
 
 def bench_single(args, cfg):
@@ -181,7 +191,7 @@ def bench_single(args, cfg):
                         "rel_err_gnorm_k0": abs(np.linalg.norm(gg) - np.linalg.norm(g)) / np.linalg.norm(g)}
     if not args.no_cpu_baseline:
         rows = {0: p.N, 1: 1_000_000, 2: 400_000}[cfg]
-        out["cpu_baseline"] = cpu_baseline_single(p, rows)
+        out["cpu_baseline"] = cpu_baseline_single(p, rows, one_core=cfg in (0, 1))
     return out
 
 
