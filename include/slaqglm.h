@@ -210,6 +210,9 @@ typedef struct {
     int32_t        loss;     /* glm_loss_t                                                          */
     float          lambda, step;
     int64_t        hist_len, hist_cap;
+    int32_t        prepared; /* 0 at first: the call then builds its auxiliary column layout in the
+                                workspace (once) and sets this; set it back to 0 whenever the matrix
+                                or the workspace has changed                                         */
 } glm_sparse_job_t;
 
 /* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz only). */
@@ -217,7 +220,10 @@ int glm_sparse_workspace_bytes(const glm_sparse_job_t *job /*HOST*/, size_t *out
 
 /* `iters` gradient-descent iterations of one sparse job: the same iteration as glm_step, with
  * absent entries counting as zeros.  Reads each stored entry twice per iteration (once per
- * layout).  The contents of the index arrays are trusted (they live on the device); sizes,
+ * layout).  With more than 786,432 rows the first call (job->prepared == 0) copies the column
+ * layout into the workspace ordered by panels of 524,288 rows, so that the gathers of the column
+ * pass stay inside L2; this needs the rows of every column in ascending order (checked on the
+ * device; otherwise the caller's layout is used as it is) and synchronises with hip_stream once.  The contents of the index arrays are trusted (they live on the device); sizes,
  * pointers and hyper-parameters are validated as in glm_step, with the same error codes. */
 int glm_step_sparse(glm_sparse_job_t *job /*HOST*/, int32_t iters, void *ws /*DEVICE*/, size_t ws_bytes,
                     void *hip_stream);

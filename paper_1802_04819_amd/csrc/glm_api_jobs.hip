@@ -8,13 +8,19 @@
 #include "glm_internal.h"
 #include "kmeans_internal.h"
 #include "lbfgs_internal.h"
+#include "sparse_internal.h"
 
 using namespace slaqglm;
 
 extern "C" {
 
 namespace {
-struct SparseLayout { size_t seg0R, seg0C, closes, headless, slast, H, T, z, r, lossP, wwP, total; long long nch; };
+struct SparseLayout {
+    size_t seg0R, seg0C, closes, headless, slast, H, T, z, r, lossP, wwP, total;
+    size_t pp, ptr2, bsum, idx2, val2, seg0P, gs2, flag;     // row-panelled column layout (P > 1)
+    long long nch;
+    int P;
+};
 SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
     SparseLayout L;
     L.nch = (nnz + kSparseChunk - 1) / kSparseChunk;
@@ -31,6 +37,19 @@ SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
     L.r = off;        off = api_align_up(off + sizeof(float) * (size_t)N);
     L.lossP = off;    off = api_align_up(off + sizeof(float) * (size_t)((N + 255) / 256));
     L.wwP = off;      off = api_align_up(off + sizeof(double) * (size_t)((D + 255) / 256));
+    L.P = sparse_panel_count(N, D);
+    L.pp = L.ptr2 = L.bsum = L.idx2 = L.val2 = L.seg0P = L.gs2 = L.flag = off;
+    if (L.P > 1) {
+        const size_t S2 = (size_t)L.P * (size_t)D;
+        L.flag = off;  off = api_align_up(off + sizeof(int));
+        L.pp = off;    off = api_align_up(off + sizeof(long long) * (S2 + (size_t)D));
+        L.ptr2 = off;  off = api_align_up(off + sizeof(long long) * (S2 + 1));
+        L.bsum = off;  off = api_align_up(off + sizeof(long long) * ((S2 + kScanBlock - 1) / kScanBlock + 1));
+        L.idx2 = off;  off = api_align_up(off + sizeof(int) * (size_t)nnz);
+        L.val2 = off;  off = api_align_up(off + sizeof(float) * (size_t)nnz);
+        L.seg0P = off; off = api_align_up(off + sizeof(int) * (nc + 1));
+        L.gs2 = off;   off = api_align_up(off + sizeof(float) * S2);
+    }
     L.total = off;
     return L;
 }
@@ -82,9 +101,33 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     a.r = reinterpret_cast<float *>(base + L.r);
     a.lossP = reinterpret_cast<float *>(base + L.lossP); a.wwP = reinterpret_cast<double *>(base + L.wwP);
     if (launch_sparse_setup(a, st) != hipSuccess) return GLM_EHIP;
+    SparsePanels pn;
+    pn.P = L.P; pn.R = kSparsePanelRows;
+    pn.pp = reinterpret_cast<long long *>(base + L.pp); pn.ptr2 = reinterpret_cast<long long *>(base + L.ptr2);
+    pn.bsum = reinterpret_cast<long long *>(base + L.bsum);
+    pn.idx2 = reinterpret_cast<int *>(base + L.idx2); pn.val2 = reinterpret_cast<float *>(base + L.val2);
+    pn.seg0 = reinterpret_cast<int *>(base + L.seg0P); pn.gs2 = reinterpret_cast<float *>(base + L.gs2);
+    pn.flag = reinterpret_cast<int *>(base + L.flag);
+    // job->prepared: 0 = nothing built yet, 1 = panelled layout in the workspace, 2 = caller's layout is used
+    if (pn.P > 1 && j.nnz > 0 && job->prepared == 0) {
+        if (launch_sparse_sorted_check(a, pn, st) != hipSuccess) return GLM_EHIP;
+        int unsorted = 0;
+        if (hipStreamSynchronize(st) != hipSuccess ||
+            hipMemcpy(&unsorted, pn.flag, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
+            return GLM_EHIP;
+        if (unsorted) {
+            job->prepared = 2;
+        } else {
+            if (launch_sparse_panel_build(a, pn, st) != hipSuccess) return GLM_EHIP;
+            job->prepared = 1;
+        }
+    } else if (job->prepared == 0) {
+        job->prepared = 2;
+    }
+    if (job->prepared != 1) pn.P = 1;
     for (int k = 0; k < iters; ++k) {
         hipEvent_t *ev = api_profile_take(1);
-        if (launch_sparse_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
+        if (launch_sparse_iteration_panels(a, pn, k, ev, st) != hipSuccess) return GLM_EHIP;
     }
     job->hist_len += iters;
     return GLM_OK;

@@ -17,6 +17,7 @@
 // inside the chunk, the whole chunk as one piece (also T).
 #include "glm_internal.h"
 #include "glm_loss.h"
+#include "sparse_internal.h"
 
 namespace slaqglm {
 
@@ -302,6 +303,195 @@ hipError_t launch_sparse_iteration(const SparseArgs &a, int k, hipEvent_t *ev, h
     if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_col_epilogue, dim3(nbC), dim3(256), 0, st, a.gs, a.D, 1.0 / (double)a.N, a.lambda,
                        a.step, a.w, a.grad, a.wwP);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(sparse_loss_kernel, dim3(1), dim3(1024), 0, st, a.lossP, (long long)nbR, a.wwP,
+                       (long long)nbC, 1.0 / (double)a.N, a.lambda, a.loss_out + k);
+    return hipGetLastError();
+}
+
+
+// ---- Row-panelled column layout ------------------------------------------------------------
+
+int sparse_panel_count(long long N, long long D) {
+    if (N <= kSparsePanelRows + kSparsePanelRows / 2) return 1;
+    long long P = (N + kSparsePanelRows - 1) / kSparsePanelRows;
+    if (P > kSparseMaxPanels) P = kSparseMaxPanels;
+    while (P > 1 && P * D >= (1LL << 31) - 8) --P;
+    return (int)P;
+}
+
+// Are the rows of every column in ascending order?  One thread per pair of neighbouring entries;
+// a descent is harmless only where the second entry starts a column (binary search, rare).
+__global__ __launch_bounds__(256) void csc_sorted_kernel(const long long *__restrict__ col_ptr,
+                                                         const int *__restrict__ row_idx, long long D,
+                                                         long long nnz, int *__restrict__ flag) {
+    const long long e = blockIdx.x * 256LL + threadIdx.x;
+    if (e + 1 >= nnz) return;
+    if (row_idx[e] <= row_idx[e + 1]) return;
+    long long lo = 0, hi = D;                          // smallest c with col_ptr[c] >= e + 1 (col_ptr[D] = nnz)
+    while (lo < hi) {
+        const long long mid = (lo + hi) >> 1;
+        if (col_ptr[mid] < e + 1) lo = mid + 1; else hi = mid;
+    }
+    if (col_ptr[lo] != e + 1) atomicOr(flag, 1);
+}
+
+// pp[p * D + col] = first entry of column col whose row is >= p R (p = 0 .. P)
+__global__ void panel_bounds_kernel(const long long *__restrict__ col_ptr, const int *__restrict__ row_idx,
+                                    long long D, int P, long long R, long long *__restrict__ pp) {
+    const long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    if (t >= (long long)(P + 1) * D) return;
+    const long long p = t / D, col = t - p * D;
+    long long lo = col_ptr[col], hi = col_ptr[col + 1];
+    const long long bound = p * R;
+    while (lo < hi) {                                  // first entry with row >= bound
+        const long long mid = (lo + hi) >> 1;
+        if ((long long)row_idx[mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    pp[t] = lo;
+}
+
+// Exclusive prefix sum of the segment lengths len[s] = pp[s + D] - pp[s], s = p D + col, in
+// three steps: per block of 4096, the block totals (one thread; at most a few hundred thousand),
+// and the final add.
+__global__ __launch_bounds__(256) void panel_scan_block_kernel(const long long *__restrict__ pp, long long D,
+                                                               long long S2, long long *__restrict__ ptr2,
+                                                               long long *__restrict__ bsum) {
+    __shared__ long long tot[256];
+    const long long base = (long long)blockIdx.x * kScanBlock + threadIdx.x * 16LL;
+    long long v[16], run = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const long long s = base + q;
+        v[q] = run;
+        run += s < S2 ? pp[s + D] - pp[s] : 0;
+    }
+    tot[threadIdx.x] = run;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long acc = 0;
+        for (int t = 0; t < 256; ++t) { const long long x = tot[t]; tot[t] = acc; acc += x; }
+        bsum[blockIdx.x] = acc;
+    }
+    __syncthreads();
+    const long long off = tot[threadIdx.x];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const long long s = base + q;
+        if (s < S2) ptr2[s] = v[q] + off;
+    }
+}
+
+__global__ void panel_scan_tops_kernel(long long nb, long long *__restrict__ bsum) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    long long acc = 0;
+    for (long long b = 0; b < nb; ++b) { const long long x = bsum[b]; bsum[b] = acc; acc += x; }
+    bsum[nb] = acc;
+}
+
+__global__ __launch_bounds__(256) void panel_scan_add_kernel(long long S2, const long long *__restrict__ bsum,
+                                                             long long nb, long long *__restrict__ ptr2) {
+    const long long s = blockIdx.x * 256LL + threadIdx.x;
+    if (s < S2) ptr2[s] += bsum[s / kScanBlock];
+    if (s == S2) ptr2[S2] = bsum[nb];
+}
+
+// One wave per (panel, column) segment: copy its entries to their place in the panelled layout.
+__global__ __launch_bounds__(256) void panel_copy_kernel(const long long *__restrict__ pp,
+                                                         const long long *__restrict__ ptr2, long long S2,
+                                                         long long D, const int *__restrict__ row_idx,
+                                                         const float *__restrict__ col_val,
+                                                         int *__restrict__ idx2, float *__restrict__ val2) {
+    const int lane = threadIdx.x & 63;
+    const long long s = blockIdx.x * 4LL + (threadIdx.x >> 6);
+    if (s >= S2) return;
+    const long long src = pp[s], n = pp[s + D] - src, dst = ptr2[s];
+    for (long long i = lane; i < n; i += 64) {
+        idx2[dst + i] = row_idx[src + i];
+        val2[dst + i] = col_val[src + i];
+    }
+}
+
+// Columns: sum of the P per-panel sums in panel order, then gradient, update, |w|^2 partials.
+__global__ __launch_bounds__(256) void sparse_col_epilogue_panels(const float *__restrict__ gs2, int P, long long D,
+                                                                  double invN, float lambda, float step,
+                                                                  float *__restrict__ w, float *__restrict__ grad,
+                                                                  double *__restrict__ wwP) {
+    __shared__ double red[256];
+    const long long j = blockIdx.x * 256LL + threadIdx.x;
+    double ww = 0.0;
+    if (j < D) {
+        double s = 0.0;
+        for (int p = 0; p < P; ++p) s += (double)gs2[(size_t)p * D + j];
+        const float wj = w[j];
+        const double g = s * invN + (double)lambda * (double)wj;
+        grad[j] = (float)g;
+        ww = (double)wj * (double)wj;
+        if (step != 0.0f) w[j] = (float)((double)wj - (double)step * g);
+    }
+    red[threadIdx.x] = ww;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] = red[threadIdx.x] + red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) wwP[blockIdx.x] = red[0];
+}
+
+hipError_t launch_sparse_sorted_check(const SparseArgs &a, const SparsePanels &pn, hipStream_t st) {
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(64), 0, st, reinterpret_cast<float *>(pn.flag), 1LL);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(csc_sorted_kernel, dim3((unsigned)((a.nnz + 255) / 256)), dim3(256), 0, st, a.col_ptr, a.row_idx,
+                       a.D, a.nnz, pn.flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_panel_build(const SparseArgs &a, const SparsePanels &pn, hipStream_t st) {
+    hipError_t e;
+    const long long S2 = (long long)pn.P * a.D;
+    const long long nbounds = (long long)(pn.P + 1) * a.D;
+    hipLaunchKernelGGL(panel_bounds_kernel, dim3((unsigned)((nbounds + 255) / 256)), dim3(256), 0, st, a.col_ptr,
+                       a.row_idx, a.D, pn.P, pn.R, pn.pp);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const long long nb = (S2 + kScanBlock - 1) / kScanBlock;
+    hipLaunchKernelGGL(panel_scan_block_kernel, dim3((unsigned)nb), dim3(256), 0, st, pn.pp, a.D, S2, pn.ptr2, pn.bsum);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(panel_scan_tops_kernel, dim3(1), dim3(64), 0, st, nb, pn.bsum);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(panel_scan_add_kernel, dim3((unsigned)((S2 + 1 + 255) / 256)), dim3(256), 0, st, S2, pn.bsum, nb,
+                       pn.ptr2);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(panel_copy_kernel, dim3((unsigned)((S2 + 3) / 4)), dim3(256), 0, st, pn.pp, pn.ptr2, S2, a.D,
+                       a.row_idx, a.col_val, pn.idx2, pn.val2);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (a.nch == 0) return hipSuccess;
+    hipLaunchKernelGGL(seg_start_kernel, dim3((unsigned)((a.nch + 1 + 255) / 256)), dim3(256), 0, st, pn.ptr2, S2, a.nch,
+                       pn.seg0);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_iteration_panels(const SparseArgs &a, const SparsePanels &pn, int k, hipEvent_t *ev,
+                                          hipStream_t st) {
+    if (pn.P <= 1) return launch_sparse_iteration(a, k, ev, st);
+    hipError_t e;
+    ChunkRec rec{a.closes, a.headless, a.slast, a.H, a.T};
+    const long long S2 = (long long)pn.P * a.D;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((a.N + 255) / 256)), dim3(256), 0, st, a.z, a.N);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((S2 + 255) / 256)), dim3(256), 0, st, pn.gs2, S2);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
+    if ((e = seg_pass(a.row_ptr, a.col_idx, a.row_val, a.w, a.N, a.nnz, a.nch, a.seg0R, a.z, rec, st)) != hipSuccess)
+        return e;
+    const unsigned nbR = (unsigned)((a.N + 255) / 256), nbC = (unsigned)((a.D + 255) / 256);
+    hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = seg_pass(pn.ptr2, pn.idx2, pn.val2, a.r, S2, a.nnz, a.nch, pn.seg0, pn.gs2, rec, st)) != hipSuccess)
+        return e;
+    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
+    hipLaunchKernelGGL(sparse_col_epilogue_panels, dim3(nbC), dim3(256), 0, st, pn.gs2, pn.P, a.D, 1.0 / (double)a.N,
+                       a.lambda, a.step, a.w, a.grad, a.wwP);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_loss_kernel, dim3(1), dim3(1024), 0, st, a.lossP, (long long)nbR, a.wwP,
                        (long long)nbC, 1.0 / (double)a.N, a.lambda, a.loss_out + k);

@@ -1,0 +1,35 @@
+// Row-panelled column layout of the sparse iteration (glm_sparse.hip, driven from glm_api_jobs.hip).
+#pragma once
+
+#include "glm_internal.h"
+
+namespace slaqglm {
+
+constexpr long long kSparsePanelRows = 512 * 1024;   // residuals of one panel: 2 MB, well inside one L2
+constexpr int kSparseMaxPanels = 64;
+constexpr int kScanBlock = 4096;                      // items per block of the prefix sum
+
+// The column pass gathers from the residual vector r [N].  Beyond a few MB r no longer stays in
+// L2 and every gather of 4 bytes pulls a whole line from memory.  So the column layout is
+// rebuilt once, in the workspace, ordered by row panel first: panel p holds, column by column,
+// the entries whose row lies in [p R, (p + 1) R).  The column pass then is the same segmented sum
+// over P * D segments, and while the entries of panel p stream by, only r [p R, (p + 1) R) is hot.
+struct SparsePanels {
+    int P;               // 1: the caller's column layout is used as it is
+    long long R;         // rows per panel
+    long long *pp;       // [(P + 1) * D] first entry of each column with row >= p R
+    long long *ptr2;     // [P * D + 1]   segment starts of the panelled layout
+    long long *bsum;     // [blocks + 1]  block totals of the prefix sum
+    int *idx2;           // [nnz] row of every entry, panelled order
+    float *val2;         // [nnz]
+    int *seg0;           // [nch + 1] segment holding each chunk's first entry
+    float *gs2;          // [P * D] column sums per panel
+    int *flag;           // [1] set if some column's rows are not in ascending order
+};
+int sparse_panel_count(long long N, long long D);
+hipError_t launch_sparse_sorted_check(const SparseArgs &a, const SparsePanels &pn, hipStream_t st);
+hipError_t launch_sparse_panel_build(const SparseArgs &a, const SparsePanels &pn, hipStream_t st);
+hipError_t launch_sparse_iteration_panels(const SparseArgs &a, const SparsePanels &pn, int k, hipEvent_t *ev,
+                                          hipStream_t st);
+
+}  // namespace slaqglm

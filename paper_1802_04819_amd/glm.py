@@ -50,7 +50,7 @@ class glm_sparse_job_t(ctypes.Structure):
         ("loss_hist", ctypes.c_void_p),
         ("N", ctypes.c_int64), ("D", ctypes.c_int64), ("nnz", ctypes.c_int64),
         ("loss", ctypes.c_int32), ("lambda_", ctypes.c_float), ("step", ctypes.c_float),
-        ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64),
+        ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64), ("prepared", ctypes.c_int32),
     ]
 
 

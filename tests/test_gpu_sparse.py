@@ -185,3 +185,64 @@ def test_sparse_errors():
         glm.glm_step_sparse(job, 1, ws)
     torch.cuda.synchronize()
     assert job.hist_len == 0 and job.w.abs().sum().item() == 0
+
+
+def _tall(seed, N=1_200_000, D=300, nnz=3_000_000):
+    """More rows than one panel of the column layout holds: a long column through every panel, a
+    column that lives in one panel only, empty columns, the rest uniform."""
+    rng = np.random.default_rng(seed)
+    rows = rng.integers(0, N, size=nnz); cols = rng.integers(3, D - 5, size=nnz)
+    rows = np.concatenate([rows, np.arange(0, N, 7), rng.integers(600_000, 700_000, size=5000)])
+    cols = np.concatenate([cols, np.zeros(len(np.arange(0, N, 7)), dtype=np.int64), np.ones(5000, dtype=np.int64)])
+    vals = (rng.standard_normal(len(rows)) / 3).astype(np.float32)
+    return sp.csr_matrix((vals, (rows, cols)), shape=(N, D))
+
+
+@pytest.mark.parametrize("loss", [synth.LOGISTIC, synth.SQUARED])
+def test_row_panelled_column_layout(loss):
+    _say(f"[case] sparse, 1.2e6 rows (column layout rebuilt by row panels), loss {loss}")
+    A = _tall(11)
+    N, D = A.shape
+    rng = np.random.default_rng(3)
+    y = _labels(loss, N, rng)
+    eta = 0.5 if loss == synth.LOGISTIC else 0.05
+    job, csr = _job_from_scipy(A, y, loss, 1e-4, eta, 3)
+    assert job.c.prepared == 0
+    _check_steps(job, csr, y, D, loss, 1e-4, eta, 3, "panels")
+    assert job.c.prepared == 1
+
+
+def test_unsorted_columns_fall_back_to_the_callers_layout():
+    _say("[case] sparse, 1.2e6 rows, rows of a column not ascending: caller's layout is used")
+    A = _tall(12)
+    N, D = A.shape
+    rng = np.random.default_rng(4)
+    y = _labels(synth.LOGISTIC, N, rng)
+    job, csr = _job_from_scipy(A, y, synth.LOGISTIC, 1e-4, 0.5, 2)
+    # reverse the entries of every column: same matrix, descending rows
+    cp = job.tensors[3].cpu().numpy(); ri = job.tensors[4].cpu().numpy(); cv = job.tensors[5].cpu().numpy()
+    ri2, cv2 = ri.copy(), cv.copy()
+    for j in range(D):
+        ri2[cp[j]:cp[j + 1]] = ri[cp[j]:cp[j + 1]][::-1]; cv2[cp[j]:cp[j + 1]] = cv[cp[j]:cp[j + 1]][::-1]
+    job.tensors[4].copy_(torch.from_numpy(ri2)); job.tensors[5].copy_(torch.from_numpy(cv2))
+    _check_steps(job, csr, y, D, synth.LOGISTIC, 1e-4, 0.5, 2, "unsorted")
+    assert job.c.prepared == 2
+
+
+def test_panelled_layout_reruns_and_split_calls_bit_identical():
+    _say("[case] sparse with panels: reruns and 2 + 3 iterations = 5")
+    A = _tall(13)
+    N, D = A.shape
+    y = _labels(synth.LOGISTIC, N, np.random.default_rng(5))
+    outs = []
+    for split in ((5,), (5,), (2, 3)):
+        job, _ = _job_from_scipy(A, y, synth.LOGISTIC, 1e-4, 0.5, 5)
+        ws = glm.alloc_sparse_workspace(job)
+        for n in split:
+            glm.glm_step_sparse(job, n, ws)
+        torch.cuda.synchronize()
+        assert job.c.prepared == 1
+        outs.append((job.history().cpu().clone(), job.w.cpu().clone(), job.grad.cpu().clone()))
+    for o in outs[1:]:
+        for x, z in zip(outs[0], o):
+            assert torch.equal(x, z)
