@@ -215,7 +215,8 @@ typedef struct {
                                 or the workspace has changed                                         */
 } glm_sparse_job_t;
 
-/* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz only). */
+/* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz only).  With more than 786,432
+ * rows this includes room for a second copy of the column layout (8 bytes per entry). */
 int glm_sparse_workspace_bytes(const glm_sparse_job_t *job /*HOST*/, size_t *out_bytes /*HOST*/);
 
 /* `iters` gradient-descent iterations of one sparse job: the same iteration as glm_step, with
