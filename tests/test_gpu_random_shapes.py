@@ -118,3 +118,20 @@ def test_lbfgs_run(i):
     for k in range(8):
         if moving[: k + 1].all():
             assert rel(got[k], hist[k]) <= REL_TOL, (k, got[k], hist[k])
+
+
+@pytest.mark.parametrize("i", range(3))
+def test_sparse_step_with_row_panels(i):
+    rng = np.random.default_rng(700 + i)
+    N = int(rng.integers(786_433, 3_500_000)); D = int(rng.integers(1, 5000)); nnz = int(rng.integers(1, 3_000_000))
+    loss = int(rng.integers(0, 3))
+    rows = rng.integers(0, N, size=nnz); cols = (rng.random(nnz) ** float(rng.uniform(1, 4)) * D).astype(np.int64)
+    if i == 0:
+        rows[: nnz // 2] = rng.integers(N // 3, N // 3 + 1000, size=nnz // 2)       # one crowded panel
+    A = sp.csr_matrix(((rng.standard_normal(nnz) / 3).astype(np.float32), (rows, cols)), shape=(N, D))
+    _say(f"[case] random sparse with row panels N={N} D={D} nnz={A.nnz} loss={loss}")
+    y = ts._labels(loss, N, rng)
+    eta = {0: 0.5, 1: 0.05, 2: 0.02}[loss]
+    job, csr = ts._job_from_scipy(A, y, loss, 1e-4, eta, 2)
+    ts._check_steps(job, csr, y, D, loss, 1e-4, eta, 2, "random panels")
+    assert job.c.prepared == 1
