@@ -51,5 +51,25 @@ def build_lib(force: bool = True, verbose: bool = False) -> str:
     return LIB_PATH
 
 
+C_DEMO_SRC = os.path.join(ROOT, "tests", "c_abi_demo.c")
+C_DEMO_BIN = os.path.join(ROOT, "tests", "c_abi_demo.bin")
+
+
+def build_c_demo() -> str:
+    """Compile the plain-C consumer of the library (gcc, C99): proof that the header is C and that
+    the entry points need nothing but pointers and sizes.  Returns the program's path."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-O1", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"),
+           C_DEMO_SRC, "-o", C_DEMO_BIN,
+           "-L", os.path.dirname(LIB_PATH), "-lslaqglm", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../paper_1802_04819_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed on the C demo:\n" + res.stdout)
+    return C_DEMO_BIN
+
+
 if __name__ == "__main__":
     print(build_lib(force=True, verbose="-v" in sys.argv))
+    print(build_c_demo())

@@ -142,3 +142,11 @@ def test_probe_and_profile_argument_checks():
     n = ctypes.c_int32(0)
     ms = (ctypes.c_float * 4)()
     assert lib.glm_profile_end(ms, ctypes.byref(n)) == glm.GLM_EINVAL     # not recording
+
+
+def test_header_is_c_and_the_c_consumer_links():
+    """gcc -std=c99 -Wall -Wextra -Werror accepts the header and links a C program against the
+    library (the program itself runs in the GPU suite)."""
+    from paper_1802_04819_amd import build as b
+    path = b.build_c_demo()
+    assert os.path.exists(path) and os.access(path, os.X_OK)
