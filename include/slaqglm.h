@@ -211,8 +211,12 @@ typedef struct {
     float          lambda, step;
     int64_t        hist_len, hist_cap;
     int32_t        prepared; /* 0 at first: the call then builds its auxiliary column layout in the
-                                workspace (once) and sets this; set it back to 0 whenever the matrix
-                                or the workspace has changed                                         */
+                                workspace (once) and sets this to 1 (built) or 2 (not needed or not
+                                possible).  Set it back to 0 whenever the CONTENTS of the matrix or of
+                                the workspace have changed.  A value of 1 is believed only for the
+                                workspace address and column arrays it was set on (the library keeps
+                                a host-side record); otherwise the layout is built again.  Other
+                                values: GLM_EINVAL                                                   */
 } glm_sparse_job_t;
 
 /* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz only).  With more than 786,432

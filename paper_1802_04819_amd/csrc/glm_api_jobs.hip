@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 #include "api_internal.h"
 #include "glm_internal.h"
@@ -53,6 +54,34 @@ SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
     L.total = off;
     return L;
 }
+// Which workspaces hold a panelled layout, and of which matrix.  job->prepared == 1 is only
+// believed when the workspace and the column arrays are the ones the layout was built from;
+// anything else (a struct copied to another job, a reallocated workspace) rebuilds it.
+struct PanelKey {
+    const void *ws, *col_ptr, *row_idx, *col_val;
+    long long N, D, nnz;
+    bool operator==(const PanelKey &o) const {
+        return ws == o.ws && col_ptr == o.col_ptr && row_idx == o.row_idx && col_val == o.col_val &&
+               N == o.N && D == o.D && nnz == o.nnz;
+    }
+};
+std::mutex g_panel_mu;
+std::vector<PanelKey> g_panel_built;
+constexpr size_t kPanelRegistryMax = 1024;
+
+bool panel_registry_has(const PanelKey &k) {
+    std::lock_guard<std::mutex> lock(g_panel_mu);
+    for (const PanelKey &e : g_panel_built) if (e == k) return true;
+    return false;
+}
+void panel_registry_put(const PanelKey &k) {
+    std::lock_guard<std::mutex> lock(g_panel_mu);
+    // one entry per workspace: a new layout in the same memory replaces the old one
+    for (PanelKey &e : g_panel_built) if (e.ws == k.ws) { e = k; return; }
+    if (g_panel_built.size() >= kPanelRegistryMax) g_panel_built.clear();   // forgotten layouts are rebuilt
+    g_panel_built.push_back(k);
+}
+
 int validate_sparse_shape(const glm_sparse_job_t &j) {
     if (j.N < 1 || j.D < 1 || j.N >= (1LL << 31) || j.D >= (1LL << 31) || j.nnz < 0) return GLM_EINVAL;
     if (j.nnz / kSparseChunk >= (1LL << 31) - 8) return GLM_EINVAL;
@@ -80,6 +109,7 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     if (!std::isfinite(j.lambda) || j.lambda < 0.0f || !std::isfinite(j.step) || j.step < 0.0f) return GLM_EINVAL;
     if (j.hist_len < 0 || j.hist_cap < 0 || j.hist_len > j.hist_cap) return GLM_EINVAL;
     if (j.hist_len + (int64_t)iters > j.hist_cap) return GLM_ENOSPC;
+    if (j.prepared < 0 || j.prepared > 2) return GLM_EINVAL;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
     const SparseLayout L = make_sparse_layout(j.N, j.D, j.nnz);
     if (ws_bytes < L.total) return GLM_ENOSPC;
@@ -109,6 +139,8 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     pn.seg0 = reinterpret_cast<int *>(base + L.seg0P); pn.gs2 = reinterpret_cast<float *>(base + L.gs2);
     pn.flag = reinterpret_cast<int *>(base + L.flag);
     // job->prepared: 0 = nothing built yet, 1 = panelled layout in the workspace, 2 = caller's layout is used
+    const PanelKey key{ws, j.col_ptr, j.row_idx, j.col_val, j.N, j.D, j.nnz};
+    if (job->prepared == 1 && !(pn.P > 1 && j.nnz > 0 && panel_registry_has(key))) job->prepared = 0;
     if (pn.P > 1 && j.nnz > 0 && job->prepared == 0) {
         if (launch_sparse_sorted_check(a, pn, st) != hipSuccess) return GLM_EHIP;
         int unsorted = 0;
@@ -119,6 +151,7 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
             job->prepared = 2;
         } else {
             if (launch_sparse_panel_build(a, pn, st) != hipSuccess) return GLM_EHIP;
+            panel_registry_put(key);
             job->prepared = 1;
         }
     } else if (job->prepared == 0) {

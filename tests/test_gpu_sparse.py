@@ -246,3 +246,39 @@ def test_panelled_layout_reruns_and_split_calls_bit_identical():
     for o in outs[1:]:
         for x, z in zip(outs[0], o):
             assert torch.equal(x, z)
+
+
+def test_prepared_flag_is_only_believed_for_the_workspace_it_was_set_on():
+    _say("[case] sparse with panels: two jobs taking turns on one workspace; a forged flag on a fresh workspace")
+    A, B = _tall(21), _tall(22, N=1_000_003, D=200, nnz=2_000_000)
+    ya = _labels(synth.LOGISTIC, A.shape[0], np.random.default_rng(6))
+    yb = _labels(synth.LOGISTIC, B.shape[0], np.random.default_rng(7))
+    # references: each job alone on a workspace of its own
+    refs = []
+    for M, y in ((A, ya), (B, yb)):
+        job, _ = _job_from_scipy(M, y, synth.LOGISTIC, 1e-4, 0.5, 4)
+        glm.glm_step_sparse(job, 4, glm.alloc_sparse_workspace(job))
+        torch.cuda.synchronize()
+        refs.append((job.history().cpu().clone(), job.w.cpu().clone()))
+    ja, _ = _job_from_scipy(A, ya, synth.LOGISTIC, 1e-4, 0.5, 4)
+    jb, _ = _job_from_scipy(B, yb, synth.LOGISTIC, 1e-4, 0.5, 4)
+    wa, wb = glm.alloc_sparse_workspace(ja), glm.alloc_sparse_workspace(jb)
+    shared = wa if wa.numel() >= wb.numel() else wb
+    for _ in range(2):                      # A, B, A, B on the same memory, two iterations each
+        for job in (ja, jb):
+            glm.glm_step_sparse(job, 2, shared)
+            assert job.c.prepared == 1
+    torch.cuda.synchronize()
+    for job, ref in ((ja, refs[0]), (jb, refs[1])):
+        assert torch.equal(job.history().cpu(), ref[0]) and torch.equal(job.w.cpu(), ref[1])
+    # a struct that claims a layout which this (new, zero-filled) workspace does not hold
+    jc, _ = _job_from_scipy(A, ya, synth.LOGISTIC, 1e-4, 0.5, 4)
+    jc.c.prepared = 1
+    fresh = torch.zeros_like(wa)
+    glm.glm_step_sparse(jc, 4, fresh)
+    torch.cuda.synchronize()
+    assert torch.equal(jc.history().cpu(), refs[0][0]) and torch.equal(jc.w.cpu(), refs[0][1])
+    jc.c.prepared = 3
+    with pytest.raises(glm.GlmError) as e:
+        glm.glm_step_sparse(jc, 0, fresh)
+    assert e.value.status == glm.GLM_EINVAL
