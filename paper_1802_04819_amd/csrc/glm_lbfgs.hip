@@ -32,9 +32,12 @@ __global__ __launch_bounds__(kLbThreads) void lbfgs_direction_kernel(LbArgs a, c
     __shared__ double red[kLbThreads / 64];
     __shared__ double alpha[kLbMaxMemory];
     const int tid = threadIdx.x, D = a.D, m = a.memory;
+    // The counters live in the caller's workspace: clamp them, so that a state that claims
+    // "started" over memory that never held a ring cannot index outside S and Y.
     int pairs = reset ? 0 : a.ring[0];
-    const int head = reset ? 0 : a.ring[1];
-    if (m == 0) pairs = 0;
+    int head = reset ? 0 : a.ring[1];
+    pairs = m == 0 ? 0 : min(max(pairs, 0), m);
+    head = m == 0 ? 0 : min(max(head, 0), m - 1);
     double q[kLbPer], gv[kLbPer];
     double gg = 0.0;
 #pragma unroll
@@ -127,7 +130,8 @@ __global__ __launch_bounds__(kLbThreads) void lbfgs_accept_kernel(LbArgs a, floa
     }
     sy = lb_block_sum(sy, red);
     yy = lb_block_sum(yy, red);
-    const int pairs = a.ring[0], head = a.ring[1];
+    const int pairs = m > 0 ? min(max(a.ring[0], 0), m) : 0;
+    const int head = m > 0 ? min(max(a.ring[1], 0), m - 1) : 0;
     const bool keep = m > 0 && sy > 1e-10 * yy;
     __syncthreads();                                   // every thread has read the counters
 #pragma unroll
