@@ -1,17 +1,21 @@
 // K-Means (Lloyd) iteration for gfx950.
 //
 //   norms      : cn[k] = |c_k|^2 (fp32), +inf for the padding slots past K.
-//   assign     : per tile of TR points held in LDS, the products x_i . c_k for 64 centroids at a
-//                time on the matrix cores (v_mfma_f32_32x32x2_f32, fp32 in, fp32 accumulate);
-//                the nearest centroid minimises cn[k] - 2 x_i . c_k (the |x_i|^2 term is common
-//                to all k), lowest index on equal values.  The squared distance that enters the
-//                loss is then recomputed for the chosen centroid as sum_j (x_ij - c_kj)^2, which
-//                has no cancellation.  Writes assign[i] and one loss partial per tile.
+//   assign     : the nearest centroid minimises cn[k] - 2 x_i . c_k (the |x_i|^2 term is common to
+//                all k), lowest index on equal values.  Three kernels, by shape: at most 32
+//                centroids on the vector units, a row per lane; otherwise D <= 128 with operands
+//                split into bfloat16 parts on the matrix cores, centroids stationary in
+//                registers; otherwise per tile of TR points held in LDS, 64 centroids at a time
+//                (v_mfma_f32_32x32x2_f32, fp32 in, fp32 accumulate).  The squared distance that
+//                enters the loss is recomputed for the chosen centroid as sum_j (x_ij - c_kj)^2,
+//                which has no cancellation: by the two matrix-core kernels themselves (the tile
+//                is still in LDS), by the accumulation pass for the first (whose rows are gone).
 //   accumulate : second pass over X.  A wave owns a slab of 64 columns, a contiguous range of
 //                rows and up to 32 clusters, keeps their sums in registers and adds the rows
 //                assigned to them in row order.  Partials go to part[split].
-//   finalize   : per centroid, adds the partials in split order (fp64), divides by the cluster
-//                size (an empty cluster keeps its centroid), and sums the loss partials.
+//   finalize   : per centroid and 16 columns, adds the partials in a fixed order (fp64: sixteen
+//                interleaved runs over the splits, then the runs), divides by the cluster size
+//                (an empty cluster keeps its centroid), and sums the loss partials.
 //
 // Lane layout of the 32x32x2 instruction (lane l of 64): A[i][k] from lane i + 32 k,
 // B[k][j] from lane j + 32 k, D[i][j] in lane j + 32 ((i / 4) % 2), register (i % 4) + 4 (i / 8).
@@ -33,21 +37,23 @@ static size_t assign_lds_bytes(int TR, int Dp) {
 
 KmShape km_shape(long long N, int D, int K) {
     KmShape s;
-    s.split = D <= kKmSplitMaxD;
+    s.small = K <= kKmSmallK;
+    s.split = !s.small && D <= kKmSplitMaxD;
     s.Dp = s.split ? (D + 63) / 64 * 64 : (D + 31) / 32 * 32;
     s.Kp = s.split ? (K + 255) / 256 * 256 : (K + kKmChunk - 1) / kKmChunk * kKmChunk;
-    s.TR = s.split ? 32 : 128;
-    while (!s.split && s.TR > 32 && assign_lds_bytes(s.TR, s.Dp) > kLdsBudget) s.TR /= 2;
+    s.TR = s.small ? kKmSmallRows : s.split ? 32 : 128;
+    while (!s.small && !s.split && s.TR > 32 && assign_lds_bytes(s.TR, s.Dp) > kLdsBudget) s.TR /= 2;
     s.T = (N + s.TR - 1) / s.TR;
-    s.lds_assign = s.split ? 0 : assign_lds_bytes(s.TR, s.Dp);
+    s.lds_assign = (s.small || s.split) ? 0 : assign_lds_bytes(s.TR, s.Dp);
     // split path: a fixed grid of persistent blocks (one per compute unit), contiguous tile ranges
     s.tiles_per_block = (s.T + 255) / 256;
     s.stream_blocks = (int)((s.T + s.tiles_per_block - 1) / s.tiles_per_block);     // no block without tiles
-    s.lossN = s.split ? (long long)s.stream_blocks * 8 : s.T;
     s.nslab = (D + 63) / 64;
     s.G = (K + 31) / 32;
     // row splits: at most 1024, at least 1024 rows each, and at most 1 GiB of partial sums
     long long pmax = 1024;
+    const long long owners = (long long)s.G * s.nslab;                // waves per row split
+    if (owners * pmax < 8192) pmax = (8192 + owners - 1) / owners;    // few owners: more splits keep enough rows in flight
     const long long cap = (1LL << 28) / ((long long)K * D);
     if (pmax > cap) pmax = cap < 1 ? 1 : cap;
     long long rps = (N + pmax - 1) / pmax;
@@ -55,6 +61,9 @@ KmShape km_shape(long long N, int D, int K) {
     rps = (rps + 63) / 64 * 64;
     s.rows_per_split = rps;
     s.P = (int)((N + rps - 1) / rps);
+    // loss partials: one per wave of the accumulation pass (few centroids), else per wave of the
+    // streaming assignment or per tile
+    s.lossN = s.small ? owners * s.P : s.split ? (long long)s.stream_blocks * 8 : s.T;
     return s;
 }
 
@@ -227,6 +236,96 @@ __global__ __launch_bounds__(TR * 2) void kmeans_assign_kernel(
     }
 }
 
+// ---- Assignment for few centroids (K <= 32) -------------------------------------------------
+//
+// With at most 32 centroids a matrix tile would be mostly padding, and the products are cheap
+// enough for the vector units: a lane owns a row and keeps x_i . c_k for every k in registers.
+// The centroid values are the same for all lanes, so they arrive through the scalar data path
+// (read-only) and cost no vector register or LDS traffic.  The rows reach their lanes through
+// LDS: 32 columns of 256 rows at a time, loaded so that eight lanes read one row's 128 bytes,
+// stored with an odd row stride.
+constexpr int kSmCols = 32;
+constexpr int kSmLd = kSmCols + 1;
+
+template <int KG>                         // groups of eight centroids: K <= 8 KG
+__global__ __launch_bounds__(kKmSmallRows) void kmeans_assign_small_kernel(
+    const float *__restrict__ X, const float *__restrict__ C, const float *__restrict__ cn, long long N, int D,
+    int K, int *__restrict__ assign) {
+    __shared__ float xs[kKmSmallRows * kSmLd];
+    const int tid = threadIdx.x;
+    const long long r0 = (long long)blockIdx.x * kKmSmallRows;
+    const int rows = (int)((N - r0) < kKmSmallRows ? (N - r0) : kKmSmallRows);
+    const int D4 = D >> 2;
+    const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X) + r0 * D4;
+    const f4 *__restrict__ C4 = reinterpret_cast<const f4 *>(C);
+    const int nch = (D + kSmCols - 1) / kSmCols;
+
+    float acc[8 * KG];
+#pragma unroll
+    for (int k = 0; k < 8 * KG; ++k) acc[k] = 0.0f;
+
+    // piece ch of the tile: thread t brings float4 number (t & 7) of rows (t >> 3) + 32 q
+    f4 pre[8];
+#define SLAQ_SM_FETCH(CH)                                                                    \
+    {                                                                                        \
+        const int c4_ = (CH) * (kSmCols / 4) + (tid & 7);                                    \
+        _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                      \
+            const int row_ = (tid >> 3) + 32 * q;                                            \
+            f4 v_ = {0.0f, 0.0f, 0.0f, 0.0f};                                                \
+            if (row_ < rows && c4_ < D4) v_ = X4[(size_t)row_ * D4 + c4_];                   \
+            pre[q] = v_;                                                                     \
+        }                                                                                    \
+    }
+    SLAQ_SM_FETCH(0);
+    for (int ch = 0; ch < nch; ++ch) {
+        if (ch) __syncthreads();                       // the previous piece has been read
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            float *dst = xs + ((tid >> 3) + 32 * q) * kSmLd + 4 * (tid & 7);
+            dst[0] = pre[q][0]; dst[1] = pre[q][1]; dst[2] = pre[q][2]; dst[3] = pre[q][3];
+        }
+        __syncthreads();
+        if (ch + 1 < nch) SLAQ_SM_FETCH(ch + 1);
+        float x[kSmCols];
+#pragma unroll
+        for (int j = 0; j < kSmCols; ++j) x[j] = xs[tid * kSmLd + j];
+        // Straight-line body: the scalar loads of a group of eight centroids go out together and
+        // the next group's can be issued under this group's arithmetic.  Columns past D hold
+        // x = 0 and re-read the last column; slots past K re-read the last centroid (never
+        // chosen: the argmin below stops at K).
+#pragma unroll
+        for (int jg = 0; jg < kSmCols / 4; ++jg) {
+            const int col4 = ch * (kSmCols / 4) + jg < D4 ? ch * (kSmCols / 4) + jg : D4 - 1;
+#pragma unroll
+            for (int g = 0; g < KG; ++g) {
+                f4 c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c[u] = C4[(size_t)(8 * g + u < K ? 8 * g + u : K - 1) * D4 + col4];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    float a = acc[8 * g + u];
+                    a = __builtin_fmaf(x[4 * jg], c[u][0], a);
+                    a = __builtin_fmaf(x[4 * jg + 1], c[u][1], a);
+                    a = __builtin_fmaf(x[4 * jg + 2], c[u][2], a);
+                    a = __builtin_fmaf(x[4 * jg + 3], c[u][3], a);
+                    acc[8 * g + u] = a;
+                }
+            }
+        }
+    }
+#undef SLAQ_SM_FETCH
+    float bv = std::numeric_limits<float>::infinity();
+    int bk = 0;
+#pragma unroll
+    for (int k = 0; k < 8 * KG; ++k) {
+        if (k < K) {
+            const float v = __builtin_fmaf(-2.0f, acc[k], cn[k]);
+            if (v < bv) { bv = v; bk = k; }
+        }
+    }
+    if (tid < rows) assign[r0 + tid] = bk;
+}
+
 // ---- Assignment with split operands (D <= 128) ---------------------------------------------
 //
 // An fp32 value is the exact sum of three bfloat16 values (8 + 8 + 8 significant bits, same
@@ -240,10 +339,7 @@ __global__ __launch_bounds__(TR * 2) void kmeans_assign_kernel(
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u4 __attribute__((ext_vector_type(4)));
 
-constexpr int kSpK = 64;                   // columns per staged piece
-constexpr int kSpRowB = 2 * kSpK + 16;     // bytes per centroid row of a piece in LDS (padded)
-constexpr int kSpArrB = kKmChunk * kSpRowB;          // one of the three split arrays of a piece
-constexpr int kSpBufB = 3 * kSpArrB;                 // a piece
+constexpr int kSpK = 64;                   // the split path pads D to a multiple of this
 
 // bfloat16 bit patterns (in the high halves) of the three parts of x
 __device__ __forceinline__ void split3(float x, unsigned &h, unsigned &m, unsigned &l) {
@@ -495,9 +591,14 @@ __global__ __launch_bounds__(512) void kmeans_assign_stream_kernel(
 typedef float floatx32 __attribute__((ext_vector_type(32)));
 constexpr int kAccJ = 8;                   // rows gathered per round
 
+// LOSS: the pass also adds sum_j (x_ij - c_kj)^2 with the entering centroid of the row's cluster
+// (read through the cache, next to the row itself) and writes one partial per wave; used when the
+// assignment kernel does not produce the loss.
+template <bool LOSS>
 __global__ __launch_bounds__(256) void kmeans_accumulate_kernel(
-    const float *__restrict__ X, const int *__restrict__ assign, long long N, int D, int K, int G, int nslab,
-    long long rows_per_split, long long total_waves, float *__restrict__ part, int *__restrict__ cntP) {
+    const float *__restrict__ X, const float *__restrict__ C, const int *__restrict__ assign, long long N, int D,
+    int K, int G, int nslab, long long rows_per_split, long long total_waves, float *__restrict__ part,
+    int *__restrict__ cntP, float *__restrict__ lossP) {
     const int lane = threadIdx.x & 63;
     const long long wg = blockIdx.x * 4LL + (threadIdx.x >> 6);
     if (wg >= total_waves) return;
@@ -512,6 +613,8 @@ __global__ __launch_bounds__(256) void kmeans_accumulate_kernel(
     const float *__restrict__ xc = X + (active ? col : 0);
 
     floatx32 acc = {0};
+    const float *__restrict__ cc = C + (active ? col : 0);
+    float dsum = 0.0f;                     // LOSS: this lane's column, rows in order
     int size = 0;                          // lane l counts the rows of local cluster l
     for (long long r = rb; r < re; r += 64) {
         const long long row = r + lane;
@@ -519,21 +622,26 @@ __global__ __launch_bounds__(256) void kmeans_accumulate_kernel(
         const int local = av / G;
         unsigned long long mask = __ballot(av >= 0 && av - local * G == w);
         while (mask) {
-            float v[kAccJ]; int a[kAccJ];
+            float v[kAccJ], c[kAccJ]; int a[kAccJ];
 #pragma unroll
             for (int j = 0; j < kAccJ; ++j) {
-                a[j] = -1; v[j] = 0.0f;
+                a[j] = -1; v[j] = 0.0f; c[j] = 0.0f;
                 if (mask) {
                     const int u = __builtin_ctzll(mask);
                     mask &= mask - 1;
                     a[j] = __builtin_amdgcn_readlane(local, u);
                     v[j] = __builtin_nontemporal_load(xc + (r + u) * D);
+                    if (LOSS) c[j] = cc[(size_t)(a[j] * G + w) * D];
                 }
             }
 #pragma unroll
             for (int j = 0; j < kAccJ; ++j)
                 if (a[j] >= 0) {
                     acc[a[j]] += v[j];
+                    if (LOSS) {
+                        const float t_ = v[j] - c[j];
+                        dsum = __builtin_fmaf(t_, t_, dsum);
+                    }
                     size += lane == a[j] ? 1 : 0;
                 }
         }
@@ -544,6 +652,11 @@ __global__ __launch_bounds__(256) void kmeans_accumulate_kernel(
         if (k < K && active) part[((size_t)p * K + k) * D + col] = acc[l];
     }
     if (slab == 0 && lane < 32 && lane * G + w < K) cntP[(size_t)p * K + lane * G + w] = size;
+    if (LOSS) {
+        if (!active) dsum = 0.0f;
+        for (int o = 32; o >= 1; o >>= 1) dsum += __shfl_xor(dsum, o, 64);
+        if (lane == 0) lossP[wg] = dsum;
+    }
 }
 
 __global__ __launch_bounds__(256) void kmeans_finalize_kernel(
@@ -551,6 +664,7 @@ __global__ __launch_bounds__(256) void kmeans_finalize_kernel(
     int P, long long N, int D, int K, float *__restrict__ C, int *__restrict__ counts, float *__restrict__ loss_out) {
     __shared__ int redi[256];
     __shared__ double redd[256];
+    // block (k, slab of 16 columns); thread = (split lane pl of 16, column dc of 16)
     const int k = blockIdx.x, tid = threadIdx.x;
     int n = 0;
     for (int p = tid; p < P; p += 256) n += cntP[(size_t)p * K + k];
@@ -561,23 +675,34 @@ __global__ __launch_bounds__(256) void kmeans_finalize_kernel(
         __syncthreads();
     }
     const int size = redi[0];
-    if (tid == 0) counts[k] = size;
-    for (int d = tid; d < D; d += 256) {
-        const float *__restrict__ pp = part + (size_t)k * D + d;
-        const size_t stride = (size_t)K * D;
+    if (tid == 0 && blockIdx.y == 0) counts[k] = size;
+    const int pl = tid >> 4, dc = tid & 15;
+    const int d = blockIdx.y * 16 + dc;
+    {
+        // splits pl, pl + 16, ... in order, then the sixteen lanes in order: a fixed sequence
         double tot = 0.0;
-        int p = 0;
-        for (; p + 16 <= P; p += 16) {
-            float v[16];
+        if (d < D) {
+            const float *__restrict__ pp = part + (size_t)k * D + d;
+            const size_t stride = (size_t)K * D;
+            int p = pl;
+            for (; p + 16 * 7 < P; p += 16 * 8) {
+                float v[8];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) v[u] = pp[(size_t)(p + u) * stride];
+                for (int u = 0; u < 8; ++u) v[u] = pp[(size_t)(p + 16 * u) * stride];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) tot += (double)v[u];
+                for (int u = 0; u < 8; ++u) tot += (double)v[u];
+            }
+            for (; p < P; p += 16) tot += (double)pp[(size_t)p * stride];
         }
-        for (; p < P; ++p) tot += (double)pp[(size_t)p * stride];
-        if (size > 0) C[(size_t)k * D + d] = (float)(tot / (double)size);
+        redd[tid] = tot;
+        __syncthreads();
+        if (pl == 0 && d < D) {
+            for (int q = 1; q < 16; ++q) tot += redd[16 * q + dc];
+            if (size > 0) C[(size_t)k * D + d] = (float)(tot / (double)size);
+        }
+        __syncthreads();
     }
-    if (k == 0) {
+    if (k == 0 && blockIdx.y == 0) {
         // loss: thread t adds a contiguous run of the tile partials, then a fixed tree
         double s = 0.0;
         for (long long t = T * tid / 256; t < T * (tid + 1) / 256; ++t) s += (double)lossP[t];
@@ -618,7 +743,16 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
-    if (a.s.split) {
+    if (a.s.small) {
+        const dim3 grid((unsigned)a.s.T), block(kKmSmallRows);
+        switch ((a.K + 7) / 8) {
+        case 1: hipLaunchKernelGGL(kmeans_assign_small_kernel<1>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 2: hipLaunchKernelGGL(kmeans_assign_small_kernel<2>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 3: hipLaunchKernelGGL(kmeans_assign_small_kernel<3>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        default: hipLaunchKernelGGL(kmeans_assign_small_kernel<4>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        }
+        e = hipGetLastError();
+    } else if (a.s.split) {
         const size_t lds = (size_t)4 * 3 * kStRows * (2 * a.s.Dp + 16) + 2 * kStWaves * kStRows * sizeof(float2);
         const void *fn = a.s.Dp == 64 ? reinterpret_cast<const void *>(&kmeans_assign_stream_kernel<1>)
                                       : reinterpret_cast<const void *>(&kmeans_assign_stream_kernel<2>);
@@ -643,11 +777,15 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
     if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
     const long long waves = (long long)a.s.P * a.s.nslab * a.s.G;
-    hipLaunchKernelGGL(kmeans_accumulate_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, a.X, a.assign,
-                       a.N, a.D, a.K, a.s.G, a.s.nslab, a.s.rows_per_split, waves, a.part, a.cntP);
+    if (a.s.small)
+        hipLaunchKernelGGL(kmeans_accumulate_kernel<true>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, a.X, a.C,
+                           a.assign, a.N, a.D, a.K, a.s.G, a.s.nslab, a.s.rows_per_split, waves, a.part, a.cntP, a.lossP);
+    else
+        hipLaunchKernelGGL(kmeans_accumulate_kernel<false>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, a.X, a.C,
+                           a.assign, a.N, a.D, a.K, a.s.G, a.s.nslab, a.s.rows_per_split, waves, a.part, a.cntP, a.lossP);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
-    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((unsigned)a.K), dim3(256), 0, st, a.part, a.cntP, a.lossP, a.s.lossN,
+    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((unsigned)a.K, (unsigned)((a.D + 15) / 16)), dim3(256), 0, st, a.part, a.cntP, a.lossP, a.s.lossN,
                        a.s.P, a.N, a.D, a.K, a.C, a.counts, a.loss_out + k);
     return hipGetLastError();
 }
