@@ -2,8 +2,9 @@
 //
 //   norms      : cn[k] = |c_k|^2 (fp32), +inf for the padding slots past K.
 //   assign     : the nearest centroid minimises cn[k] - 2 x_i . c_k (the |x_i|^2 term is common to
-//                all k), lowest index on equal values.  Three kernels, by shape: at most 32
-//                centroids on the vector units, a row per lane; otherwise D <= 128 with operands
+//                all k), lowest index on equal values.  Three kernels, by shape: few centroids
+//                (K <= 32, or K <= 64 and K D <= 4096) on the vector units, a row per lane;
+//                otherwise D <= 128 with operands
 //                split into bfloat16 parts on the matrix cores, centroids stationary in
 //                registers; otherwise per tile of TR points held in LDS, 64 centroids at a time
 //                (v_mfma_f32_32x32x2_f32, fp32 in, fp32 accumulate).  The squared distance that
@@ -37,7 +38,7 @@ static size_t assign_lds_bytes(int TR, int Dp) {
 
 KmShape km_shape(long long N, int D, int K) {
     KmShape s;
-    s.small = K <= kKmSmallK;
+    s.small = K <= 32 || (K <= kKmSmallK && (long long)K * D <= kKmSmallWork);
     s.split = !s.small && D <= kKmSplitMaxD;
     s.Dp = s.split ? (D + 63) / 64 * 64 : (D + 31) / 32 * 32;
     s.Kp = s.split ? (K + 255) / 256 * 256 : (K + kKmChunk - 1) / kKmChunk * kKmChunk;
@@ -236,9 +237,9 @@ __global__ __launch_bounds__(TR * 2) void kmeans_assign_kernel(
     }
 }
 
-// ---- Assignment for few centroids (K <= 32) -------------------------------------------------
+// ---- Assignment for few centroids (K <= 32, or K <= 64 with K D <= 4096) --------------------
 //
-// With at most 32 centroids a matrix tile would be mostly padding, and the products are cheap
+// With so few centroids a matrix tile would be mostly padding, and the products are cheap
 // enough for the vector units: a lane owns a row and keeps x_i . c_k for every k in registers.
 // The centroid values are the same for all lanes, so they arrive through the scalar data path
 // (read-only) and cost no vector register or LDS traffic.  The rows reach their lanes through
@@ -749,7 +750,11 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
         case 1: hipLaunchKernelGGL(kmeans_assign_small_kernel<1>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
         case 2: hipLaunchKernelGGL(kmeans_assign_small_kernel<2>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
         case 3: hipLaunchKernelGGL(kmeans_assign_small_kernel<3>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
-        default: hipLaunchKernelGGL(kmeans_assign_small_kernel<4>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 4: hipLaunchKernelGGL(kmeans_assign_small_kernel<4>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 5: hipLaunchKernelGGL(kmeans_assign_small_kernel<5>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 6: hipLaunchKernelGGL(kmeans_assign_small_kernel<6>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 7: hipLaunchKernelGGL(kmeans_assign_small_kernel<7>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        default: hipLaunchKernelGGL(kmeans_assign_small_kernel<8>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
         }
         e = hipGetLastError();
     } else if (a.s.split) {

@@ -11,13 +11,14 @@ constexpr int kKmMaxD = 1024;           // the X tile of the assignment kernel m
 constexpr int kKmMaxK = 1024;           // 32 owner groups of 32 clusters in the accumulation pass
 constexpr int kKmSplitMaxD = 128;       // up to here a row's split operands fit in a lane pair's registers
 constexpr int kKmChunk = 64;            // centroids per matrix-core chunk
-constexpr int kKmSmallK = 32;           // up to here the assignment runs on the vector units, a row per lane
+constexpr int kKmSmallK = 64;           // up to here the assignment may run on the vector units, a row per lane
+constexpr int kKmSmallWork = 4096;      // ... beyond 32 centroids only while K * D stays below this
 constexpr int kKmSmallRows = 256;       // rows per block of that kernel
 
 // Shapes derived from (N, D, K) alone, so that every call on the same problem runs the same
 // launches and adds in the same order.
 struct KmShape {
-    bool small;          // K <= 32: assignment on the vector units (too few centroids to fill a matrix tile)
+    bool small;          // few centroids: assignment on the vector units (a matrix tile would be mostly padding)
     bool split;          // otherwise, D <= 128: assignment with three-way bfloat16 operands
     int TR;              // rows per assignment tile (128, 64 or 32)
     int Dp;              // D rounded up to a multiple of 64 (split) or 32

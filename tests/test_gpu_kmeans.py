@@ -83,10 +83,12 @@ SHAPES = [
     # N, D, K: tiles, ragged tails, every tile height and slab width
     (5000, 128, 64), (4097, 32, 7), (300, 4, 3), (2500, 36, 65), (1111, 260, 20), (700, 1024, 9),
     (6000, 64, 300), (3000, 16, 1024), (129, 8, 1), (64, 128, 64),
-    # at most 32 centroids (vector-unit assignment): group-of-eight boundaries, ragged last column
+    # few centroids (vector-unit assignment): group-of-eight boundaries, ragged last column
     # piece, one and two row tiles, and the first K on the matrix-core side
     (513, 100, 32), (256, 36, 17), (257, 68, 8), (40, 12, 25), (10000, 128, 16), (777, 44, 24),
     (3000, 512, 31), (2000, 64, 33),
+    # 33 to 64 centroids stay on the vector units while K * D <= 4096
+    (3000, 64, 64), (2000, 32, 50), (1500, 100, 40), (1500, 104, 40), (900, 16, 57),
 ]
 
 
