@@ -4,8 +4,9 @@ epoch is fixed, and two policies share it: equal shares (the work-conserving fai
 quality-driven loop (predict every job's next reductions, allocate greedily).  The paper's own
 numbers (average normalised loss 73 % lower, 45 % less time to a 90 % loss reduction) come from its
 cluster and data sets and are context only; here the test states what holds on this workload:
-the quality-driven run has the lower time-averaged normalised loss, and more of its jobs reach a
-90 % loss reduction inside the window, sooner on average.
+the quality-driven run has the lower time-averaged normalised loss, more of its jobs reach a
+90 % loss reduction inside the window, sooner on average, and it moves capacity from the better half
+of the jobs to the quarter with the highest loss (the paper's figure of shares by loss group).
 """
 import numpy as np
 import pytest
@@ -28,6 +29,7 @@ def _simulate(policy, probs, arrive, E, C, H):
     fit = torch.zeros(J, 8, dtype=torch.float64, device="cuda")
     curves = [glm.GLM_CURVE_LINEAR if p.loss == synth.SQUARED else glm.GLM_CURVE_SUBLINEAR for p in probs]
     trace = np.full((E + 1, J), np.nan)                # loss of every arrived job at the start of each epoch
+    allocs = np.zeros((E, J), np.int64)
     for e in range(E):
         active = [j for j in range(J) if arrive[j] <= e]
         alloc = np.zeros(J, np.int32)
@@ -54,13 +56,14 @@ def _simulate(policy, probs, arrive, E, C, H):
             for r, j in enumerate(active):
                 alloc[j] = a[r]
         assert alloc[active].min() >= 1 and alloc.sum() <= C
+        allocs[e] = alloc
         glm.glm_step_batched(jobs, alloc, ws)
         torch.cuda.synchronize()
         for j in active:
             trace[e + 1, j] = jobs[j].loss_hist[jobs[j].hist_len - 1].item()
             if np.isnan(trace[e, j]):
                 trace[e, j] = jobs[j].loss_hist[0].item()
-    return trace, [j.history().cpu().numpy() for j in jobs]
+    return trace, [j.history().cpu().numpy() for j in jobs], allocs
 
 
 def test_arriving_jobs_quality_driven_versus_fair():
@@ -77,8 +80,8 @@ def test_arriving_jobs_quality_driven_versus_fair():
     arrive = np.minimum(np.cumsum(rng.poisson(0.5, size=J)), E - 6)      # about two arrivals per epoch
     arrive[0] = 0
     C = 120
-    tf, hf = _simulate("fair", probs, arrive, E, C, H)
-    tg, hg = _simulate("greedy", probs, arrive, E, C, H)
+    tf, hf, af = _simulate("fair", probs, arrive, E, C, H)
+    tg, hg, ag = _simulate("greedy", probs, arrive, E, C, H)
     first = np.array([h[0] for h in hf])
     floor = np.array([min(a.min(), b.min()) for a, b in zip(hf, hg)])
     span = np.maximum(first - floor, 1e-30)
@@ -108,3 +111,24 @@ def test_arriving_jobs_quality_driven_versus_fair():
          f"mean epochs to get there (window-censored): fair {cens_f:.2f}, quality-driven {cens_g:.2f}")
     assert avg_g.mean() < avg_f.mean()
     assert reached_g >= reached_f and cens_g <= cens_f
+
+    # Where the capacity goes (Sec. 3, the figure of resource shares by loss group): per epoch the
+    # arrived jobs are ranked by normalised loss; the quarter with the highest loss, the next
+    # quarter and the better half.  Equal shares give them 25 / 25 / 50 % by construction.
+    def shares(n, allocs):
+        out = []
+        for e in range(E):
+            act = np.nonzero(arrive <= e)[0]
+            if len(act) < 8:
+                continue
+            order = act[np.argsort(-n[e, act], kind="stable")]
+            q = len(order) // 4
+            tot = allocs[e, act].sum()
+            out.append([allocs[e, order[:q]].sum() / tot, allocs[e, order[q:2 * q]].sum() / tot,
+                        allocs[e, order[2 * q:]].sum() / tot])
+        return np.mean(out, axis=0)
+
+    sf, sg = shares(nf, af), shares(ng, ag)
+    _say("  share of the capacity by loss group (highest quarter / next quarter / better half): "
+         f"fair {sf[0]:.2f} / {sf[1]:.2f} / {sf[2]:.2f}, quality-driven {sg[0]:.2f} / {sg[1]:.2f} / {sg[2]:.2f}")
+    assert sg[0] > sf[0] and sg[2] < sf[2]
