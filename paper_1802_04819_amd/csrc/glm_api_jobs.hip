@@ -167,11 +167,13 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
 }
 
 namespace {
-struct KmLayout { size_t cn, Cs, lossP, bestv, part, cntP, total; KmShape s; };
+struct KmLayout { size_t mean, Cc, cn, Cs, lossP, bestv, part, cntP, total; KmShape s; };
 KmLayout make_kmeans_layout(long long N, int D, int K) {
     KmLayout L;
     L.s = km_shape(N, D, K);
     size_t off = 0;
+    L.mean = off;  off = api_align_up(off + sizeof(float) * (size_t)D);
+    L.Cc = off;    off = api_align_up(off + sizeof(float) * (size_t)K * D);
     L.cn = off;    off = api_align_up(off + sizeof(float) * (size_t)L.s.Kp);
     L.Cs = off;    off = api_align_up(off + sizeof(unsigned short) * 3 * (size_t)L.s.Kp * L.s.Dp);
     L.lossP = off; off = api_align_up(off + sizeof(float) * (size_t)L.s.lossN);
@@ -217,6 +219,7 @@ int glm_kmeans_step(glm_kmeans_job_t *job, int32_t iters, void *ws, size_t ws_by
     KmArgs a;
     a.X = j.X; a.C = j.C; a.assign = j.assign; a.counts = j.counts; a.loss_out = j.loss_hist + j.hist_len;
     a.N = j.N; a.D = j.D; a.K = j.K;
+    a.mean = reinterpret_cast<float *>(base + L.mean); a.Cc = reinterpret_cast<float *>(base + L.Cc);
     a.Cs = reinterpret_cast<unsigned short *>(base + L.Cs);
     a.bestv = reinterpret_cast<float *>(base + L.bestv);
     a.cn = reinterpret_cast<float *>(base + L.cn); a.lossP = reinterpret_cast<float *>(base + L.lossP);

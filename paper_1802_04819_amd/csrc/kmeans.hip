@@ -1,6 +1,9 @@
 // K-Means (Lloyd) iteration for gfx950.
 //
-//   norms      : cn[k] = |c_k|^2 (fp32), +inf for the padding slots past K.
+//   shift      : once per call, the column means of a sample of the rows; the assignment works
+//                on points and centroids minus this shift (distances are unchanged, the fp32
+//                rounding of the expanded form is not: it scales with |x|^2 + |c|^2).
+//   center     : Cc = C - shift, cn[k] = |Cc_k|^2 (fp32), +inf for the padding slots past K.
 //   assign     : the nearest centroid minimises cn[k] - 2 x_i . c_k (the |x_i|^2 term is common to
 //                all k), lowest index on equal values.  Three kernels, by shape: few centroids
 //                (K <= 32, or K <= 64 and K D <= 4096) on the vector units, a row per lane;
@@ -72,15 +75,55 @@ __device__ __forceinline__ floatx16 km_mfma(float a, float b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
-__global__ __launch_bounds__(256) void kmeans_norms_kernel(const float *__restrict__ C, int D, int K, int Kp,
-                                                           float *__restrict__ cn) {
+// The common shift: column means over at most 1024 evenly spaced rows.  Distances do not change
+// when the points and the centroids are shifted together, but the fp32 rounding of the expanded
+// form |c|^2 - 2 x . c scales with |x|^2 + |c|^2, so data far from the origin would lose the
+// near ties; after the shift both are of the size of the data's spread.  One slice of the
+// sample per wave, the sixteen waves added in order.
+constexpr int kKmMeanSample = 1024;
+constexpr int kKmMeanWaves = 16;
+
+__global__ __launch_bounds__(64 * kKmMeanWaves) void kmeans_mean_kernel(const float *__restrict__ X, long long N, int D,
+                                                                        float *__restrict__ mean) {
+    __shared__ float red[kKmMeanWaves][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + lane;
+    const long long S = N < kKmMeanSample ? N : kKmMeanSample;
+    const long long stride = N / S;
+    float s = 0.0f;
+    if (col < D) {
+        // sample rows wave, wave + 16, ...: eight loads in flight, added in order
+        long long i = wave;
+        for (; i + 7 * kKmMeanWaves < S; i += 8 * kKmMeanWaves) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = X[(size_t)((i + u * kKmMeanWaves) * stride) * D + col];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; i < S; i += kKmMeanWaves) s += X[(size_t)(i * stride) * D + col];
+    }
+    red[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && col < D) {
+        float t = red[0][lane];
+        for (int w = 1; w < kKmMeanWaves; ++w) t += red[w][lane];
+        mean[col] = t / (float)S;
+    }
+}
+
+// Cc = C - mean, cn[k] = |Cc_k|^2 (+inf for the padding slots past K): one wave per centroid.
+__global__ __launch_bounds__(256) void kmeans_center_kernel(const float *__restrict__ C, const float *__restrict__ mean,
+                                                            int D, int K, int Kp, float *__restrict__ Cc,
+                                                            float *__restrict__ cn) {
     const int lane = threadIdx.x & 63;
     const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (k >= Kp) return;
     float s = 0.0f;
     if (k < K)
         for (int j = lane; j < D; j += 64) {
-            const float c = C[(size_t)k * D + j];
+            const float c = C[(size_t)k * D + j] - mean[j];
+            Cc[(size_t)k * D + j] = c;
             s = __builtin_fmaf(c, c, s);
         }
     for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
@@ -89,8 +132,9 @@ __global__ __launch_bounds__(256) void kmeans_norms_kernel(const float *__restri
 
 template <int TR>
 __global__ __launch_bounds__(TR * 2) void kmeans_assign_kernel(
-    const float *__restrict__ X, const float *__restrict__ C, const float *__restrict__ cn, long long N, int D,
-    int K, int Dp, int Kp, int *__restrict__ assign, float *__restrict__ lossP) {
+    const float *__restrict__ X, const float *__restrict__ C, const float *__restrict__ mean,
+    const float *__restrict__ cn, long long N, int D, int K, int Dp, int Kp, int *__restrict__ assign,
+    float *__restrict__ lossP) {
     constexpr int NT = TR * 2;             // threads: one wave per 32 rows
     constexpr int NW = TR / 32;
     constexpr int Q = kKmChunk * 8 / NT;   // float4 of a 64 x 32 centroid piece staged per thread
@@ -109,13 +153,14 @@ __global__ __launch_bounds__(TR * 2) void kmeans_assign_kernel(
     const int D4 = D >> 2, Dp4 = Dp >> 2;
     const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X);
     const f4 *__restrict__ C4 = reinterpret_cast<const f4 *>(C);
+    const f4 *__restrict__ M4 = reinterpret_cast<const f4 *>(mean);
 
-    // the tile of points, zero beyond D and beyond N
+    // the tile of points minus the common shift, zero beyond D and beyond N
     for (int idx = tid; idx < TR * Dp4; idx += NT) {
         const int row = idx / Dp4, c4 = idx - row * Dp4;
         const long long r = r0 + row;
         f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (r < N && c4 < D4) v = __builtin_nontemporal_load(X4 + r * D4 + c4);
+        if (r < N && c4 < D4) v = __builtin_nontemporal_load(X4 + r * D4 + c4) - M4[c4];
         Xs4[row * ldx4 + c4] = v;
     }
 
@@ -250,8 +295,8 @@ constexpr int kSmLd = kSmCols + 1;
 
 template <int KG>                         // groups of eight centroids: K <= 8 KG
 __global__ __launch_bounds__(kKmSmallRows) void kmeans_assign_small_kernel(
-    const float *__restrict__ X, const float *__restrict__ C, const float *__restrict__ cn, long long N, int D,
-    int K, int *__restrict__ assign) {
+    const float *__restrict__ X, const float *__restrict__ C, const float *__restrict__ mean,
+    const float *__restrict__ cn, long long N, int D, int K, int *__restrict__ assign) {
     __shared__ float xs[kKmSmallRows * kSmLd];
     const int tid = threadIdx.x;
     const long long r0 = (long long)blockIdx.x * kKmSmallRows;
@@ -259,6 +304,7 @@ __global__ __launch_bounds__(kKmSmallRows) void kmeans_assign_small_kernel(
     const int D4 = D >> 2;
     const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X) + r0 * D4;
     const f4 *__restrict__ C4 = reinterpret_cast<const f4 *>(C);
+    const f4 *__restrict__ M4 = reinterpret_cast<const f4 *>(mean);
     const int nch = (D + kSmCols - 1) / kSmCols;
 
     float acc[8 * KG];
@@ -266,10 +312,12 @@ __global__ __launch_bounds__(kKmSmallRows) void kmeans_assign_small_kernel(
     for (int k = 0; k < 8 * KG; ++k) acc[k] = 0.0f;
 
     // piece ch of the tile: thread t brings float4 number (t & 7) of rows (t >> 3) + 32 q
-    f4 pre[8];
+    f4 pre[8], mpre;                      // mpre: the common shift of this thread's four columns
 #define SLAQ_SM_FETCH(CH)                                                                    \
     {                                                                                        \
         const int c4_ = (CH) * (kSmCols / 4) + (tid & 7);                                    \
+        mpre = f4{0.0f, 0.0f, 0.0f, 0.0f};                                                   \
+        if (c4_ < D4) mpre = M4[c4_];                                                        \
         _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                      \
             const int row_ = (tid >> 3) + 32 * q;                                            \
             f4 v_ = {0.0f, 0.0f, 0.0f, 0.0f};                                                \
@@ -283,7 +331,10 @@ __global__ __launch_bounds__(kKmSmallRows) void kmeans_assign_small_kernel(
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             float *dst = xs + ((tid >> 3) + 32 * q) * kSmLd + 4 * (tid & 7);
-            dst[0] = pre[q][0]; dst[1] = pre[q][1]; dst[2] = pre[q][2]; dst[3] = pre[q][3];
+            // the shift comes off here, where the prefetched values are first needed (columns past
+            // D hold zero in both; rows past N are never written out)
+            const f4 v = pre[q] - mpre;
+            dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
         }
         __syncthreads();
         if (ch + 1 < nch) SLAQ_SM_FETCH(ch + 1);
@@ -387,8 +438,9 @@ constexpr int kStGroup = 32 * kStWaves;    // centroids per launch
 
 template <int NKP>
 __global__ __launch_bounds__(512) void kmeans_assign_stream_kernel(
-    const float *__restrict__ X, const float *__restrict__ C, const unsigned short *__restrict__ Cs,
-    const float *__restrict__ cn, long long N, int D, int Kp, int gbase, int first, int last,
+    const float *__restrict__ X, const float *__restrict__ C, const float *__restrict__ mean,
+    const unsigned short *__restrict__ Cs, const float *__restrict__ cn, long long N, int D, int Kp, int gbase,
+    int first, int last,
     long long tiles, long long tiles_per_block, int *__restrict__ assign, float *__restrict__ bestv,
     float *__restrict__ lossW) {
     constexpr int Dp = kSpK * NKP;
@@ -429,6 +481,12 @@ __global__ __launch_bounds__(512) void kmeans_assign_stream_kernel(
     // loader role: row lr of the tile, columns 8 seg .. + 7
     const int lr = tid >> 4, seg = tid & 15;
     const bool loads = seg < Dp / 8;
+    f4 mr0 = {0.0f, 0.0f, 0.0f, 0.0f}, mr1 = mr0;      // the common shift of this thread's columns
+    if (loads) {
+        const f4 *__restrict__ M4 = reinterpret_cast<const f4 *>(mean);
+        if (2 * seg < D4) mr0 = M4[2 * seg];
+        if (2 * seg + 1 < D4) mr1 = M4[2 * seg + 1];
+    }
     // distance role: row 4 wave + rl of the tile, columns 8 part .. + 7
     const int rl = lane >> 4, part = lane & 15;
     const int erow = 4 * wave + rl;
@@ -444,7 +502,10 @@ __global__ __launch_bounds__(512) void kmeans_assign_stream_kernel(
     }
 #define SLAQ_ST_STASH(B)                                                                     \
     if (loads) {                                                                             \
-        const float x_[8] = {xr0.x, xr0.y, xr0.z, xr0.w, xr1.x, xr1.y, xr1.z, xr1.w};        \
+        /* the shift is taken off here, where the loaded values are first needed (columns    \
+           past D hold zero in both) */                                                      \
+        const f4 xs0_ = xr0 - mr0, xs1_ = xr1 - mr1;                                         \
+        const float x_[8] = {xs0_.x, xs0_.y, xs0_.z, xs0_.w, xs1_.x, xs1_.y, xs1_.z, xs1_.w}; \
         u4 wh_, wm_, wl_;                                                                    \
         _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                      \
             unsigned h0, m0, l0, h1, m1, l1;                                                 \
@@ -722,8 +783,8 @@ static hipError_t launch_assign(const KmArgs &a, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&kmeans_assign_kernel<TR>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.s.lds_assign);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kmeans_assign_kernel<TR>, dim3((unsigned)a.s.T), dim3(TR * 2), a.s.lds_assign, st, a.X, a.C,
-                       a.cn, a.N, a.D, a.K, a.s.Dp, a.s.Kp, a.assign, a.lossP);
+    hipLaunchKernelGGL(kmeans_assign_kernel<TR>, dim3((unsigned)a.s.T), dim3(TR * 2), a.s.lds_assign, st, a.X, a.Cc,
+                       a.mean, a.cn, a.N, a.D, a.K, a.s.Dp, a.s.Kp, a.assign, a.lossP);
     return hipGetLastError();
 }
 
@@ -734,12 +795,17 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
     if ((e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev)) != hipSuccess) return e;
     if ((size_t)lds_max < a.s.lds_assign) return hipErrorInvalidValue;
 
-    hipLaunchKernelGGL(kmeans_norms_kernel, dim3((unsigned)((a.s.Kp + 3) / 4)), dim3(256), 0, st, a.C, a.D, a.K,
-                       a.s.Kp, a.cn);
+    if (k == 0) {                          // the shift depends on X only: once per call
+        hipLaunchKernelGGL(kmeans_mean_kernel, dim3((unsigned)((a.D + 63) / 64)), dim3(64 * kKmMeanWaves), 0, st, a.X, a.N, a.D,
+                           a.mean);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kmeans_center_kernel, dim3((unsigned)((a.s.Kp + 3) / 4)), dim3(256), 0, st, a.C, a.mean, a.D,
+                       a.K, a.s.Kp, a.Cc, a.cn);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (a.s.split) {
         const long long n = (long long)a.s.Kp * a.s.Dp;
-        hipLaunchKernelGGL(kmeans_split_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.C, a.D, a.K,
+        hipLaunchKernelGGL(kmeans_split_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.Cc, a.D, a.K,
                            a.s.Kp, a.s.Dp, a.Cs);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
@@ -747,14 +813,14 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
     if (a.s.small) {
         const dim3 grid((unsigned)a.s.T), block(kKmSmallRows);
         switch ((a.K + 7) / 8) {
-        case 1: hipLaunchKernelGGL(kmeans_assign_small_kernel<1>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
-        case 2: hipLaunchKernelGGL(kmeans_assign_small_kernel<2>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
-        case 3: hipLaunchKernelGGL(kmeans_assign_small_kernel<3>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
-        case 4: hipLaunchKernelGGL(kmeans_assign_small_kernel<4>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
-        case 5: hipLaunchKernelGGL(kmeans_assign_small_kernel<5>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
-        case 6: hipLaunchKernelGGL(kmeans_assign_small_kernel<6>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
-        case 7: hipLaunchKernelGGL(kmeans_assign_small_kernel<7>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
-        default: hipLaunchKernelGGL(kmeans_assign_small_kernel<8>, grid, block, 0, st, a.X, a.C, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 1: hipLaunchKernelGGL(kmeans_assign_small_kernel<1>, grid, block, 0, st, a.X, a.Cc, a.mean, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 2: hipLaunchKernelGGL(kmeans_assign_small_kernel<2>, grid, block, 0, st, a.X, a.Cc, a.mean, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 3: hipLaunchKernelGGL(kmeans_assign_small_kernel<3>, grid, block, 0, st, a.X, a.Cc, a.mean, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 4: hipLaunchKernelGGL(kmeans_assign_small_kernel<4>, grid, block, 0, st, a.X, a.Cc, a.mean, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 5: hipLaunchKernelGGL(kmeans_assign_small_kernel<5>, grid, block, 0, st, a.X, a.Cc, a.mean, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 6: hipLaunchKernelGGL(kmeans_assign_small_kernel<6>, grid, block, 0, st, a.X, a.Cc, a.mean, a.cn, a.N, a.D, a.K, a.assign); break;
+        case 7: hipLaunchKernelGGL(kmeans_assign_small_kernel<7>, grid, block, 0, st, a.X, a.Cc, a.mean, a.cn, a.N, a.D, a.K, a.assign); break;
+        default: hipLaunchKernelGGL(kmeans_assign_small_kernel<8>, grid, block, 0, st, a.X, a.Cc, a.mean, a.cn, a.N, a.D, a.K, a.assign); break;
         }
         e = hipGetLastError();
     } else if (a.s.split) {
@@ -767,11 +833,11 @@ hipError_t launch_kmeans_iteration(const KmArgs &a, int k, hipEvent_t *ev, hipSt
             const int first = gi == 0, last = gi == groups - 1;
             if (a.s.Dp == 64)
                 hipLaunchKernelGGL(kmeans_assign_stream_kernel<1>, dim3((unsigned)a.s.stream_blocks), dim3(512), lds, st,
-                                   a.X, a.C, a.Cs, a.cn, a.N, a.D, a.s.Kp, gi * kStGroup, first, last, a.s.T,
+                                   a.X, a.Cc, a.mean, a.Cs, a.cn, a.N, a.D, a.s.Kp, gi * kStGroup, first, last, a.s.T,
                                    a.s.tiles_per_block, a.assign, a.bestv, a.lossP);
             else
                 hipLaunchKernelGGL(kmeans_assign_stream_kernel<2>, dim3((unsigned)a.s.stream_blocks), dim3(512), lds, st,
-                                   a.X, a.C, a.Cs, a.cn, a.N, a.D, a.s.Kp, gi * kStGroup, first, last, a.s.T,
+                                   a.X, a.Cc, a.mean, a.Cs, a.cn, a.N, a.D, a.s.Kp, gi * kStGroup, first, last, a.s.T,
                                    a.s.tiles_per_block, a.assign, a.bestv, a.lossP);
             e = hipGetLastError();
         }

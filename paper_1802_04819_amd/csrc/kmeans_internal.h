@@ -38,8 +38,10 @@ KmShape km_shape(long long N, int D, int K);
 struct KmArgs {
     const float *X; float *C; int *assign; int *counts; float *loss_out;
     long long N; int D, K;
-    float *cn;           // [Kp] squared centroid norms, +inf past K
-    unsigned short *Cs;  // [3, Kp, Dp] bfloat16 parts of the centroids (split path)
+    float *mean;         // [D] common shift: column means of a sample of the rows, once per call
+    float *Cc;           // [K, D] centroids minus the shift
+    float *cn;           // [Kp] squared norms of the shifted centroids, +inf past K
+    unsigned short *Cs;  // [3, Kp, Dp] bfloat16 parts of the shifted centroids (split path)
     float *lossP;        // [lossN] partial sums of the squared distances
     float *bestv;        // [N] best value so far (split path with more than 256 centroids)
     float *part;         // [P, K, D] per-split column sums

@@ -114,10 +114,15 @@ def test_trajectory_matches_oracle_trajectory():
     assert np.mean(job.assign.cpu().numpy() == a_end) > 0.999
 
 
-def test_shifted_data_keeps_the_loss_accurate():
-    _say("[case] kmeans on data far from the origin (|x|^2 >> cluster spread)")
-    p = synth.make_kmeans(8000, 32, 10, seed=9, offset=40.0)
-    run_checked(p, 3, "offset 40")
+@pytest.mark.parametrize("N,D,K,offset", [(8000, 32, 10, 40.0), (24398, 56, 47, 40.0), (6065, 292, 25, 40.0),
+                                          (8000, 128, 100, 40.0), (7812, 512, 60, 40.0), (5000, 64, 20, 1000.0)])
+def test_shifted_data_keeps_loss_and_assignments_accurate(N, D, K, offset):
+    """Data far from the origin (|x|^2 >> cluster spread), on each assignment path: the loss comes
+    from the definition and the products are taken on points and centroids minus a common shift, so
+    neither the loss nor the near ties suffer from the size of |x|^2."""
+    _say(f"[case] kmeans on data far from the origin: N={N} D={D} K={K} offset={offset}")
+    p = synth.make_kmeans(N, D, K, seed=9, blobs=max(2, min(K, 30)), offset=offset)
+    run_checked(p, 3, f"offset {offset}")
 
 
 def test_duplicate_centroids_empty_clusters_and_exact_ties():
