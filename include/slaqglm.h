@@ -177,11 +177,13 @@ typedef struct {
 int glm_kmeans_workspace_bytes(const glm_kmeans_job_t *job /*HOST*/, size_t *out_bytes /*HOST*/);
 
 /* `iters` K-Means iterations, enqueued on hip_stream; returns without synchronising.  The
- * products x_i . c_k run on the matrix cores with fp32-equivalent accuracy (for D <= 128 as six
- * bfloat16 products of three-way split operands, else in fp32); the nearest centroid is decided
- * on |c_k|^2 - 2 x_i . c_k in fp32, so where two centroids are equally near to within fp32
- * rounding either may be chosen; the squared distance that enters L is recomputed from the
- * definition.
+ * products x_i . c_k have fp32 accuracy on every path: on the vector units for few centroids
+ * (K <= 32, or K <= 64 with K D <= 4096), else on the matrix cores (for D <= 128 as six bfloat16
+ * products of three-way split operands, else in fp32).  They are taken on points and centroids
+ * minus a common shift (the column means of a sample of the rows), so the distance of the data
+ * from the origin does not matter; the nearest centroid is decided on |c_k|^2 - 2 x_i . c_k in
+ * fp32, so where two centroids are equally near to within fp32 rounding either may be chosen; the
+ * squared distance that enters L is recomputed from the definition.
  * Sums use a fixed order (no floating-point atomics in global memory): reruns are bit-identical.
  * Errors: GLM_EINVAL for bad pointers, alignment or shapes, GLM_ENOSPC if ws_bytes or the
  * history capacity is too small, GLM_EHIP if a launch fails; nothing is enqueued on
