@@ -174,3 +174,20 @@ def test_closed_loop_quality_driven_allocation_beats_equal_shares():
     def mean_norm(hs):
         return float(np.mean([(h[-1] - lo) / (h[0] - lo) for h, lo in zip(hs, floor)]))
     assert mean_norm(greedy) < mean_norm(fair), (mean_norm(greedy), mean_norm(fair))
+
+
+def test_histories_of_diverged_jobs_give_zero_finite_gains():
+    """A job whose loss became NaN or infinite must not poison the epoch: its gains are 0 (so it
+    keeps the one unit every job gets) and finite (the allocator rejects anything else)."""
+    _say("[case] predictor on histories with NaN, infinities and extreme magnitudes")
+    nan, inf = float("nan"), float("inf")
+    H = [[nan] * 8, [inf] * 8, [1, nan, 0.5, 0.4, 0.35, 0.33], [1, 0.8, inf, 0.5, 0.4, 0.3], [1, 0.5, 0.25, 0.125, nan],
+         [1, 0.9, 0.81, 0.73, -inf], [3e38] * 5, [0.0] * 6,
+         [1e30, 5e29, 3e29, 2e29, 1.5e29, 1.2e29], [1e-38, 5e-39, 3e-39, 2e-39, 1e-39], [1, 2, 4, 8, 16, 32]]
+    for curve in (glm.GLM_CURVE_SUBLINEAR, glm.GLM_CURVE_LINEAR):
+        pred, gain, fit = _predict([_Hist(h) for h in H], curve, 0.9, 128, 8)
+        assert np.isfinite(gain).all()
+        assert np.all(fit[:8, 0] == 0) and np.all(gain[:8] == 0)          # nothing to fit
+        assert np.all(fit[8:10, 0] == 1) and np.all(gain[8:10] > 0) and np.all(gain[8:10] < 1)   # scale does not matter
+        alloc = glm.glm_allocate_greedy(gain, 3 * len(H))
+        assert alloc.sum() == 3 * len(H) and alloc.min() >= 1 and np.all(alloc[:8] <= alloc[8:10].max())
