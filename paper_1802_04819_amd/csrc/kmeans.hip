@@ -79,7 +79,8 @@ __device__ __forceinline__ floatx16 km_mfma(float a, float b, floatx16 c) {
 // when the points and the centroids are shifted together, but the fp32 rounding of the expanded
 // form |c|^2 - 2 x . c scales with |x|^2 + |c|^2, so data far from the origin would lose the
 // near ties; after the shift both are of the size of the data's spread.  One slice of the
-// sample per wave, the sixteen waves added in order.
+// sample per wave, the sixteen waves added in order.  Values that are not finite are left out, so
+// that one bad row cannot spoil the shift of all the others.
 constexpr int kKmMeanSample = 1024;
 constexpr int kKmMeanWaves = 16;
 
@@ -99,16 +100,20 @@ __global__ __launch_bounds__(64 * kKmMeanWaves) void kmeans_mean_kernel(const fl
 #pragma unroll
             for (int u = 0; u < 8; ++u) v[u] = X[(size_t)((i + u * kKmMeanWaves) * stride) * D + col];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) s += v[u];
+            for (int u = 0; u < 8; ++u) s += __builtin_isfinite(v[u]) ? v[u] : 0.0f;
         }
-        for (; i < S; i += kKmMeanWaves) s += X[(size_t)(i * stride) * D + col];
+        for (; i < S; i += kKmMeanWaves) {
+            const float v = X[(size_t)(i * stride) * D + col];
+            s += __builtin_isfinite(v) ? v : 0.0f;
+        }
     }
     red[wave][lane] = s;
     __syncthreads();
     if (wave == 0 && col < D) {
         float t = red[0][lane];
         for (int w = 1; w < kKmMeanWaves; ++w) t += red[w][lane];
-        mean[col] = t / (float)S;
+        t /= (float)S;
+        mean[col] = __builtin_isfinite(t) ? t : 0.0f;      // any finite shift is valid; NaN or inf is not
     }
 }
 

@@ -200,3 +200,27 @@ def test_kmeans_errors():
     assert lib.glm_kmeans_workspace_bytes(None, ctypes.byref(out)) == glm.GLM_EINVAL
     torch.cuda.synchronize()
     assert job.hist_len == 0 and torch.equal(job.C.cpu(), p.C0)          # nothing was enqueued
+
+
+@pytest.mark.parametrize("N,D,K", [(3000, 32, 7), (3000, 64, 100), (2000, 260, 70)])
+def test_rows_that_are_not_numbers_get_a_valid_cluster(N, D, K):
+    """NaN and infinite rows cannot be nearest to anything; they must still land in a valid cluster
+    (index arithmetic depends on it) and the sizes must add up.  One case per assignment path."""
+    _say(f"[case] kmeans with NaN / infinite rows N={N} D={D} K={K}")
+    p = synth.make_kmeans(N, D, K, seed=77)
+    X = p.X.clone()
+    X[0, 1] = float("nan"); X[5] = float("nan"); X[N - 1, 3] = float("inf"); X[N // 2, 0] = float("-inf"); X[17, D - 1] = float("nan")
+    C0 = p.C0.clone()                      # starting centroids: finite rows only
+    job, ws = _job(X, C0, 1)
+    glm.glm_kmeans_step(job, 1, ws)
+    torch.cuda.synchronize()
+    a = job.assign.cpu().numpy(); cnt = job.counts.cpu().numpy()
+    assert a.min() >= 0 and a.max() < K
+    assert np.array_equal(cnt, np.bincount(a, minlength=K)) and cnt.sum() == N
+    # the other rows are assigned as if the bad rows were not there (row 0 is one of the sampled
+    # rows of the common shift: a NaN there must not reach the rest)
+    bad = np.zeros(N, bool); bad[[0, 5, N - 1, N // 2, 17]] = True
+    _, best, second = oracle.kmeans_assign(p.X.numpy(), C0.numpy().astype(np.float64))
+    a_ref = oracle.kmeans_step(p.X.numpy(), C0.numpy().astype(np.float64))[2]
+    clear = (~bad) & ((second - best) > 1e-5 * ((p.X.numpy().astype(np.float64) ** 2).sum(1) + (C0.numpy() ** 2).sum(1).max()))
+    assert np.array_equal(a[clear], a_ref[clear])
