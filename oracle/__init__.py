@@ -57,6 +57,10 @@ def _load():
         lib.oracle_run.argtypes = [ctypes.c_int, fp, fp, ctypes.c_int64, ctypes.c_int32,
                                    dp, ctypes.c_double, ctypes.c_double, ctypes.c_int32,
                                    ctypes.c_int32, dp, dp, dp]
+        lib.oracle_run_schedule.restype = ctypes.c_int
+        lib.oracle_run_schedule.argtypes = [ctypes.c_int, fp, fp, ctypes.c_int64, ctypes.c_int32,
+                                            dp, ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_int64,
+                                            ctypes.c_int32, dp, dp, dp]
         i64p = ctypes.POINTER(ctypes.c_int64)
         i32p = ctypes.POINTER(ctypes.c_int32)
         lib.oracle_sparse_loss_grad.restype = ctypes.c_int
@@ -141,6 +145,29 @@ def run(loss: int, X, y, w0, lam: float, eta: float, K: int, chunks: int = 0):
                             int(K), int(chunks), _dptr(lh), _dptr(gh), _dptr(gl))
     if rc != 0:
         raise ValueError("oracle_run rejected its arguments")
+    return lh, gh, w, gl
+
+
+CONSTANT, INV_SQRT = 0, 1
+
+
+def run_schedule(loss: int, X, y, w0, lam: float, eta: float, schedule: int, K: int, k0: int = 0):
+    """K gradient-descent iterations from w0 with the step of iteration k (counted from the job's
+    start, k0 + position in this call) given by the schedule: CONSTANT eta, INV_SQRT
+    eta / sqrt(k + 1).  Returns as run()."""
+    X = _f32(X)
+    N, D = X.shape
+    y = _f32(y, (N,))
+    w = np.array(w0, dtype=np.float64, copy=True)
+    if w.shape != (D,):
+        raise ValueError("w0 must have shape (D,)")
+    lh = np.empty(K, dtype=np.float64)
+    gh = np.empty(K, dtype=np.float64)
+    gl = np.zeros(D, dtype=np.float64)
+    rc = _load().oracle_run_schedule(int(loss), _fptr(X), _fptr(y), N, D, _dptr(w), float(lam), float(eta),
+                                     int(schedule), int(k0), int(K), _dptr(lh), _dptr(gh), _dptr(gl))
+    if rc != 0:
+        raise ValueError("oracle_run_schedule rejected its arguments")
     return lh, gh, w, gl
 
 

@@ -202,6 +202,36 @@ int oracle_sparse_loss_grad(int loss, const int64_t *row_ptr, const int32_t *col
     return 0;
 }
 
+/* As oracle_run, with the step of every iteration given by a schedule.  k counts the iterations
+ * of the job from its start: k = k0 + position in this call, so that a run split into several
+ * calls takes the same steps as one call.
+ *   schedule 0: eta_k = eta
+ *   schedule 1: eta_k = eta / sqrt(k + 1)   (the decay of MLlib's gradient descent, the library
+ *               the jobs of Sec. 3 "Setup" ran on; a first-order method of Sec. 2, class I) */
+int oracle_run_schedule(int loss, const float *X, const float *y, int64_t N, int32_t D,
+                        double *w, double lambda, double eta, int schedule, int64_t k0, int32_t K,
+                        double *loss_hist, double *gnorm_hist, double *g_last)
+{
+    if (K < 0 || k0 < 0 || (schedule != 0 && schedule != 1)) return -1;
+    double *g = (double *)malloc(sizeof(double) * (size_t)(D > 0 ? D : 1));
+    if (!g) return -1;
+    for (int32_t i = 0; i < K; ++i) {
+        double L;
+        int rc = oracle_loss_grad(loss, X, y, N, D, w, lambda, &L, g);
+        if (rc != 0) { free(g); return rc; }
+        double gg = 0.0;
+        for (int32_t j = 0; j < D; ++j) gg += g[j] * g[j];
+        loss_hist[i] = L;
+        gnorm_hist[i] = sqrt(gg);
+        const int64_t k = k0 + i;
+        const double eta_k = (schedule == 1) ? eta / sqrt((double)(k + 1)) : eta;
+        for (int32_t j = 0; j < D; ++j) w[j] = w[j] - eta_k * g[j];
+        if (g_last) memcpy(g_last, g, sizeof(double) * (size_t)D);
+    }
+    free(g);
+    return 0;
+}
+
 /* K constant-step iterations on a CSR matrix; histories as in oracle_run. */
 int oracle_sparse_run(int loss, const int64_t *row_ptr, const int32_t *col_idx, const float *val,
                       const float *y, int64_t N, int64_t D, double *w, double lambda, double eta,
