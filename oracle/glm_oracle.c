@@ -172,36 +172,6 @@ int oracle_run(int loss, const float *X, const float *y, int64_t N, int32_t D,
     return 0;
 }
 
-/*
- * The same loss and gradient for a sparse X given in CSR form (row_ptr [N+1], col_idx and val
- * [nnz]; entries of a row in stored order, duplicates add).  Plain loops over the stored entries:
- * absent entries are zeros of the dense definition above.  g must hold D doubles.
- */
-int oracle_sparse_loss_grad(int loss, const int64_t *row_ptr, const int32_t *col_idx,
-                            const float *val, const float *y, int64_t N, int64_t D,
-                            const double *w, double lambda, double *L_out, double *g)
-{
-    if (loss < 0 || loss > 2 || N < 1 || D < 1) return -1;
-    double S = 0.0;
-    for (int64_t j = 0; j < D; ++j) g[j] = 0.0;
-    for (int64_t i = 0; i < N; ++i) {
-        double z = 0.0;
-        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
-            if (col_idx[e] < 0 || col_idx[e] >= D) return -1;
-            z += (double)val[e] * w[col_idx[e]];
-        }
-        double l, r;
-        sample_loss_residual(loss, z, (double)y[i], &l, &r);
-        S += l;
-        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) g[col_idx[e]] += (double)val[e] * r;
-    }
-    double ww = 0.0;
-    for (int64_t j = 0; j < D; ++j) ww += w[j] * w[j];
-    *L_out = S / (double)N + 0.5 * lambda * ww;
-    for (int64_t j = 0; j < D; ++j) g[j] = g[j] / (double)N + lambda * w[j];
-    return 0;
-}
-
 /* As oracle_run, with the step of every iteration given by a schedule.  k counts the iterations
  * of the job from its start: k = k0 + position in this call, so that a run split into several
  * calls takes the same steps as one call.
@@ -229,6 +199,36 @@ int oracle_run_schedule(int loss, const float *X, const float *y, int64_t N, int
         if (g_last) memcpy(g_last, g, sizeof(double) * (size_t)D);
     }
     free(g);
+    return 0;
+}
+
+/*
+ * The same loss and gradient for a sparse X given in CSR form (row_ptr [N+1], col_idx and val
+ * [nnz]; entries of a row in stored order, duplicates add).  Plain loops over the stored entries:
+ * absent entries are zeros of the dense definition above.  g must hold D doubles.
+ */
+int oracle_sparse_loss_grad(int loss, const int64_t *row_ptr, const int32_t *col_idx,
+                            const float *val, const float *y, int64_t N, int64_t D,
+                            const double *w, double lambda, double *L_out, double *g)
+{
+    if (loss < 0 || loss > 2 || N < 1 || D < 1) return -1;
+    double S = 0.0;
+    for (int64_t j = 0; j < D; ++j) g[j] = 0.0;
+    for (int64_t i = 0; i < N; ++i) {
+        double z = 0.0;
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            if (col_idx[e] < 0 || col_idx[e] >= D) return -1;
+            z += (double)val[e] * w[col_idx[e]];
+        }
+        double l, r;
+        sample_loss_residual(loss, z, (double)y[i], &l, &r);
+        S += l;
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) g[col_idx[e]] += (double)val[e] * r;
+    }
+    double ww = 0.0;
+    for (int64_t j = 0; j < D; ++j) ww += w[j] * w[j];
+    *L_out = S / (double)N + 0.5 * lambda * ww;
+    for (int64_t j = 0; j < D; ++j) g[j] = g[j] / (double)N + lambda * w[j];
     return 0;
 }
 
