@@ -53,6 +53,14 @@ extern "C" {
  * (logistic regression, linear SVM and linear regression of Sec. 3 "Setup"). */
 typedef enum { GLM_LOGISTIC = 0, GLM_HINGE = 1, GLM_SQUARED = 2 } glm_loss_t;
 
+/* Step of iteration k, k counted from the start of the job (= its index in loss_hist):
+ *   GLM_STEP_CONSTANT  step
+ *   GLM_STEP_INV_SQRT  step / sqrt(k + 1): the decay of MLlib's gradient descent, the library the
+ *                      paper's jobs ran on (Sec. 3 "Setup"); with it subgradient descent on the
+ *                      hinge loss shows the diminishing returns the scheduler relies on (Sec. 1),
+ *                      which it does not with a constant step. */
+typedef enum { GLM_STEP_CONSTANT = 0, GLM_STEP_INV_SQRT = 1 } glm_step_schedule_t;
+
 typedef enum {
     GLM_OK       =  0,
     GLM_EINVAL   = -1,  /* null/misaligned pointer, size or hyper-parameter out of range */
@@ -82,6 +90,8 @@ typedef struct {
     int64_t      hist_len; /* entries already in loss_hist (= iterations done so far); advanced by
                               the number of iterations enqueued when a call succeeds               */
     int64_t      hist_cap; /* capacity of loss_hist                                                */
+    int32_t      schedule; /* glm_step_schedule_t; read by glm_step and glm_step_batched only; a run
+                              split into several calls takes the same steps as one call            */
 } glm_job_t;
 
 /* Bytes of DEVICE workspace that glm_step (J = 1), glm_step_batched (J jobs) or

@@ -50,6 +50,7 @@ int validate_job(const glm_job_t &j) {
     if (j.loss < GLM_LOGISTIC || j.loss > GLM_SQUARED) return GLM_EINVAL;
     if (!std::isfinite(j.lambda) || j.lambda < 0.0f) return GLM_EINVAL;
     if (!std::isfinite(j.step) || j.step < 0.0f) return GLM_EINVAL;
+    if (j.schedule != GLM_STEP_CONSTANT && j.schedule != GLM_STEP_INV_SQRT) return GLM_EINVAL;
     if (j.hist_len < 0 || j.hist_cap < 0 || j.hist_len > j.hist_cap) return GLM_EINVAL;
     return GLM_OK;
 }
@@ -171,7 +172,7 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
         d.lpart = reinterpret_cast<float *>(base + s.lpart);
         d.wn2 = reinterpret_cast<double *>(base + s.wn2);
         d.N = src.N; d.invN = 1.0 / (double)src.N; d.D = src.D; d.loss = src.loss;
-        d.lambda = src.lambda; d.step = src.step; d.P = s.P; d.cls = s.cls; d.iters = iters[j];
+        d.lambda = src.lambda; d.step = src.step; d.sched = src.schedule; d.k0 = src.hist_len; d.P = s.P; d.cls = s.cls; d.iters = iters[j];
         max_cls = std::max(max_cls, s.cls);
         d.blk0 = blk0[a];
         for (int b = 0; b < s.P; ++b) blk_job[blk0[a] + b] = a;

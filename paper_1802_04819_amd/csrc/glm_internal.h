@@ -26,6 +26,8 @@ struct DevJob {
     int          loss;
     float        lambda;
     float        step;
+    int          sched;      // glm_step_schedule_t
+    long long    k0;         // iterations the job had done when the call started
     int          P;          // row blocks; a function of (N, D) only
     int          cls;        // lane-layout class; a function of D only
     int          iters;      // rounds this job takes part in during this call

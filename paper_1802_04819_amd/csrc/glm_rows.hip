@@ -400,7 +400,11 @@ __global__ __launch_bounds__(kFinCols * kFinSegs) void finalize_kernel(
         const float wj = jb.w[col];
         const double g = tot * jb.invN + (double)jb.lambda * (double)wj;
         jb.grad[col] = (float)g;
-        if (jb.step != 0.0f) jb.w[col] = (float)((double)wj - (double)jb.step * g);
+        if (jb.step != 0.0f) {
+            double eta = (double)jb.step;
+            if (jb.sched == GLM_STEP_INV_SQRT) eta = eta / sqrt((double)(jb.k0 + round + 1));
+            jb.w[col] = (float)((double)wj - eta * g);
+        }
     }
     if (does_loss) {                       // fixed two-level sum of the T thread partials
         if (tid < 32) {

@@ -28,6 +28,7 @@ EXPORTS = (
     "glm_lbfgs_workspace_bytes", "glm_lbfgs",
 )
 GLM_CURVE_SUBLINEAR, GLM_CURVE_LINEAR = 1, 2
+GLM_STEP_CONSTANT, GLM_STEP_INV_SQRT = 0, 1
 
 
 class glm_job_t(ctypes.Structure):
@@ -37,7 +38,7 @@ class glm_job_t(ctypes.Structure):
         ("grad", ctypes.c_void_p), ("loss_hist", ctypes.c_void_p),
         ("N", ctypes.c_int64), ("D", ctypes.c_int32), ("loss", ctypes.c_int32),
         ("lambda_", ctypes.c_float), ("step", ctypes.c_float),
-        ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64),
+        ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64), ("schedule", ctypes.c_int32),
     ]
 
 
@@ -166,7 +167,7 @@ class Job:
 
     def __init__(self, X: torch.Tensor, y: torch.Tensor, w: torch.Tensor, loss: int, lam: float,
                  step: float, hist_cap: int, grad: Optional[torch.Tensor] = None,
-                 loss_hist: Optional[torch.Tensor] = None):
+                 loss_hist: Optional[torch.Tensor] = None, schedule: int = 0):
         for t, name in ((X, "X"), (y, "y"), (w, "w")):
             if t.dtype != torch.float32 or not t.is_contiguous():
                 raise TypeError(f"{name} must be a contiguous float32 tensor")
@@ -179,7 +180,7 @@ class Job:
                           else torch.zeros(max(int(hist_cap), 1), dtype=torch.float32, device=dev))
         self.c = glm_job_t(X.data_ptr(), y.data_ptr(), w.data_ptr(), self.grad.data_ptr(),
                            self.loss_hist.data_ptr(), int(X.shape[0]), int(X.shape[1]), int(loss),
-                           float(lam), float(step), 0, int(hist_cap))
+                           float(lam), float(step), 0, int(hist_cap), int(schedule))
 
     @property
     def hist_len(self) -> int:

@@ -41,7 +41,7 @@ int main(void) {
     CHECK(hipMemset(dw, 0, sizeof(float) * D));
     job.X = dX; job.y = dy; job.w = dw; job.grad = dg; job.loss_hist = dh;
     job.N = N; job.D = D; job.loss = GLM_LOGISTIC; job.lambda = 1e-4f; job.step = 1.0f;
-    job.hist_len = 0; job.hist_cap = iters;
+    job.hist_len = 0; job.hist_cap = iters; job.schedule = GLM_STEP_CONSTANT;
     size_t ws_bytes = 0;
     int rc = glm_workspace_bytes(&job, 1, 0, &ws_bytes);
     if (rc != GLM_OK) { fprintf(stderr, "glm_workspace_bytes: %s\n", glm_strerror(rc)); return 3; }

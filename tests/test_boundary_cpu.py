@@ -35,10 +35,10 @@ def test_strerror_texts():
 def _job(**kw):
     # fake but well-formed device addresses: validation must reject before dereferencing
     f = dict(X=0x10000, y=0x20000, w=0x30000, grad=0x40000, loss_hist=0x50000, N=1000, D=64,
-             loss=0, lambda_=1e-3, step=0.1, hist_len=0, hist_cap=10)
+             loss=0, lambda_=1e-3, step=0.1, hist_len=0, hist_cap=10, schedule=0)
     f.update(kw)
     return glm.glm_job_t(f["X"], f["y"], f["w"], f["grad"], f["loss_hist"], f["N"], f["D"],
-                         f["loss"], f["lambda_"], f["step"], f["hist_len"], f["hist_cap"])
+                         f["loss"], f["lambda_"], f["step"], f["hist_len"], f["hist_cap"], f["schedule"])
 
 
 def _ws_bytes(job, J=1, M=0):
@@ -80,6 +80,7 @@ _BAD_JOBS = [
     dict(lambda_=-1.0), dict(lambda_=float("nan")), dict(lambda_=float("inf")),
     dict(step=-0.1), dict(step=float("nan")),
     dict(hist_len=-1), dict(hist_len=11, hist_cap=10),
+    dict(schedule=2), dict(schedule=-1),
 ]
 
 
