@@ -69,6 +69,10 @@ def _load():
         lib.oracle_sparse_run.restype = ctypes.c_int
         lib.oracle_sparse_run.argtypes = [ctypes.c_int, i64p, i32p, fp, fp, ctypes.c_int64, ctypes.c_int64,
                                           dp, ctypes.c_double, ctypes.c_double, ctypes.c_int32, dp, dp, dp]
+        lib.oracle_sparse_run_schedule.restype = ctypes.c_int
+        lib.oracle_sparse_run_schedule.argtypes = [ctypes.c_int, i64p, i32p, fp, fp, ctypes.c_int64, ctypes.c_int64,
+                                                   dp, ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_int64,
+                                                   ctypes.c_int32, dp, dp, dp]
         lib.oracle_kmeans_assign.restype = ctypes.c_int
         lib.oracle_kmeans_assign.argtypes = [fp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, i32p, dp, dp]
         lib.oracle_kmeans_step.restype = ctypes.c_int
@@ -214,6 +218,23 @@ def sparse_run(loss: int, row_ptr, col_idx, val, y, D: int, w0, lam: float, eta:
                                    _dptr(w), float(lam), float(eta), int(K), _dptr(lh), _dptr(gh), _dptr(gl))
     if rc != 0:
         raise ValueError("oracle_sparse_run rejected its arguments")
+    return lh, gh, w, gl
+
+
+def sparse_run_schedule(loss: int, row_ptr, col_idx, val, y, D: int, w0, lam: float, eta: float, schedule: int,
+                        K: int, k0: int = 0):
+    """As sparse_run with the step schedule of run_schedule."""
+    y = _f32(y)
+    N = y.shape[0]
+    rp, ci, v = _csr(row_ptr, col_idx, val, N, D)
+    w = np.array(w0, dtype=np.float64, copy=True)
+    lh = np.empty(K); gh = np.empty(K); gl = np.zeros(D)
+    rc = _load().oracle_sparse_run_schedule(int(loss), rp.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                            ci.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _fptr(v), _fptr(y), N, D,
+                                            _dptr(w), float(lam), float(eta), int(schedule), int(k0), int(K),
+                                            _dptr(lh), _dptr(gh), _dptr(gl))
+    if rc != 0:
+        raise ValueError("oracle_sparse_run_schedule rejected its arguments")
     return lh, gh, w, gl
 
 

@@ -255,6 +255,33 @@ int oracle_sparse_run(int loss, const int64_t *row_ptr, const int32_t *col_idx, 
     return 0;
 }
 
+/* As oracle_sparse_run, with the step schedule of oracle_run_schedule (k = k0 + position in
+ * this call; schedule 0: eta, schedule 1: eta / sqrt(k + 1)). */
+int oracle_sparse_run_schedule(int loss, const int64_t *row_ptr, const int32_t *col_idx, const float *val,
+                               const float *y, int64_t N, int64_t D, double *w, double lambda, double eta,
+                               int schedule, int64_t k0, int32_t K, double *loss_hist, double *gnorm_hist,
+                               double *g_last)
+{
+    if (K < 0 || D < 1 || k0 < 0 || (schedule != 0 && schedule != 1)) return -1;
+    double *g = (double *)malloc(sizeof(double) * (size_t)D);
+    if (!g) return -1;
+    for (int32_t i = 0; i < K; ++i) {
+        double L;
+        int rc = oracle_sparse_loss_grad(loss, row_ptr, col_idx, val, y, N, D, w, lambda, &L, g);
+        if (rc != 0) { free(g); return rc; }
+        double gg = 0.0;
+        for (int64_t j = 0; j < D; ++j) gg += g[j] * g[j];
+        loss_hist[i] = L;
+        gnorm_hist[i] = sqrt(gg);
+        const int64_t ks = k0 + i;
+        const double eta_ks = (schedule == 1) ? eta / sqrt((double)(ks + 1)) : eta;
+        for (int64_t j = 0; j < D; ++j) w[j] = w[j] - eta_ks * g[j];
+        if (g_last) memcpy(g_last, g, sizeof(double) * (size_t)D);
+    }
+    free(g);
+    return 0;
+}
+
 /* Number of threads the chunked evaluation can use (1 without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>
