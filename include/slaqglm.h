@@ -229,6 +229,7 @@ typedef struct {
                                 workspace address and column arrays it was set on (the library keeps
                                 a host-side record); otherwise the layout is built again.  Other
                                 values: GLM_EINVAL                                                   */
+    int32_t        schedule; /* glm_step_schedule_t, as in glm_job_t                                */
 } glm_sparse_job_t;
 
 /* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz only).  With more than 786,432

@@ -110,6 +110,7 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     if (j.hist_len < 0 || j.hist_cap < 0 || j.hist_len > j.hist_cap) return GLM_EINVAL;
     if (j.hist_len + (int64_t)iters > j.hist_cap) return GLM_ENOSPC;
     if (j.prepared < 0 || j.prepared > 2) return GLM_EINVAL;
+    if (j.schedule != GLM_STEP_CONSTANT && j.schedule != GLM_STEP_INV_SQRT) return GLM_EINVAL;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
     const SparseLayout L = make_sparse_layout(j.N, j.D, j.nnz);
     if (ws_bytes < L.total) return GLM_ENOSPC;
@@ -122,7 +123,7 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     a.col_ptr = reinterpret_cast<const long long *>(j.col_ptr); a.row_idx = j.row_idx; a.col_val = j.col_val;
     a.y = j.y; a.w = j.w; a.grad = j.grad; a.loss_out = j.loss_hist + j.hist_len;
     a.N = j.N; a.D = j.D; a.nnz = j.nnz; a.nch = L.nch;
-    a.loss = j.loss; a.lambda = j.lambda; a.step = j.step;
+    a.loss = j.loss; a.lambda = j.lambda; a.step = j.step; a.sched = j.schedule; a.k0 = j.hist_len;
     a.seg0R = reinterpret_cast<int *>(base + L.seg0R); a.seg0C = reinterpret_cast<int *>(base + L.seg0C);
     a.closes = reinterpret_cast<int *>(base + L.closes); a.headless = reinterpret_cast<int *>(base + L.headless);
     a.slast = reinterpret_cast<int *>(base + L.slast);

@@ -110,6 +110,7 @@ struct SparseArgs {
     const float *y; float *w; float *grad; float *loss_out;
     long long N, D, nnz, nch;           // nch = ceil(nnz / kSparseChunk)
     int loss; float lambda, step;
+    int sched; long long k0;            // step schedule; iterations done when the call started
     int *seg0R, *seg0C;                 // [nch + 1] segment holding each chunk's first entry
     int *closes, *headless, *slast;     // [nch] per-chunk leftovers of the pass in flight
     float *H, *T;                       // [nch]

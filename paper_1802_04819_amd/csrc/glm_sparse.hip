@@ -19,6 +19,8 @@
 #include "glm_loss.h"
 #include "sparse_internal.h"
 
+#include <cmath>
+
 namespace slaqglm {
 
 constexpr int kSpU = 8;                    // entries per lane
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(256) void sparse_row_epilogue(const float *__restri
 
 // Columns: X^T r -> gradient, update; per-block sums of w^2 (entering iterate) in a fixed tree.
 __global__ __launch_bounds__(256) void sparse_col_epilogue(const float *__restrict__ gs, long long D, double invN,
-                                                           float lambda, float step, float *__restrict__ w,
+                                                           float lambda, double step, float *__restrict__ w,
                                                            float *__restrict__ grad, double *__restrict__ wwP) {
     __shared__ double red[256];
     const long long j = blockIdx.x * 256LL + threadIdx.x;
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue(const float *__restri
         const double g = (double)gs[j] * invN + (double)lambda * (double)wj;
         grad[j] = (float)g;
         ww = (double)wj * (double)wj;
-        if (step != 0.0f) w[j] = (float)((double)wj - (double)step * g);
+        if (step != 0.0) w[j] = (float)((double)wj - step * g);
     }
     red[threadIdx.x] = ww;
     __syncthreads();
@@ -260,6 +262,12 @@ __global__ __launch_bounds__(1024) void sparse_loss_kernel(const float *__restri
         __syncthreads();
     }
     if (t == 0) *loss_out = (float)(redL[0] * invN + 0.5 * (double)lambda * redW[0]);
+}
+
+// Step of iteration k of this call under the job's schedule (host side, fp64).
+static double sparse_step(const SparseArgs &a, int k) {
+    const double eta = (double)a.step;
+    return a.sched == GLM_STEP_INV_SQRT ? eta / std::sqrt((double)(a.k0 + k + 1)) : eta;
 }
 
 static hipError_t seg_pass(const long long *ptr, const int *idx, const float *val, const float *vec,
@@ -302,7 +310,7 @@ hipError_t launch_sparse_iteration(const SparseArgs &a, int k, hipEvent_t *ev, h
         return e;
     if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_col_epilogue, dim3(nbC), dim3(256), 0, st, a.gs, a.D, 1.0 / (double)a.N, a.lambda,
-                       a.step, a.w, a.grad, a.wwP);
+                       sparse_step(a, k), a.w, a.grad, a.wwP);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_loss_kernel, dim3(1), dim3(1024), 0, st, a.lossP, (long long)nbR, a.wwP,
                        (long long)nbC, 1.0 / (double)a.N, a.lambda, a.loss_out + k);
@@ -414,7 +422,7 @@ __global__ __launch_bounds__(256) void panel_copy_kernel(const long long *__rest
 
 // Columns: sum of the P per-panel sums in panel order, then gradient, update, |w|^2 partials.
 __global__ __launch_bounds__(256) void sparse_col_epilogue_panels(const float *__restrict__ gs2, int P, long long D,
-                                                                  double invN, float lambda, float step,
+                                                                  double invN, float lambda, double step,
                                                                   float *__restrict__ w, float *__restrict__ grad,
                                                                   double *__restrict__ wwP) {
     __shared__ double red[256];
@@ -427,7 +435,7 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue_panels(const float *_
         const double g = s * invN + (double)lambda * (double)wj;
         grad[j] = (float)g;
         ww = (double)wj * (double)wj;
-        if (step != 0.0f) w[j] = (float)((double)wj - (double)step * g);
+        if (step != 0.0) w[j] = (float)((double)wj - step * g);
     }
     red[threadIdx.x] = ww;
     __syncthreads();
@@ -491,7 +499,7 @@ hipError_t launch_sparse_iteration_panels(const SparseArgs &a, const SparsePanel
         return e;
     if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_col_epilogue_panels, dim3(nbC), dim3(256), 0, st, pn.gs2, pn.P, a.D, 1.0 / (double)a.N,
-                       a.lambda, a.step, a.w, a.grad, a.wwP);
+                       a.lambda, sparse_step(a, k), a.w, a.grad, a.wwP);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_loss_kernel, dim3(1), dim3(1024), 0, st, a.lossP, (long long)nbR, a.wwP,
                        (long long)nbC, 1.0 / (double)a.N, a.lambda, a.loss_out + k);

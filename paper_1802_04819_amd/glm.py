@@ -52,6 +52,7 @@ class glm_sparse_job_t(ctypes.Structure):
         ("N", ctypes.c_int64), ("D", ctypes.c_int64), ("nnz", ctypes.c_int64),
         ("loss", ctypes.c_int32), ("lambda_", ctypes.c_float), ("step", ctypes.c_float),
         ("hist_len", ctypes.c_int64), ("hist_cap", ctypes.c_int64), ("prepared", ctypes.c_int32),
+        ("schedule", ctypes.c_int32),
     ]
 
 
@@ -275,7 +276,7 @@ class SparseJob:
     """A glm_sparse_job_t plus the tensors it points at."""
 
     def __init__(self, row_ptr, col_idx, row_val, col_ptr, row_idx, col_val, y, w, loss: int, lam: float,
-                 step: float, hist_cap: int):
+                 step: float, hist_cap: int, schedule: int = 0):
         for t, dt in ((row_ptr, torch.int64), (col_ptr, torch.int64), (col_idx, torch.int32),
                       (row_idx, torch.int32), (row_val, torch.float32), (col_val, torch.float32),
                       (y, torch.float32), (w, torch.float32)):
@@ -293,7 +294,7 @@ class SparseJob:
         self.c = glm_sparse_job_t(row_ptr.data_ptr(), col_idx.data_ptr(), row_val.data_ptr(),
                                   col_ptr.data_ptr(), row_idx.data_ptr(), col_val.data_ptr(), y.data_ptr(),
                                   w.data_ptr(), self.grad.data_ptr(), self.loss_hist.data_ptr(), N, D, nnz,
-                                  int(loss), float(lam), float(step), 0, int(hist_cap))
+                                  int(loss), float(lam), float(step), 0, int(hist_cap), 0, int(schedule))
 
     @property
     def hist_len(self) -> int:

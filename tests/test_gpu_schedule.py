@@ -103,3 +103,29 @@ def test_hinge_loss_flattens_under_the_decaying_step():
     assert out["constant"][1] > 0.9 * out["constant"][0]          # still falling at the initial rate
     assert out["decaying"][1] < 0.05 * out["decaying"][0]         # flattened
     assert out["decaying"][2] < out["constant"][2]                # and further down
+
+
+@pytest.mark.parametrize("loss,eta", [(synth.LOGISTIC, 1.0), (synth.HINGE, 0.2)])
+def test_sparse_job_with_the_decaying_schedule(loss, eta):
+    _say(f"[case] sparse, step / sqrt(k + 1): trajectory against the oracle and 6 = 2 + 4 iterations, loss {loss}")
+    p = synth.make_sparse_glm(loss, 20000, 3000, 12.0, seed=36, lam=1e-4, eta=eta, K=6)
+    t = lambda x: x.cuda()
+
+    def job():
+        return glm.SparseJob(t(p.row_ptr), t(p.col_idx), t(p.row_val), t(p.col_ptr), t(p.row_idx), t(p.col_val), t(p.y),
+                             p.w0.cuda().clone(), p.loss, p.lam, eta, 6, schedule=glm.GLM_STEP_INV_SQRT)
+    a = job()
+    glm.glm_step_sparse(a, 6, glm.alloc_sparse_workspace(a))
+    b = job()
+    ws = glm.alloc_sparse_workspace(b)
+    glm.glm_step_sparse(b, 2, ws); glm.glm_step_sparse(b, 4, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a.history(), b.history()) and torch.equal(a.w, b.w)
+    lh, gh, w, _ = oracle.sparse_run_schedule(p.loss, p.row_ptr.numpy(), p.col_idx.numpy(), p.row_val.numpy(), p.y.numpy(),
+                                              p.D, np.zeros(p.D), p.lam, eta, oracle.INV_SQRT, 6)
+    got = a.history().cpu().numpy()
+    assert max(rel(x, y) for x, y in zip(got, lh)) <= REL_TOL
+    assert np.max(np.abs(a.w.cpu().numpy() - w)) <= REL_TOL * np.max(np.abs(w))
+    const = oracle.sparse_run(p.loss, p.row_ptr.numpy(), p.col_idx.numpy(), p.row_val.numpy(), p.y.numpy(), p.D,
+                              np.zeros(p.D), p.lam, eta, 6)[2]
+    assert np.max(np.abs(a.w.cpu().numpy() - const)) > 100 * REL_TOL * np.max(np.abs(w))     # not the constant step

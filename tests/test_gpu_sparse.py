@@ -180,6 +180,11 @@ def test_sparse_errors():
         glm.glm_step_sparse(job, 1, ws)
     assert e.value.status == glm.GLM_EINVAL
     job.c.loss = 0
+    job.c.schedule = 5
+    with pytest.raises(glm.GlmError) as e:
+        glm.glm_step_sparse(job, 1, ws)
+    assert e.value.status == glm.GLM_EINVAL
+    job.c.schedule = 0
     job.c.lambda_ = -1.0
     with pytest.raises(glm.GlmError):
         glm.glm_step_sparse(job, 1, ws)
