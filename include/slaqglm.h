@@ -17,7 +17,7 @@
  *     l_i,r_i = per-sample loss and residual dl/dz (see glm_loss_t)
  *     L_k   = (1/N) sum_i l_i + (lambda/2) |w_k|^2          -> loss_hist[hist_len + k]
  *     g_k   = (1/N) X^T r + lambda w_k                       -> grad
- *     w_k+1 = w_k - step * g_k                               -> w
+ *     w_k+1 = w_k - step_k * g_k                             -> w   (step_k: glm_step_schedule_t)
  * X is streamed from device memory exactly once per iteration.
  *
  * Conventions for every entry point
@@ -31,6 +31,9 @@
  *     the default stream) and the call returns without waiting for it.
  *     Results are valid once the stream has been synchronised.  Calls that
  *     share a workspace must be ordered on one stream.
+ *   - Host threads may call the entry points concurrently (on different jobs,
+ *     workspaces and streams); the small host-side staging areas the library keeps
+ *     are guarded by locks.  The measurement hooks at the end are the exception.
  *   - Results are deterministic: the same library, device and arguments give
  *     bit-identical loss_hist, grad and w on every run (no floating-point
  *     atomics; every reduction has a fixed order that depends only on N and D
