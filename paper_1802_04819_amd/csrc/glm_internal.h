@@ -67,7 +67,7 @@ hipError_t launch_row_pass(const DevJob *jobs, const int *blk_job, int total_blo
 hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int total_blocks,
                            int round, hipStream_t st);
 hipError_t launch_read_probe(const float *src, size_t n, float *sink, hipStream_t st);
-constexpr int kProbeBlocks = 4096;
+constexpr int kProbeBlocks = 512;   // two per compute unit, as the row pass: measured best for 1 GB and 16 GB
 
 // Sweep (glm_sweep.hip).  M models are padded to kSweepM columns of R and rows of Gpart.
 constexpr int kSweepM = 64;

@@ -434,7 +434,7 @@ hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int t
 
 __global__ __launch_bounds__(256) void read_probe_kernel(const f4 *__restrict__ src, size_t n4,
                                                          float *__restrict__ sink) {
-    __shared__ float red[256];
+    __shared__ float red[4];
     float acc = 0.0f;
     // a block reads one contiguous span, as a block of the row pass reads its rows
     const size_t span = (n4 + gridDim.x - 1) / gridDim.x;
@@ -452,13 +452,11 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const f4 *__restrict__ 
         const f4 v = stream_load(src + i);
         acc += (v.x + v.y) + (v.z + v.w);
     }
-    red[threadIdx.x] = acc;
+    // a short tail: the probe is a ceiling only if nothing but the loads takes time
+    for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        float s = 0.0f;
-        for (int q = 0; q < 256; ++q) s += red[q];
-        sink[blockIdx.x] = s;
-    }
+    if (threadIdx.x == 0) sink[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 hipError_t launch_read_probe(const float *src, size_t n, float *sink, hipStream_t st) {
