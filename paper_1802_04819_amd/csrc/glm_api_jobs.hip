@@ -1,5 +1,6 @@
 // C-ABI entry points of the job kinds other than the dense GLM step: sparse GLM step, K-Means,
 // L-BFGS.  Validation happens before anything is enqueued; see include/slaqglm.h.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -19,11 +20,14 @@ namespace {
 struct SparseLayout {
     size_t seg0R, seg0C, closes, headless, slast, H, T, z, r, lossP, wwP, total;
     size_t pp, ptr2, bsum, idx2, val2, seg0P, gs2, flag;     // row-panelled column layout (P > 1)
+    size_t fx_slots, fx_cnt, fx_bsum;                        // fixed-point scatter path
+    size_t fx_gidx[2], fx_loc[2], fx_val[2], fx_pstart[2], fx_cstart[2], fx_part[2];   // [0] row pass, [1] column pass
+    FxPass fx_row, fx_col;
     long long nch;
     int P;
 };
 SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
-    SparseLayout L;
+    SparseLayout L{};
     L.nch = (nnz + kSparseChunk - 1) / kSparseChunk;
     const size_t nc = (size_t)L.nch;
     size_t off = 0;
@@ -38,7 +42,11 @@ SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
     L.r = off;        off = api_align_up(off + sizeof(float) * (size_t)N);
     L.lossP = off;    off = api_align_up(off + sizeof(float) * (size_t)((N + 255) / 256));
     L.wwP = off;      off = api_align_up(off + sizeof(double) * (size_t)((D + 255) / 256));
-    L.P = sparse_panel_count(N, D);
+    sparse_fx_plan(N, D, nnz, &L.fx_row, &L.fx_col);
+    const bool any_fx = L.fx_row.on || L.fx_col.on;
+    // the row-panelled column layout is the older remedy for the column pass; with the scatter
+    // path in use it is not built
+    L.P = any_fx ? 1 : sparse_panel_count(N, D);
     L.pp = L.ptr2 = L.bsum = L.idx2 = L.val2 = L.seg0P = L.gs2 = L.flag = off;
     if (L.P > 1) {
         const size_t S2 = (size_t)L.P * (size_t)D;
@@ -50,6 +58,27 @@ SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
         L.val2 = off;  off = api_align_up(off + sizeof(float) * (size_t)nnz);
         L.seg0P = off; off = api_align_up(off + sizeof(int) * (nc + 1));
         L.gs2 = off;   off = api_align_up(off + sizeof(float) * S2);
+    }
+    L.fx_slots = L.fx_cnt = L.fx_bsum = off;
+    for (int i = 0; i < 2; ++i) L.fx_gidx[i] = L.fx_loc[i] = L.fx_val[i] = L.fx_pstart[i] = L.fx_cstart[i] = L.fx_part[i] = off;
+    if (any_fx) {
+        const FxPass *ps[2] = {&L.fx_row, &L.fx_col};
+        long long maxP = 1, ntiles = 1;
+        for (int i = 0; i < 2; ++i)
+            if (ps[i]->on) { maxP = std::max<long long>(maxP, ps[i]->P); ntiles = ps[i]->ntiles; }
+        const size_t ncnt = (size_t)maxP * (size_t)ntiles;
+        L.fx_slots = off; off = api_align_up(off + sizeof(unsigned) * kFxSlots);
+        L.fx_cnt = off;   off = api_align_up(off + sizeof(long long) * (ncnt + 1));
+        L.fx_bsum = off;  off = api_align_up(off + sizeof(long long) * ((ncnt + kScanBlock - 1) / kScanBlock + 2));
+        for (int i = 0; i < 2; ++i) {
+            if (!ps[i]->on) continue;
+            L.fx_gidx[i] = off;   off = api_align_up(off + sizeof(int) * (size_t)nnz);
+            L.fx_loc[i] = off;    off = api_align_up(off + sizeof(unsigned short) * (size_t)nnz);
+            L.fx_val[i] = off;    off = api_align_up(off + sizeof(float) * (size_t)nnz);
+            L.fx_pstart[i] = off; off = api_align_up(off + sizeof(long long) * ((size_t)ps[i]->P + 1));
+            L.fx_cstart[i] = off; off = api_align_up(off + sizeof(long long) * ((size_t)ps[i]->P + 1));
+            L.fx_part[i] = off;   off = api_align_up(off + sizeof(long long) * (size_t)ps[i]->max_chunks * kFxPanel);
+        }
     }
     L.total = off;
     return L;
@@ -139,10 +168,30 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     pn.idx2 = reinterpret_cast<int *>(base + L.idx2); pn.val2 = reinterpret_cast<float *>(base + L.val2);
     pn.seg0 = reinterpret_cast<int *>(base + L.seg0P); pn.gs2 = reinterpret_cast<float *>(base + L.gs2);
     pn.flag = reinterpret_cast<int *>(base + L.flag);
-    // job->prepared: 0 = nothing built yet, 1 = panelled layout in the workspace, 2 = caller's layout is used
+    SparseFx fx;
+    fx.row = L.fx_row; fx.col = L.fx_col;
+    fx.slots = reinterpret_cast<unsigned *>(base + L.fx_slots);
+    fx.cnt = reinterpret_cast<long long *>(base + L.fx_cnt); fx.bsum = reinterpret_cast<long long *>(base + L.fx_bsum);
+    {
+        FxPass *ps[2] = {&fx.row, &fx.col};
+        for (int i = 0; i < 2; ++i) {
+            ps[i]->gidx = reinterpret_cast<int *>(base + L.fx_gidx[i]);
+            ps[i]->loc = reinterpret_cast<unsigned short *>(base + L.fx_loc[i]);
+            ps[i]->val = reinterpret_cast<float *>(base + L.fx_val[i]);
+            ps[i]->pstart = reinterpret_cast<long long *>(base + L.fx_pstart[i]);
+            ps[i]->cstart = reinterpret_cast<long long *>(base + L.fx_cstart[i]);
+            ps[i]->part = reinterpret_cast<long long *>(base + L.fx_part[i]);
+        }
+    }
+    const bool any_fx = (fx.row.on || fx.col.on) && j.nnz > 0;
+    // job->prepared: 0 = nothing built yet, 1 = auxiliary layouts in the workspace, 2 = caller's layout is used
     const PanelKey key{ws, j.col_ptr, j.row_idx, j.col_val, j.N, j.D, j.nnz};
-    if (job->prepared == 1 && !(pn.P > 1 && j.nnz > 0 && panel_registry_has(key))) job->prepared = 0;
-    if (pn.P > 1 && j.nnz > 0 && job->prepared == 0) {
+    if (job->prepared == 1 && !((pn.P > 1 || any_fx) && j.nnz > 0 && panel_registry_has(key))) job->prepared = 0;
+    if (any_fx && job->prepared == 0) {
+        if (launch_sparse_fx_build(a, fx, st) != hipSuccess) return GLM_EHIP;
+        panel_registry_put(key);
+        job->prepared = 1;
+    } else if (pn.P > 1 && j.nnz > 0 && job->prepared == 0) {
         if (launch_sparse_sorted_check(a, pn, st) != hipSuccess) return GLM_EHIP;
         int unsorted = 0;
         if (hipStreamSynchronize(st) != hipSuccess ||
@@ -158,10 +207,12 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     } else if (job->prepared == 0) {
         job->prepared = 2;
     }
-    if (job->prepared != 1) pn.P = 1;
+    if (job->prepared != 1) { pn.P = 1; fx.row.on = fx.col.on = 0; }
+    if (!any_fx) fx.row.on = fx.col.on = 0;
+    if ((fx.row.on || fx.col.on) && launch_sparse_fx_begin(a, fx, st) != hipSuccess) return GLM_EHIP;
     for (int k = 0; k < iters; ++k) {
         hipEvent_t *ev = api_profile_take(1);
-        if (launch_sparse_iteration_panels(a, pn, k, ev, st) != hipSuccess) return GLM_EHIP;
+        if (launch_sparse_iteration_any(a, pn, fx, k, ev, st) != hipSuccess) return GLM_EHIP;
     }
     job->hist_len += iters;
     return GLM_OK;

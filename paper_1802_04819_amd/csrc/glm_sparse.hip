@@ -201,18 +201,38 @@ __global__ void fill_zero_kernel(float *__restrict__ p, long long n) {
     if (i < n) p[i] = 0.0f;
 }
 
+// For the fixed-point passes: the largest |v| of the block goes into *maxslot (bit patterns of
+// non-negative floats order as unsigned integers; the maximum does not depend on the order), and
+// block 0 clears *zeroslot, which the next kernel but one accumulates into.  Both may be null.
+__device__ __forceinline__ void block_absmax(float v, unsigned *__restrict__ maxslot, unsigned *__restrict__ zeroslot) {
+    __shared__ unsigned redm[256];
+    if (maxslot) {
+        redm[threadIdx.x] = __float_as_uint(v) & 0x7FFFFFFFu;
+        __syncthreads();
+        for (int s = 128; s >= 1; s >>= 1) {
+            if (threadIdx.x < s) redm[threadIdx.x] = max(redm[threadIdx.x], redm[threadIdx.x + s]);
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) atomicMax(maxslot, redm[0]);
+    }
+    if (zeroslot && blockIdx.x == 0 && threadIdx.x == 0) *zeroslot = 0u;
+}
+
 // Rows: margins -> loss and residual; per-block loss sums in a fixed tree.
 __global__ __launch_bounds__(256) void sparse_row_epilogue(const float *__restrict__ z, const float *__restrict__ y,
                                                            long long N, int loss, float *__restrict__ r,
-                                                           float *__restrict__ lossP) {
+                                                           float *__restrict__ lossP, unsigned *__restrict__ maxslot,
+                                                           unsigned *__restrict__ zeroslot) {
     __shared__ float red[256];
     const long long i = blockIdx.x * 256LL + threadIdx.x;
-    float l = 0.0f;
+    float l = 0.0f, rmag = 0.0f;
     if (i < N) {
         float rr;
         loss_residual(loss, z[i], y[i], l, rr);
         r[i] = rr;
+        rmag = rr;
     }
+    block_absmax(rmag, maxslot, zeroslot);
     red[threadIdx.x] = l;
     __syncthreads();
     for (int s = 128; s >= 1; s >>= 1) {
@@ -225,17 +245,22 @@ __global__ __launch_bounds__(256) void sparse_row_epilogue(const float *__restri
 // Columns: X^T r -> gradient, update; per-block sums of w^2 (entering iterate) in a fixed tree.
 __global__ __launch_bounds__(256) void sparse_col_epilogue(const float *__restrict__ gs, long long D, double invN,
                                                            float lambda, double step, float *__restrict__ w,
-                                                           float *__restrict__ grad, double *__restrict__ wwP) {
+                                                           float *__restrict__ grad, double *__restrict__ wwP,
+                                                           unsigned *__restrict__ maxslot,
+                                                           unsigned *__restrict__ zeroslot) {
     __shared__ double red[256];
     const long long j = blockIdx.x * 256LL + threadIdx.x;
     double ww = 0.0;
+    float wnew = 0.0f;
     if (j < D) {
         const float wj = w[j];
         const double g = (double)gs[j] * invN + (double)lambda * (double)wj;
         grad[j] = (float)g;
         ww = (double)wj * (double)wj;
-        if (step != 0.0) w[j] = (float)((double)wj - step * g);
+        wnew = wj;
+        if (step != 0.0) { wnew = (float)((double)wj - step * g); w[j] = wnew; }
     }
+    block_absmax(wnew, maxslot, zeroslot);
     red[threadIdx.x] = ww;
     __syncthreads();
     for (int s = 128; s >= 1; s >>= 1) {
@@ -304,13 +329,13 @@ hipError_t launch_sparse_iteration(const SparseArgs &a, int k, hipEvent_t *ev, h
     if ((e = seg_pass(a.row_ptr, a.col_idx, a.row_val, a.w, a.N, a.nnz, a.nch, a.seg0R, a.z, rec, st)) != hipSuccess)
         return e;
     const unsigned nbR = (unsigned)((a.N + 255) / 256), nbC = (unsigned)((a.D + 255) / 256);
-    hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP);
+    hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP, nullptr, nullptr);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = seg_pass(a.col_ptr, a.row_idx, a.col_val, a.r, a.D, a.nnz, a.nch, a.seg0C, a.gs, rec, st)) != hipSuccess)
         return e;
     if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_col_epilogue, dim3(nbC), dim3(256), 0, st, a.gs, a.D, 1.0 / (double)a.N, a.lambda,
-                       sparse_step(a, k), a.w, a.grad, a.wwP);
+                       sparse_step(a, k), a.w, a.grad, a.wwP, nullptr, nullptr);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_loss_kernel, dim3(1), dim3(1024), 0, st, a.lossP, (long long)nbR, a.wwP,
                        (long long)nbC, 1.0 / (double)a.N, a.lambda, a.loss_out + k);
@@ -424,10 +449,13 @@ __global__ __launch_bounds__(256) void panel_copy_kernel(const long long *__rest
 __global__ __launch_bounds__(256) void sparse_col_epilogue_panels(const float *__restrict__ gs2, int P, long long D,
                                                                   double invN, float lambda, double step,
                                                                   float *__restrict__ w, float *__restrict__ grad,
-                                                                  double *__restrict__ wwP) {
+                                                                  double *__restrict__ wwP,
+                                                                  unsigned *__restrict__ maxslot,
+                                                                  unsigned *__restrict__ zeroslot) {
     __shared__ double red[256];
     const long long j = blockIdx.x * 256LL + threadIdx.x;
     double ww = 0.0;
+    float wnew = 0.0f;
     if (j < D) {
         double s = 0.0;
         for (int p = 0; p < P; ++p) s += (double)gs2[(size_t)p * D + j];
@@ -435,8 +463,10 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue_panels(const float *_
         const double g = s * invN + (double)lambda * (double)wj;
         grad[j] = (float)g;
         ww = (double)wj * (double)wj;
-        if (step != 0.0) w[j] = (float)((double)wj - step * g);
+        wnew = wj;
+        if (step != 0.0) { wnew = (float)((double)wj - step * g); w[j] = wnew; }
     }
+    block_absmax(wnew, maxslot, zeroslot);
     red[threadIdx.x] = ww;
     __syncthreads();
     for (int s = 128; s >= 1; s >>= 1) {
@@ -493,13 +523,60 @@ hipError_t launch_sparse_iteration_panels(const SparseArgs &a, const SparsePanel
     if ((e = seg_pass(a.row_ptr, a.col_idx, a.row_val, a.w, a.N, a.nnz, a.nch, a.seg0R, a.z, rec, st)) != hipSuccess)
         return e;
     const unsigned nbR = (unsigned)((a.N + 255) / 256), nbC = (unsigned)((a.D + 255) / 256);
-    hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP);
+    hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP, nullptr, nullptr);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = seg_pass(pn.ptr2, pn.idx2, pn.val2, a.r, S2, a.nnz, a.nch, pn.seg0, pn.gs2, rec, st)) != hipSuccess)
         return e;
     if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_col_epilogue_panels, dim3(nbC), dim3(256), 0, st, pn.gs2, pn.P, a.D, 1.0 / (double)a.N,
-                       a.lambda, sparse_step(a, k), a.w, a.grad, a.wwP);
+                       a.lambda, sparse_step(a, k), a.w, a.grad, a.wwP, nullptr, nullptr);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(sparse_loss_kernel, dim3(1), dim3(1024), 0, st, a.lossP, (long long)nbR, a.wwP,
+                       (long long)nbC, 1.0 / (double)a.N, a.lambda, a.loss_out + k);
+    return hipGetLastError();
+}
+
+// One iteration with each product on the path chosen for it: fixed-point scatter (fx), the
+// row-panelled column layout (pn, column pass only) or the plain segmented sums.
+hipError_t launch_sparse_iteration_any(const SparseArgs &a, const SparsePanels &pn, const SparseFx &fx, int k,
+                                       hipEvent_t *ev, hipStream_t st) {
+    if (!fx.row.on && !fx.col.on) return launch_sparse_iteration_panels(a, pn, k, ev, st);
+    hipError_t e;
+    ChunkRec rec{a.closes, a.headless, a.slast, a.H, a.T};
+    const bool panels = !fx.col.on && pn.P > 1;
+    const long long S2 = (long long)pn.P * a.D;
+    // the segmented sums add into their outputs: clear those
+    if (!fx.row.on) {
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((a.N + 255) / 256)), dim3(256), 0, st, a.z, a.N);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (!fx.col.on) {
+        float *dst = panels ? pn.gs2 : a.gs;
+        const long long n = panels ? S2 : a.D;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dst, n);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
+    if (fx.row.on) e = launch_sparse_fx_pass(fx, true, a.w, a.D, a.nnz, a.z, st);
+    else e = seg_pass(a.row_ptr, a.col_idx, a.row_val, a.w, a.N, a.nnz, a.nch, a.seg0R, a.z, rec, st);
+    if (e != hipSuccess) return e;
+    const unsigned nbR = (unsigned)((a.N + 255) / 256), nbC = (unsigned)((a.D + 255) / 256);
+    // max |r| feeds the column pass's scale; max |w| is cleared here and refilled by the column epilogue
+    hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP,
+                       fx.col.on ? fx.slots + kFxSlotMaxR : nullptr, fx.row.on ? fx.slots + kFxSlotMaxW : nullptr);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (fx.col.on) e = launch_sparse_fx_pass(fx, false, a.r, a.N, a.nnz, a.gs, st);
+    else if (panels) e = seg_pass(pn.ptr2, pn.idx2, pn.val2, a.r, S2, a.nnz, a.nch, pn.seg0, pn.gs2, rec, st);
+    else e = seg_pass(a.col_ptr, a.row_idx, a.col_val, a.r, a.D, a.nnz, a.nch, a.seg0C, a.gs, rec, st);
+    if (e != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
+    unsigned *mw = fx.row.on ? fx.slots + kFxSlotMaxW : nullptr, *zr = fx.col.on ? fx.slots + kFxSlotMaxR : nullptr;
+    if (panels)
+        hipLaunchKernelGGL(sparse_col_epilogue_panels, dim3(nbC), dim3(256), 0, st, pn.gs2, pn.P, a.D, 1.0 / (double)a.N,
+                           a.lambda, sparse_step(a, k), a.w, a.grad, a.wwP, mw, zr);
+    else
+        hipLaunchKernelGGL(sparse_col_epilogue, dim3(nbC), dim3(256), 0, st, a.gs, a.D, 1.0 / (double)a.N, a.lambda,
+                           sparse_step(a, k), a.w, a.grad, a.wwP, mw, zr);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(sparse_loss_kernel, dim3(1), dim3(1024), 0, st, a.lossP, (long long)nbR, a.wwP,
                        (long long)nbC, 1.0 / (double)a.N, a.lambda, a.loss_out + k);

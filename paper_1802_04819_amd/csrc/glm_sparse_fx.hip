@@ -1,0 +1,407 @@
+// Sparse products by scatter into LDS with fixed-point sums.
+//
+// The segmented sums of glm_sparse.hip gather one value of the other vector per stored entry; with
+// vectors of millions of elements every gather of a wave touches 64 different cache lines and
+// the pass runs at the rate of the cache, not of memory.  Here the roles are turned round.  The
+// outputs (rows of z = X w, or columns of s = X^T r) are cut into panels of 16384; the entries of
+// a panel are stored together, ordered by the index of the OTHER dimension, so that
+//   - the value gathered from the other vector moves monotonically through memory while the
+//     panel streams by (a wave's 64 gathers fall into one or two cache lines), and
+//   - the 16384 sums of the panel live in LDS (128 KB) and every product is added to its sum
+//     there.
+// Adding in LDS means atomics, and the order of floating-point atomics is not fixed.  So the sums
+// are integers: a product p becomes round(p * 2^e) as a 64-bit integer, with e chosen from the
+// largest magnitudes present so that no sum can overflow (|sum| 2^e < 2^62).  Integer addition
+// is associative: whatever the order, the sum is the same, and reruns are bit-identical.  The
+// resolution is 2^-(62 - log2 longest run) of the largest possible product: far finer than the
+// 2^-24 of an fp32 product.
+//
+// Layout of a pass (built once per matrix, in the workspace): entries sorted by (panel of the
+// output index, position in the source layout).  For the row pass the source is the caller's
+// column layout (CSC: within a panel, columns ascend), for the column pass the row layout (CSR).
+// Per entry: the index into the gathered vector (int32), the output index inside its panel
+// (uint16) and the value (fp32): 10 bytes.  A panel is shared by as many blocks as its entries
+// call for (contiguous chunks of a fixed length: popular columns make some panels hundreds of
+// times larger than others); each block writes its 16384 partial sums, a small kernel adds the
+// slices of a panel and converts to fp32.
+#include "sparse_internal.h"
+
+#include <cmath>
+
+namespace slaqglm {
+
+namespace {
+
+constexpr int kFxTile = 2048;            // entries per tile of the split (one wave, 32 steps of 64)
+constexpr int kFxThreads = 1024;
+constexpr int kFxUnroll = 4;
+
+// ------------------------------------------------------------------ building the layout
+
+// cnt[key * ntiles + tile] = entries of the tile whose output index lies in panel `key`
+__global__ __launch_bounds__(256) void fx_hist_kernel(const int *__restrict__ idx, long long nnz, long long ntiles,
+                                                      int P, long long *__restrict__ cnt) {
+    __shared__ int hist[4][kFxMaxPanels];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int i = lane; i < kFxMaxPanels; i += 64) hist[wave][i] = 0;
+    __syncthreads();
+    const long long tile = blockIdx.x * 4LL + wave;
+    if (tile < ntiles) {
+        const long long e0 = tile * kFxTile;
+        for (int s = 0; s < kFxTile / 64; ++s) {
+            const long long e = e0 + s * 64 + lane;
+            if (e < nnz) {
+                const unsigned key = min((unsigned)idx[e] >> 14, (unsigned)(P - 1));
+                atomicAdd(&hist[wave][key], 1);
+            }
+        }
+    }
+    __syncthreads();
+    if (tile < ntiles)
+        for (int k = lane; k < P; k += 64) cnt[(long long)k * ntiles + tile] = hist[wave][k];
+}
+
+// exclusive prefix sum of a[0 .. n), total to a[n]: blocks of 4096, block totals by one thread, add
+__global__ __launch_bounds__(256) void fx_scan_block_kernel(long long *__restrict__ a, long long n,
+                                                            long long *__restrict__ bsum) {
+    __shared__ long long tot[256];
+    const long long base = (long long)blockIdx.x * kScanBlock + threadIdx.x * 16LL;
+    long long v[16], run = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const long long s = base + q;
+        v[q] = run;
+        run += s < n ? a[s] : 0;
+    }
+    tot[threadIdx.x] = run;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long acc = 0;
+        for (int t = 0; t < 256; ++t) { const long long x = tot[t]; tot[t] = acc; acc += x; }
+        bsum[blockIdx.x] = acc;
+    }
+    __syncthreads();
+    const long long off = tot[threadIdx.x];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const long long s = base + q;
+        if (s < n) a[s] = v[q] + off;
+    }
+}
+
+__global__ void fx_scan_tops_kernel(long long nb, long long *__restrict__ bsum) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    long long acc = 0;
+    for (long long b = 0; b < nb; ++b) { const long long x = bsum[b]; bsum[b] = acc; acc += x; }
+    bsum[nb] = acc;
+}
+
+__global__ __launch_bounds__(256) void fx_scan_add_kernel(long long n, const long long *__restrict__ bsum, long long nb,
+                                                          long long *__restrict__ a) {
+    const long long s = blockIdx.x * 256LL + threadIdx.x;
+    if (s < n) a[s] += bsum[s / kScanBlock];
+    if (s == n) a[n] = bsum[nb];
+}
+
+// pstart[p] = first entry of panel p (p == P: the total, stored at cnt[P * ntiles]);
+// cstart[p] = first block of panel p when every block takes `chunk` entries.  One thread: P <= 256.
+__global__ void fx_pstart_kernel(const long long *__restrict__ cnt, long long ntiles, int P, long long chunk,
+                                 long long *__restrict__ pstart, long long *__restrict__ cstart) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    long long blocks = 0;
+    for (int p = 0; p <= P; ++p) {
+        const long long s = cnt[(long long)p * ntiles];
+        pstart[p] = s;
+        cstart[p] = blocks;
+        if (p < P) blocks += (cnt[(long long)(p + 1) * ntiles] - s + chunk - 1) / chunk;
+    }
+}
+
+// largest m in [lo, hi] with ptr[m] <= e  (ptr[lo] <= e is given)
+__device__ __forceinline__ long long fx_owner(const long long *__restrict__ ptr, long long lo, long long hi, long long e) {
+    while (lo < hi) {
+        const long long mid = lo + (hi - lo + 1) / 2;
+        if (ptr[mid] <= e) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Stable split: entry e of the source layout goes to the next free place of its panel.  One wave
+// per tile, 64 entries per step in source order; inside a step the lanes with the same panel
+// are ranked by lane.
+__global__ __launch_bounds__(256) void fx_scatter_kernel(const long long *__restrict__ ptr, long long M,
+                                                         const int *__restrict__ idx, const float *__restrict__ val,
+                                                         long long nnz, long long ntiles, int P,
+                                                         const long long *__restrict__ cnt, int *__restrict__ gidx,
+                                                         unsigned short *__restrict__ loc, float *__restrict__ valo) {
+    __shared__ long long cur[4][kFxMaxPanels];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long tile = blockIdx.x * 4LL + wave;
+    if (tile < ntiles)
+        for (int k = lane; k < P; k += 64) cur[wave][k] = cnt[(long long)k * ntiles + tile];
+    __syncthreads();
+    if (tile >= ntiles) return;                        // whole waves leave: no block-wide barrier below
+    const long long e0 = tile * kFxTile;
+    const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    for (int s = 0; s < kFxTile / 64; ++s) {
+        const long long eb = e0 + s * 64;
+        if (eb >= nnz) break;
+        const long long e = eb + lane;
+        const bool ok = e < nnz;
+        const long long elast = eb + 63 < nnz ? eb + 63 : nnz - 1;
+        // owners (row of a CSR entry, column of a CSC entry): between those of the step's ends
+        const long long m0 = fx_owner(ptr, 0, M - 1, eb);
+        const long long m1 = fx_owner(ptr, m0, M - 1, elast);
+        const long long m = ok ? fx_owner(ptr, m0, m1, e) : m0;
+        const int raw = ok ? idx[e] : 0;
+        const unsigned key = min((unsigned)raw >> 14, (unsigned)(P - 1));
+        long long pos = 0;
+        unsigned long long todo = __ballot(ok);
+        while (todo) {
+            const int lead = __builtin_ctzll(todo);
+            const unsigned kk = (unsigned)__builtin_amdgcn_readlane((int)key, lead);
+            const unsigned long long same = __ballot(ok && key == kk);
+            const long long base = cur[wave][kk];
+            if (ok && key == kk) pos = base + __builtin_popcountll(same & lt);
+            if (lane == lead) cur[wave][kk] = base + __builtin_popcountll(same);
+            todo &= ~same;
+        }
+        if (ok) {
+            gidx[pos] = (int)m;
+            loc[pos] = (unsigned short)((unsigned)raw & (kFxPanel - 1));
+            valo[pos] = val[e];
+        }
+    }
+}
+
+// *slot = max(*slot, bits of max |x|); bits of non-negative floats order as unsigned integers
+__global__ __launch_bounds__(256) void fx_absmax_kernel(const float *__restrict__ x, long long n,
+                                                        unsigned *__restrict__ slot) {
+    __shared__ unsigned red[256];
+    unsigned m = 0;
+    for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n; i += (long long)gridDim.x * 256)
+        m = max(m, __float_as_uint(x[i]) & 0x7FFFFFFFu);
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] = max(red[threadIdx.x], red[threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) atomicMax(slot, red[0]);
+}
+
+// *slot = max(*slot, longest run ptr[m + 1] - ptr[m]), capped at 2^31 - 1
+__global__ __launch_bounds__(256) void fx_maxlen_kernel(const long long *__restrict__ ptr, long long M,
+                                                        unsigned *__restrict__ slot) {
+    __shared__ unsigned red[256];
+    unsigned m = 0;
+    for (long long i = blockIdx.x * 256LL + threadIdx.x; i < M; i += (long long)gridDim.x * 256) {
+        const long long len = ptr[i + 1] - ptr[i];
+        m = max(m, (unsigned)(len < 0 ? 0 : len > 0x7FFFFFFFLL ? 0x7FFFFFFFLL : len));
+    }
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] = max(red[threadIdx.x], red[threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) atomicMax(slot, red[0]);
+}
+
+__global__ void fx_set_slots_kernel(unsigned *__restrict__ slots, int first, int count) {
+    const int i = threadIdx.x;
+    if (i < count) slots[first + i] = 0;
+}
+
+// ------------------------------------------------------------------ the pass
+
+// Exponent e with |sum of maxlen products| * 2^e < 2^62, from the bit patterns of the largest
+// |value| and the largest |element of the gathered vector|: |v| < 2^(ev + 1), |x| < 2^(ex + 1).
+__device__ __forceinline__ int fx_exponent(unsigned maxval_bits, unsigned maxvec_bits, unsigned maxlen) {
+    const int ev = (int)((maxval_bits >> 23) & 255u) - 127;
+    const int ex = (int)((maxvec_bits >> 23) & 255u) - 127;
+    const int cl = maxlen > 1 ? 32 - __clz((int)(maxlen - 1)) : 0;
+    const int e = 60 - ev - ex - cl;
+    return e < -126 ? -126 : e > 126 ? 126 : e;
+}
+
+__global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
+    const int *__restrict__ gidx, const unsigned short *__restrict__ loc, const float *__restrict__ val,
+    const float *__restrict__ vec, long long vec_len, long long nnz, const long long *__restrict__ pstart,
+    const long long *__restrict__ cstart, int P, long long chunk, unsigned *slots, int vec_slot, int len_slot,
+    int e_slot, long long *__restrict__ part) {
+    extern __shared__ unsigned long long fx_sums[];    // [kFxPanel]
+    __shared__ int s_panel;
+    const int tid = threadIdx.x;
+    // which panel this block belongs to: the last p with cstart[p] <= blockIdx (blocks past the
+    // last panel's have nothing to do: the grid is an upper bound known from the shape alone)
+    if (tid == 0) {
+        int p = -1;
+        if ((long long)blockIdx.x < cstart[P]) {
+            int lo = 0, hi = P - 1;
+            while (lo < hi) {
+                const int mid = lo + (hi - lo + 1) / 2;
+                if (cstart[mid] <= (long long)blockIdx.x) lo = mid; else hi = mid - 1;
+            }
+            p = lo;
+        }
+        s_panel = p;
+    }
+    for (int i = tid; i < kFxPanel; i += kFxThreads) fx_sums[i] = 0ull;
+    const int e2 = fx_exponent(slots[kFxSlotMaxVal], slots[vec_slot], slots[len_slot]);
+    if (blockIdx.x == 0 && tid == 0) slots[e_slot] = (unsigned)e2;          // for the kernel that converts back
+    const float scale = __builtin_ldexpf(1.0f, e2);
+    const unsigned vmax = (unsigned)(vec_len - 1);
+    __syncthreads();
+    const int p = s_panel;
+    if (p < 0) return;                                 // uniform over the block
+    long long s0 = pstart[p], s1 = pstart[p + 1];
+    s0 = s0 < 0 ? 0 : s0 > nnz ? nnz : s0;
+    s1 = s1 < s0 ? s0 : s1 > nnz ? nnz : s1;
+    const long long c = (long long)blockIdx.x - cstart[p];
+    long long b0 = s0 + c * chunk, b1 = b0 + chunk;
+    b0 = b0 > s1 ? s1 : b0;
+    b1 = b1 > s1 ? s1 : b1;
+    // Two loads stand between an entry and its sum: the entry itself, then the element of the
+    // other vector it points at.  The entries of the next round are requested before the current
+    // round's elements are waited for, so that one latency is paid per round, not two.
+    int g[kFxUnroll]; unsigned l[kFxUnroll]; float v[kFxUnroll];
+#define SLAQ_FX_LOAD(E)                                                                      \
+    _Pragma("unroll") for (int u = 0; u < kFxUnroll; ++u) {                                  \
+        const long long eu_ = (E) + (long long)u * kFxThreads;                               \
+        const bool ok_ = eu_ < b1;                                                           \
+        /* the layout is the library's own, but it lives in the caller's workspace: keep     \
+           every index inside its array whatever the memory holds */                         \
+        g[u] = ok_ ? (int)min((unsigned)__builtin_nontemporal_load(gidx + eu_), vmax) : 0;   \
+        l[u] = ok_ ? (unsigned)__builtin_nontemporal_load(loc + eu_) & (unsigned)(kFxPanel - 1) : 0u; \
+        v[u] = ok_ ? __builtin_nontemporal_load(val + eu_) : 0.0f;                           \
+    }
+    const long long stride = (long long)kFxThreads * kFxUnroll;
+    long long e = b0 + tid;
+    if (e < b1) SLAQ_FX_LOAD(e)
+    for (; e < b1; e += stride) {
+        float x[kFxUnroll], vv[kFxUnroll]; unsigned ll[kFxUnroll];
+#pragma unroll
+        for (int u = 0; u < kFxUnroll; ++u) { x[u] = vec[g[u]]; vv[u] = v[u]; ll[u] = l[u]; }
+        if (e + stride < b1) SLAQ_FX_LOAD(e + stride)
+#pragma unroll
+        for (int u = 0; u < kFxUnroll; ++u) {
+            const long long q = __float2ll_rn((vv[u] * x[u]) * scale);
+            if (e + (long long)u * kFxThreads < b1) atomicAdd(&fx_sums[ll[u]], (unsigned long long)q);
+        }
+    }
+#undef SLAQ_FX_LOAD
+    __syncthreads();
+    long long *__restrict__ dst = part + (long long)blockIdx.x * kFxPanel;
+    for (int i = tid; i < kFxPanel; i += kFxThreads) dst[i] = (long long)fx_sums[i];
+}
+
+// out[i] = (sum over the slices of i's panel) * 2^-e
+__global__ __launch_bounds__(256) void fx_finish_kernel(const long long *__restrict__ part,
+                                                        const long long *__restrict__ cstart, int P, long long out_len,
+                                                        const unsigned *__restrict__ slots, int e_slot,
+                                                        float *__restrict__ out) {
+    const long long i = blockIdx.x * 256LL + threadIdx.x;      // 256 divides the panel: a block is in one panel
+    if (i >= out_len) return;
+    const int p = (int)(i / kFxPanel);
+    const int o = (int)(i - (long long)p * kFxPanel);
+    long long c0 = cstart[p], c1 = cstart[p < P ? p + 1 : p];
+    long long s = 0;
+    for (long long c = c0; c < c1; ++c) s += part[c * kFxPanel + o];
+    out[i] = (float)ldexp((double)s, -(int)slots[e_slot]);
+}
+
+hipError_t fx_build_pass(const FxPass &ps, const long long *ptr, long long M, const int *idx, const float *val,
+                         long long nnz, long long *cnt, long long *bsum, hipStream_t st) {
+    hipError_t e;
+    const long long ntiles = ps.ntiles;
+    const unsigned tb = (unsigned)((ntiles + 3) / 4);
+    hipLaunchKernelGGL(fx_hist_kernel, dim3(tb), dim3(256), 0, st, idx, nnz, ntiles, ps.P, cnt);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const long long n = (long long)ps.P * ntiles;
+    const long long nb = (n + kScanBlock - 1) / kScanBlock;
+    hipLaunchKernelGGL(fx_scan_block_kernel, dim3((unsigned)nb), dim3(256), 0, st, cnt, n, bsum);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_scan_tops_kernel, dim3(1), dim3(64), 0, st, nb, bsum);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_scan_add_kernel, dim3((unsigned)((n + 1 + 255) / 256)), dim3(256), 0, st, n, bsum, nb, cnt);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_pstart_kernel, dim3(1), dim3(64), 0, st, cnt, ntiles, ps.P, ps.chunk, ps.pstart, ps.cstart);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_scatter_kernel, dim3(tb), dim3(256), 0, st, ptr, M, idx, val, nnz, ntiles, ps.P, cnt, ps.gidx,
+                       ps.loc, ps.val);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Which passes take this path, with how many panels and blocks per panel.  A function of the
+// shape alone.
+void sparse_fx_plan(long long N, long long D, long long nnz, FxPass *row, FxPass *col) {
+    FxPass *ps[2] = {row, col};
+    const long long out_len[2] = {N, D};
+    for (int i = 0; i < 2; ++i) {
+        FxPass &f = *ps[i];
+        f = FxPass{};
+        f.out_len = out_len[i];
+        const long long P = (out_len[i] + kFxPanel - 1) / kFxPanel;
+        f.on = nnz >= kFxMinEntries && P <= kFxMaxPanels;
+        if (!f.on) continue;
+        f.P = (int)P;
+        // about a thousand blocks in all (four per compute unit), whatever the sizes of the panels
+        long long chunk = ((nnz + 1023) / 1024 + 4095) / 4096 * 4096;
+        f.chunk = chunk < 32768 ? 32768 : chunk;
+        f.max_chunks = (nnz + f.chunk - 1) / f.chunk + P;
+        f.ntiles = (nnz + kFxTile - 1) / kFxTile;
+    }
+}
+
+// Once per matrix: both layouts, the largest |value| and the longest row and column.
+hipError_t launch_sparse_fx_build(const SparseArgs &a, const SparseFx &fx, hipStream_t st) {
+    hipError_t e;
+    hipLaunchKernelGGL(fx_set_slots_kernel, dim3(1), dim3(64), 0, st, fx.slots, 0, kFxSlots);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_absmax_kernel, dim3(1024), dim3(256), 0, st, a.row_val, a.nnz, fx.slots + kFxSlotMaxVal);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_maxlen_kernel, dim3(1024), dim3(256), 0, st, a.row_ptr, a.N, fx.slots + kFxSlotLenRow);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_maxlen_kernel, dim3(1024), dim3(256), 0, st, a.col_ptr, a.D, fx.slots + kFxSlotLenCol);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    // row pass: outputs are rows, source is the column layout (columns ascend inside a panel)
+    if (fx.row.on &&
+        (e = fx_build_pass(fx.row, a.col_ptr, a.D, a.row_idx, a.col_val, a.nnz, fx.cnt, fx.bsum, st)) != hipSuccess)
+        return e;
+    // column pass: outputs are columns, source is the row layout
+    if (fx.col.on &&
+        (e = fx_build_pass(fx.col, a.row_ptr, a.N, a.col_idx, a.row_val, a.nnz, fx.cnt, fx.bsum, st)) != hipSuccess)
+        return e;
+    return hipSuccess;
+}
+
+// At the start of every call: the largest |w| of the entering iterate, no residuals yet.
+hipError_t launch_sparse_fx_begin(const SparseArgs &a, const SparseFx &fx, hipStream_t st) {
+    hipError_t e;
+    hipLaunchKernelGGL(fx_set_slots_kernel, dim3(1), dim3(64), 0, st, fx.slots, kFxSlotMaxW, 2);   // max|w|, max|r|
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_absmax_kernel, dim3(256), dim3(256), 0, st, a.w, a.D, fx.slots + kFxSlotMaxW);
+    return hipGetLastError();
+}
+
+// z = X w (row = true, into out [N]) or s = X^T r (row = false, into out [D])
+hipError_t launch_sparse_fx_pass(const SparseFx &fx, bool row, const float *vec, long long vec_len, long long nnz,
+                                 float *out, hipStream_t st) {
+    const FxPass &ps = row ? fx.row : fx.col;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fx_pass_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kFxPanel * 8);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_pass_kernel, dim3((unsigned)ps.max_chunks), dim3(kFxThreads), kFxPanel * 8, st, ps.gidx, ps.loc,
+                       ps.val, vec, vec_len, nnz, ps.pstart, ps.cstart, ps.P, ps.chunk, fx.slots,
+                       row ? kFxSlotMaxW : kFxSlotMaxR, row ? kFxSlotLenRow : kFxSlotLenCol,
+                       row ? kFxSlotERow : kFxSlotECol, ps.part);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_finish_kernel, dim3((unsigned)((ps.out_len + 255) / 256)), dim3(256), 0, st, ps.part, ps.cstart,
+                       ps.P, ps.out_len, fx.slots, row ? kFxSlotERow : kFxSlotECol, out);
+    return hipGetLastError();
+}
+
+}  // namespace slaqglm

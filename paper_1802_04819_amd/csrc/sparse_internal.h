@@ -32,4 +32,39 @@ hipError_t launch_sparse_panel_build(const SparseArgs &a, const SparsePanels &pn
 hipError_t launch_sparse_iteration_panels(const SparseArgs &a, const SparsePanels &pn, int k, hipEvent_t *ev,
                                           hipStream_t st);
 
+// ---- scatter into LDS with fixed-point sums (glm_sparse_fx.hip) --------------------------------
+constexpr int kFxPanel = 16384;              // outputs per panel: their 64-bit sums fill 128 KB of LDS
+constexpr int kFxMaxPanels = 256;            // bins of the split that builds the layout
+constexpr long long kFxMinEntries = 1LL << 22;
+// device scalars of the path (unsigned [kFxSlots])
+enum : int { kFxSlotMaxW = 0, kFxSlotMaxR = 1, kFxSlotMaxVal = 2, kFxSlotERow = 3, kFxSlotECol = 4, kFxSlotLenRow = 5,
+             kFxSlotLenCol = 6, kFxSlots = 8 };
+struct FxPass {
+    int on;                  // this pass takes the path
+    int P;                   // panels
+    long long chunk;         // entries per block: a panel of n entries is shared by ceil(n / chunk) blocks
+    long long max_chunks;    // upper bound of the number of blocks, known from the shape alone
+    long long out_len;       // N for the row pass, D for the column pass
+    long long ntiles;        // tiles of the split
+    int *gidx;               // [nnz] index into the gathered vector
+    unsigned short *loc;     // [nnz] output index inside its panel
+    float *val;              // [nnz]
+    long long *pstart;       // [P + 1] first entry of each panel
+    long long *cstart;       // [P + 1] first block of each panel
+    long long *part;         // [max_chunks, kFxPanel] fixed-point partial sums, one slice per block
+};
+struct SparseFx {
+    FxPass row, col;
+    unsigned *slots;         // [kFxSlots]
+    long long *cnt;          // [max(P) * ntiles + 1] split counters
+    long long *bsum;         // block totals of their prefix sum
+};
+void sparse_fx_plan(long long N, long long D, long long nnz, FxPass *row, FxPass *col);
+hipError_t launch_sparse_fx_build(const SparseArgs &a, const SparseFx &fx, hipStream_t st);
+hipError_t launch_sparse_fx_begin(const SparseArgs &a, const SparseFx &fx, hipStream_t st);
+hipError_t launch_sparse_fx_pass(const SparseFx &fx, bool row, const float *vec, long long vec_len, long long nnz,
+                                 float *out, hipStream_t st);
+hipError_t launch_sparse_iteration_any(const SparseArgs &a, const SparsePanels &pn, const SparseFx &fx, int k,
+                                       hipEvent_t *ev, hipStream_t st);
+
 }  // namespace slaqglm

@@ -287,3 +287,57 @@ def test_prepared_flag_is_only_believed_for_the_workspace_it_was_set_on():
     with pytest.raises(glm.GlmError) as e:
         glm.glm_step_sparse(jc, 0, fresh)
     assert e.value.status == glm.GLM_EINVAL
+
+
+# ---- products by scatter into LDS with fixed-point sums (at least 2^22 stored entries) ----------
+
+@pytest.mark.parametrize("loss,N,D,mean", [(synth.LOGISTIC, 300_000, 200_000, 20.0), (synth.SQUARED, 250_000, 70_000, 18.0),
+                                           (synth.HINGE, 1_500_000, 300, 3.2)])
+def test_scatter_path_each_step_matches_oracle(loss, N, D, mean):
+    _say(f"[case] sparse, fixed-point scatter path: loss {loss}, {N} x {D}, about {mean} entries per row")
+    eta = {synth.LOGISTIC: 0.5, synth.HINGE: 0.05, synth.SQUARED: 0.05}[loss]
+    p = synth.make_sparse_glm(loss, N, D, mean, seed=41, lam=1e-4, eta=eta, K=3)
+    assert p.col_idx.numel() >= (1 << 22)
+    job = _job_from_problem(p)
+    _check_steps(job, (p.row_ptr.numpy(), p.col_idx.numpy(), p.row_val.numpy()), p.y.numpy(), D, loss, p.lam, eta, 3,
+                 "scatter")
+    assert job.c.prepared == 1
+
+
+def test_scatter_path_reruns_split_calls_and_duplicates():
+    _say("[case] sparse, fixed-point scatter path: duplicates, empty rows and columns, reruns and 2 + 3 = 5, bit for bit")
+    rng = np.random.default_rng(42)
+    N, D, nnz = 120_000, 50_000, 5_000_000
+    rows = rng.integers(0, N - 500, size=nnz); cols = rng.integers(100, D, size=nnz)      # rows / columns left empty
+    rows[:1000] = 7; cols[:1000] = 123                                                    # a thousand duplicates
+    vals = (rng.standard_normal(nnz) * np.exp(rng.uniform(-6, 6, size=nnz))).astype(np.float32)   # 5 decades of sizes
+    coo = sp.coo_matrix((vals, (rows, cols)), shape=(N, D))
+    # CSR with the duplicates kept (scipy would add them up)
+    order = np.lexsort((cols, rows))
+    rp = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=N))]).astype(np.int64)
+    ci = cols[order].astype(np.int32); rv = vals[order]
+    corder = np.argsort(ci, kind="stable")
+    cp = np.concatenate([[0], np.cumsum(np.bincount(ci, minlength=D))]).astype(np.int64)
+    ri = np.repeat(np.arange(N, dtype=np.int32), np.diff(rp))[corder]
+    y = _labels(synth.SQUARED, N, rng)
+    T = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def job():
+        return glm.SparseJob(T(rp), T(ci), T(rv), T(cp), T(ri), T(rv[corder]), T(y), torch.zeros(D, device="cuda"),
+                             synth.SQUARED, 1e-4, 1e-6, 5)
+    outs = []
+    for split in ((5,), (5,), (2, 3)):
+        jb = job()
+        ws = glm.alloc_sparse_workspace(jb)
+        for n in split:
+            glm.glm_step_sparse(jb, n, ws)
+        torch.cuda.synchronize()
+        assert jb.c.prepared == 1
+        outs.append((jb.history().cpu().clone(), jb.w.cpu().clone(), jb.grad.cpu().clone()))
+    for o in outs[1:]:
+        for x, z in zip(outs[0], o):
+            assert torch.equal(x, z)
+    # and the numbers are the oracle's
+    jb = job()
+    _check_steps(jb, (rp, ci, rv), y, D, synth.SQUARED, 1e-4, 1e-6, 2, "scatter duplicates")
+    del coo
