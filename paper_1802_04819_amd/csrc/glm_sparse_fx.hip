@@ -34,7 +34,7 @@ namespace {
 
 constexpr int kFxTile = 2048;            // entries per tile of the split (one wave, 32 steps of 64)
 constexpr int kFxThreads = 1024;
-constexpr int kFxUnroll = 4;
+constexpr int kFxUnroll = 2;             // rounds of four entries per lane in flight
 
 // ------------------------------------------------------------------ building the layout
 
@@ -103,18 +103,29 @@ __global__ __launch_bounds__(256) void fx_scan_add_kernel(long long n, const lon
     if (s == n) a[n] = bsum[nb];
 }
 
-// pstart[p] = first entry of panel p (p == P: the total, stored at cnt[P * ntiles]);
-// cstart[p] = first block of panel p when every block takes `chunk` entries.  One thread: P <= 256.
+// One thread (P <= 256): pstart[p] = first entry of panel p in the padded layout (every panel
+// starts at a multiple of four and is filled up to one with zero entries), shift[p] = how far its
+// entries move up for that, cstart[p] = first block of panel p when every block takes `chunk`
+// entries.  cnt[p * ntiles] is the exact start of panel p (p == P: the total).
 __global__ void fx_pstart_kernel(const long long *__restrict__ cnt, long long ntiles, int P, long long chunk,
-                                 long long *__restrict__ pstart, long long *__restrict__ cstart) {
+                                 long long *__restrict__ pstart, long long *__restrict__ shift,
+                                 long long *__restrict__ cstart, int *__restrict__ gidx,
+                                 unsigned short *__restrict__ loc, float *__restrict__ val) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    long long blocks = 0;
-    for (int p = 0; p <= P; ++p) {
+    long long blocks = 0, at = 0;
+    for (int p = 0; p < P; ++p) {
         const long long s = cnt[(long long)p * ntiles];
-        pstart[p] = s;
+        const long long len = cnt[(long long)(p + 1) * ntiles] - s;
+        const long long padded = (len + 3) & ~3LL;
+        pstart[p] = at;
+        shift[p] = at - s;
         cstart[p] = blocks;
-        if (p < P) blocks += (cnt[(long long)(p + 1) * ntiles] - s + chunk - 1) / chunk;
+        for (long long q = len; q < padded; ++q) { gidx[at + q] = 0; loc[at + q] = 0; val[at + q] = 0.0f; }
+        at += padded;
+        blocks += (padded + chunk - 1) / chunk;
     }
+    pstart[P] = at;
+    cstart[P] = blocks;
 }
 
 // largest m in [lo, hi] with ptr[m] <= e  (ptr[lo] <= e is given)
@@ -132,13 +143,14 @@ __device__ __forceinline__ long long fx_owner(const long long *__restrict__ ptr,
 __global__ __launch_bounds__(256) void fx_scatter_kernel(const long long *__restrict__ ptr, long long M,
                                                          const int *__restrict__ idx, const float *__restrict__ val,
                                                          long long nnz, long long ntiles, int P,
-                                                         const long long *__restrict__ cnt, int *__restrict__ gidx,
+                                                         const long long *__restrict__ cnt,
+                                                         const long long *__restrict__ shift, int *__restrict__ gidx,
                                                          unsigned short *__restrict__ loc, float *__restrict__ valo) {
     __shared__ long long cur[4][kFxMaxPanels];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long tile = blockIdx.x * 4LL + wave;
     if (tile < ntiles)
-        for (int k = lane; k < P; k += 64) cur[wave][k] = cnt[(long long)k * ntiles + tile];
+        for (int k = lane; k < P; k += 64) cur[wave][k] = cnt[(long long)k * ntiles + tile] + shift[k];
     __syncthreads();
     if (tile >= ntiles) return;                        // whole waves leave: no block-wide barrier below
     const long long e0 = tile * kFxTile;
@@ -255,39 +267,58 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
     __syncthreads();
     const int p = s_panel;
     if (p < 0) return;                                 // uniform over the block
-    long long s0 = pstart[p], s1 = pstart[p + 1];
-    s0 = s0 < 0 ? 0 : s0 > nnz ? nnz : s0;
-    s1 = s1 < s0 ? s0 : s1 > nnz ? nnz : s1;
+    const long long cap = (nnz + 4LL * P) & ~3LL;     // the arrays hold nnz + 4 P entries
+    long long s0 = pstart[p] & ~3LL, s1 = pstart[p + 1] & ~3LL;
+    s0 = s0 < 0 ? 0 : s0 > cap ? cap : s0;
+    s1 = s1 < s0 ? s0 : s1 > cap ? cap : s1;
     const long long c = (long long)blockIdx.x - cstart[p];
     long long b0 = s0 + c * chunk, b1 = b0 + chunk;
     b0 = b0 > s1 ? s1 : b0;
     b1 = b1 > s1 ? s1 : b1;
     // Two loads stand between an entry and its sum: the entry itself, then the element of the
     // other vector it points at.  The entries of the next round are requested before the current
-    // round's elements are waited for, so that one latency is paid per round, not two.
-    int g[kFxUnroll]; unsigned l[kFxUnroll]; float v[kFxUnroll];
-#define SLAQ_FX_LOAD(E)                                                                      \
+    // round's elements are waited for, so that one latency is paid per round, not two.  A lane
+    // takes four consecutive entries with one 16-byte load per array (b0 and b1 are multiples
+    // of four: panels are padded, chunks are multiples of 4096).
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    typedef int i4 __attribute__((ext_vector_type(4)));
+    typedef unsigned short us4 __attribute__((ext_vector_type(4)));
+    const i4 *__restrict__ g4p = reinterpret_cast<const i4 *>(gidx);
+    const us4 *__restrict__ l4p = reinterpret_cast<const us4 *>(loc);
+    const f4 *__restrict__ v4p = reinterpret_cast<const f4 *>(val);
+    i4 g[kFxUnroll]; us4 l[kFxUnroll]; f4 v[kFxUnroll];
+#define SLAQ_FX_LOAD(Q)                                                                      \
     _Pragma("unroll") for (int u = 0; u < kFxUnroll; ++u) {                                  \
-        const long long eu_ = (E) + (long long)u * kFxThreads;                               \
-        const bool ok_ = eu_ < b1;                                                           \
-        /* the layout is the library's own, but it lives in the caller's workspace: keep     \
-           every index inside its array whatever the memory holds */                         \
-        g[u] = ok_ ? (int)min((unsigned)__builtin_nontemporal_load(gidx + eu_), vmax) : 0;   \
-        l[u] = ok_ ? (unsigned)__builtin_nontemporal_load(loc + eu_) & (unsigned)(kFxPanel - 1) : 0u; \
-        v[u] = ok_ ? __builtin_nontemporal_load(val + eu_) : 0.0f;                           \
+        const long long q_ = (Q) + (long long)u * kFxThreads;                                \
+        const bool ok_ = q_ < q1;                                                            \
+        g[u] = ok_ ? __builtin_nontemporal_load(g4p + q_) : i4{0, 0, 0, 0};                  \
+        l[u] = ok_ ? __builtin_nontemporal_load(l4p + q_) : us4{0, 0, 0, 0};                 \
+        v[u] = ok_ ? __builtin_nontemporal_load(v4p + q_) : f4{0.0f, 0.0f, 0.0f, 0.0f};      \
     }
+    const long long q1 = b1 >> 2;
     const long long stride = (long long)kFxThreads * kFxUnroll;
-    long long e = b0 + tid;
-    if (e < b1) SLAQ_FX_LOAD(e)
-    for (; e < b1; e += stride) {
-        float x[kFxUnroll], vv[kFxUnroll]; unsigned ll[kFxUnroll];
-#pragma unroll
-        for (int u = 0; u < kFxUnroll; ++u) { x[u] = vec[g[u]]; vv[u] = v[u]; ll[u] = l[u]; }
-        if (e + stride < b1) SLAQ_FX_LOAD(e + stride)
+    long long q = (b0 >> 2) + tid;
+    if (q < q1) SLAQ_FX_LOAD(q)
+    for (; q < q1; q += stride) {
+        f4 x[kFxUnroll], vv[kFxUnroll]; us4 ll[kFxUnroll];
 #pragma unroll
         for (int u = 0; u < kFxUnroll; ++u) {
-            const long long q = __float2ll_rn((vv[u] * x[u]) * scale);
-            if (e + (long long)u * kFxThreads < b1) atomicAdd(&fx_sums[ll[u]], (unsigned long long)q);
+            // the layout is the library's own, but it lives in the caller's workspace: keep every
+            // index inside its array whatever the memory holds
+#pragma unroll
+            for (int c = 0; c < 4; ++c) x[u][c] = vec[min((unsigned)g[u][c], vmax)];
+            vv[u] = v[u]; ll[u] = l[u];
+        }
+        if (q + stride < q1) SLAQ_FX_LOAD(q + stride)
+#pragma unroll
+        for (int u = 0; u < kFxUnroll; ++u) {
+            if (q + (long long)u * kFxThreads < q1) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const long long t = __float2ll_rn((vv[u][c] * x[u][c]) * scale);
+                    atomicAdd(&fx_sums[(unsigned)ll[u][c] & (unsigned)(kFxPanel - 1)], (unsigned long long)t);
+                }
+            }
         }
     }
 #undef SLAQ_FX_LOAD
@@ -326,10 +357,11 @@ hipError_t fx_build_pass(const FxPass &ps, const long long *ptr, long long M, co
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(fx_scan_add_kernel, dim3((unsigned)((n + 1 + 255) / 256)), dim3(256), 0, st, n, bsum, nb, cnt);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_pstart_kernel, dim3(1), dim3(64), 0, st, cnt, ntiles, ps.P, ps.chunk, ps.pstart, ps.cstart);
+    hipLaunchKernelGGL(fx_pstart_kernel, dim3(1), dim3(64), 0, st, cnt, ntiles, ps.P, ps.chunk, ps.pstart, ps.shift,
+                       ps.cstart, ps.gidx, ps.loc, ps.val);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_scatter_kernel, dim3(tb), dim3(256), 0, st, ptr, M, idx, val, nnz, ntiles, ps.P, cnt, ps.gidx,
-                       ps.loc, ps.val);
+    hipLaunchKernelGGL(fx_scatter_kernel, dim3(tb), dim3(256), 0, st, ptr, M, idx, val, nnz, ntiles, ps.P, cnt, ps.shift,
+                       ps.gidx, ps.loc, ps.val);
     return hipGetLastError();
 }
 
@@ -351,7 +383,7 @@ void sparse_fx_plan(long long N, long long D, long long nnz, FxPass *row, FxPass
         // about a thousand blocks in all (four per compute unit), whatever the sizes of the panels
         long long chunk = ((nnz + 1023) / 1024 + 4095) / 4096 * 4096;
         f.chunk = chunk < 32768 ? 32768 : chunk;
-        f.max_chunks = (nnz + f.chunk - 1) / f.chunk + P;
+        f.max_chunks = (nnz + f.chunk - 1) / f.chunk + P + 1;      // panels are padded by up to three entries each
         f.ntiles = (nnz + kFxTile - 1) / kFxTile;
     }
 }

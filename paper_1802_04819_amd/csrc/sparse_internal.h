@@ -46,10 +46,12 @@ struct FxPass {
     long long max_chunks;    // upper bound of the number of blocks, known from the shape alone
     long long out_len;       // N for the row pass, D for the column pass
     long long ntiles;        // tiles of the split
-    int *gidx;               // [nnz] index into the gathered vector
-    unsigned short *loc;     // [nnz] output index inside its panel
-    float *val;              // [nnz]
+    int *gidx;               // [nnz + 4 P] index into the gathered vector
+    unsigned short *loc;     // [nnz + 4 P] output index inside its panel
+    float *val;              // [nnz + 4 P]; every panel starts at a multiple of four entries and is
+                             //   filled up to one with zero entries, so that lanes load four at a time
     long long *pstart;       // [P + 1] first entry of each panel
+    long long *shift;        // [P] how far the panel's entries moved up for that alignment
     long long *cstart;       // [P + 1] first block of each panel
     long long *part;         // [max_chunks, kFxPanel] fixed-point partial sums, one slice per block
 };
