@@ -205,17 +205,25 @@ __global__ void fill_zero_kernel(float *__restrict__ p, long long n) {
 // non-negative floats order as unsigned integers; the maximum does not depend on the order), and
 // block 0 clears *zeroslot, which the next kernel but one accumulates into.  Both may be null.
 __device__ __forceinline__ void block_absmax(float v, unsigned *__restrict__ maxslot, unsigned *__restrict__ zeroslot) {
-    __shared__ unsigned redm[256];
+    __shared__ unsigned redm[4];
     if (maxslot) {
-        redm[threadIdx.x] = __float_as_uint(v) & 0x7FFFFFFFu;
+        unsigned m = __float_as_uint(v) & 0x7FFFFFFFu;
+        for (int o = 32; o >= 1; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o, 64));
+        if ((threadIdx.x & 63) == 0) redm[threadIdx.x >> 6] = m;
         __syncthreads();
-        for (int s = 128; s >= 1; s >>= 1) {
-            if (threadIdx.x < s) redm[threadIdx.x] = max(redm[threadIdx.x], redm[threadIdx.x + s]);
-            __syncthreads();
-        }
-        if (threadIdx.x == 0) atomicMax(maxslot, redm[0]);
+        if (threadIdx.x == 0) atomicMax(maxslot, max(max(redm[0], redm[1]), max(redm[2], redm[3])));
     }
     if (zeroslot && blockIdx.x == 0 && threadIdx.x == 0) *zeroslot = 0u;
+}
+
+// Sum over the 256 threads of a block in a fixed order: a butterfly inside each wave, then the
+// four waves in order.  Valid in thread 0.
+template <typename T>
+__device__ __forceinline__ T block_sum_256(T v, T *red4) {
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    if ((threadIdx.x & 63) == 0) red4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return ((red4[0] + red4[1]) + red4[2]) + red4[3];
 }
 
 // Rows: margins -> loss and residual; per-block loss sums in a fixed tree.
@@ -223,7 +231,7 @@ __global__ __launch_bounds__(256) void sparse_row_epilogue(const float *__restri
                                                            long long N, int loss, float *__restrict__ r,
                                                            float *__restrict__ lossP, unsigned *__restrict__ maxslot,
                                                            unsigned *__restrict__ zeroslot) {
-    __shared__ float red[256];
+    __shared__ float red[4];
     const long long i = blockIdx.x * 256LL + threadIdx.x;
     float l = 0.0f, rmag = 0.0f;
     if (i < N) {
@@ -233,13 +241,8 @@ __global__ __launch_bounds__(256) void sparse_row_epilogue(const float *__restri
         rmag = rr;
     }
     block_absmax(rmag, maxslot, zeroslot);
-    red[threadIdx.x] = l;
-    __syncthreads();
-    for (int s = 128; s >= 1; s >>= 1) {
-        if (threadIdx.x < s) red[threadIdx.x] = red[threadIdx.x] + red[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) lossP[blockIdx.x] = red[0];
+    const float tot = block_sum_256(l, red);
+    if (threadIdx.x == 0) lossP[blockIdx.x] = tot;
 }
 
 // Columns: X^T r -> gradient, update; per-block sums of w^2 (entering iterate) in a fixed tree.
@@ -248,7 +251,7 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue(const float *__restri
                                                            float *__restrict__ grad, double *__restrict__ wwP,
                                                            unsigned *__restrict__ maxslot,
                                                            unsigned *__restrict__ zeroslot) {
-    __shared__ double red[256];
+    __shared__ double red[4];
     const long long j = blockIdx.x * 256LL + threadIdx.x;
     double ww = 0.0;
     float wnew = 0.0f;
@@ -261,13 +264,8 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue(const float *__restri
         if (step != 0.0) { wnew = (float)((double)wj - step * g); w[j] = wnew; }
     }
     block_absmax(wnew, maxslot, zeroslot);
-    red[threadIdx.x] = ww;
-    __syncthreads();
-    for (int s = 128; s >= 1; s >>= 1) {
-        if (threadIdx.x < s) red[threadIdx.x] = red[threadIdx.x] + red[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) wwP[blockIdx.x] = red[0];
+    const double tot = block_sum_256(ww, red);
+    if (threadIdx.x == 0) wwP[blockIdx.x] = tot;
 }
 
 // loss_out = (sum lossP) / N + lambda / 2 * (sum wwP); thread t adds a contiguous run, then a fixed tree.
@@ -452,7 +450,7 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue_panels(const float *_
                                                                   double *__restrict__ wwP,
                                                                   unsigned *__restrict__ maxslot,
                                                                   unsigned *__restrict__ zeroslot) {
-    __shared__ double red[256];
+    __shared__ double red[4];
     const long long j = blockIdx.x * 256LL + threadIdx.x;
     double ww = 0.0;
     float wnew = 0.0f;
@@ -467,13 +465,8 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue_panels(const float *_
         if (step != 0.0) { wnew = (float)((double)wj - step * g); w[j] = wnew; }
     }
     block_absmax(wnew, maxslot, zeroslot);
-    red[threadIdx.x] = ww;
-    __syncthreads();
-    for (int s = 128; s >= 1; s >>= 1) {
-        if (threadIdx.x < s) red[threadIdx.x] = red[threadIdx.x] + red[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) wwP[blockIdx.x] = red[0];
+    const double tot = block_sum_256(ww, red);
+    if (threadIdx.x == 0) wwP[blockIdx.x] = tot;
 }
 
 hipError_t launch_sparse_sorted_check(const SparseArgs &a, const SparsePanels &pn, hipStream_t st) {

@@ -327,19 +327,28 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
     for (int i = tid; i < kFxPanel; i += kFxThreads) dst[i] = (long long)fx_sums[i];
 }
 
-// out[i] = (sum over the slices of i's panel) * 2^-e
+// out[i] = (sum over the slices of i's panel) * 2^-e.  A block takes 32 outputs; its eight
+// groups of 32 lanes share the slices (a popular panel has hundreds), integer sums in any order.
 __global__ __launch_bounds__(256) void fx_finish_kernel(const long long *__restrict__ part,
                                                         const long long *__restrict__ cstart, int P, long long out_len,
                                                         const unsigned *__restrict__ slots, int e_slot,
                                                         float *__restrict__ out) {
-    const long long i = blockIdx.x * 256LL + threadIdx.x;      // 256 divides the panel: a block is in one panel
-    if (i >= out_len) return;
-    const int p = (int)(i / kFxPanel);
-    const int o = (int)(i - (long long)p * kFxPanel);
-    long long c0 = cstart[p], c1 = cstart[p < P ? p + 1 : p];
+    __shared__ long long red[8][32];
+    const int o32 = threadIdx.x & 31, sl = threadIdx.x >> 5;
+    const long long i = blockIdx.x * 32LL + o32;               // 32 divides the panel: a block is in one panel
     long long s = 0;
-    for (long long c = c0; c < c1; ++c) s += part[c * kFxPanel + o];
-    out[i] = (float)ldexp((double)s, -(int)slots[e_slot]);
+    if (i < out_len) {
+        const int p = (int)(i / kFxPanel);
+        const int o = (int)(i - (long long)p * kFxPanel);
+        const long long c0 = cstart[p], c1 = cstart[p < P ? p + 1 : p];
+        for (long long c = c0 + sl; c < c1; c += 8) s += part[c * kFxPanel + o];
+    }
+    red[sl][o32] = s;
+    __syncthreads();
+    if (sl == 0 && i < out_len) {
+        for (int q = 1; q < 8; ++q) s += red[q][o32];
+        out[i] = (float)ldexp((double)s, -(int)slots[e_slot]);
+    }
 }
 
 hipError_t fx_build_pass(const FxPass &ps, const long long *ptr, long long M, const int *idx, const float *val,
@@ -431,7 +440,7 @@ hipError_t launch_sparse_fx_pass(const SparseFx &fx, bool row, const float *vec,
                        row ? kFxSlotMaxW : kFxSlotMaxR, row ? kFxSlotLenRow : kFxSlotLenCol,
                        row ? kFxSlotERow : kFxSlotECol, ps.part);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_finish_kernel, dim3((unsigned)((ps.out_len + 255) / 256)), dim3(256), 0, st, ps.part, ps.cstart,
+    hipLaunchKernelGGL(fx_finish_kernel, dim3((unsigned)((ps.out_len + 31) / 32)), dim3(256), 0, st, ps.part, ps.cstart,
                        ps.P, ps.out_len, fx.slots, row ? kFxSlotERow : kFxSlotECol, out);
     return hipGetLastError();
 }
