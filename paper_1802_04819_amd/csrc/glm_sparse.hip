@@ -201,6 +201,8 @@ __global__ void fill_zero_kernel(float *__restrict__ p, long long n) {
     if (i < n) p[i] = 0.0f;
 }
 
+constexpr int kEpi = 8;                    // elements per thread of the epilogues
+
 // For the fixed-point passes: the largest |v| of the block goes into *maxslot (bit patterns of
 // non-negative floats order as unsigned integers; the maximum does not depend on the order), and
 // block 0 clears *zeroslot, which the next kernel but one accumulates into.  Both may be null.
@@ -232,13 +234,19 @@ __global__ __launch_bounds__(256) void sparse_row_epilogue(const float *__restri
                                                            float *__restrict__ lossP, unsigned *__restrict__ maxslot,
                                                            unsigned *__restrict__ zeroslot) {
     __shared__ float red[4];
-    const long long i = blockIdx.x * 256LL + threadIdx.x;
+    // kEpi elements per thread, 256 apart: blocks of one element per thread are so short that
+    // the kernel runs at the rate blocks can be started
     float l = 0.0f, rmag = 0.0f;
-    if (i < N) {
-        float rr;
-        loss_residual(loss, z[i], y[i], l, rr);
-        r[i] = rr;
-        rmag = rr;
+#pragma unroll
+    for (int q = 0; q < kEpi; ++q) {
+        const long long i = ((long long)blockIdx.x * kEpi + q) * 256 + threadIdx.x;
+        if (i < N) {
+            float lq, rr;
+            loss_residual(loss, z[i], y[i], lq, rr);
+            r[i] = rr;
+            l += lq;
+            rmag = __builtin_fmaxf(rmag, __builtin_fabsf(rr));
+        }
     }
     block_absmax(rmag, maxslot, zeroslot);
     const float tot = block_sum_256(l, red);
@@ -252,18 +260,22 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue(const float *__restri
                                                            unsigned *__restrict__ maxslot,
                                                            unsigned *__restrict__ zeroslot) {
     __shared__ double red[4];
-    const long long j = blockIdx.x * 256LL + threadIdx.x;
     double ww = 0.0;
-    float wnew = 0.0f;
-    if (j < D) {
-        const float wj = w[j];
-        const double g = (double)gs[j] * invN + (double)lambda * (double)wj;
-        grad[j] = (float)g;
-        ww = (double)wj * (double)wj;
-        wnew = wj;
-        if (step != 0.0) { wnew = (float)((double)wj - step * g); w[j] = wnew; }
+    float wmag = 0.0f;
+#pragma unroll
+    for (int q = 0; q < kEpi; ++q) {
+        const long long j = ((long long)blockIdx.x * kEpi + q) * 256 + threadIdx.x;
+        if (j < D) {
+            const float wj = w[j];
+            const double g = (double)gs[j] * invN + (double)lambda * (double)wj;
+            grad[j] = (float)g;
+            ww += (double)wj * (double)wj;
+            float wnew = wj;
+            if (step != 0.0) { wnew = (float)((double)wj - step * g); w[j] = wnew; }
+            wmag = __builtin_fmaxf(wmag, __builtin_fabsf(wnew));
+        }
     }
-    block_absmax(wnew, maxslot, zeroslot);
+    block_absmax(wmag, maxslot, zeroslot);
     const double tot = block_sum_256(ww, red);
     if (threadIdx.x == 0) wwP[blockIdx.x] = tot;
 }
@@ -326,7 +338,7 @@ hipError_t launch_sparse_iteration(const SparseArgs &a, int k, hipEvent_t *ev, h
     if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
     if ((e = seg_pass(a.row_ptr, a.col_idx, a.row_val, a.w, a.N, a.nnz, a.nch, a.seg0R, a.z, rec, st)) != hipSuccess)
         return e;
-    const unsigned nbR = (unsigned)((a.N + 255) / 256), nbC = (unsigned)((a.D + 255) / 256);
+    const unsigned nbR = (unsigned)((a.N + 256 * kEpi - 1) / (256 * kEpi)), nbC = (unsigned)((a.D + 256 * kEpi - 1) / (256 * kEpi));
     hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP, nullptr, nullptr);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = seg_pass(a.col_ptr, a.row_idx, a.col_val, a.r, a.D, a.nnz, a.nch, a.seg0C, a.gs, rec, st)) != hipSuccess)
@@ -451,20 +463,24 @@ __global__ __launch_bounds__(256) void sparse_col_epilogue_panels(const float *_
                                                                   unsigned *__restrict__ maxslot,
                                                                   unsigned *__restrict__ zeroslot) {
     __shared__ double red[4];
-    const long long j = blockIdx.x * 256LL + threadIdx.x;
     double ww = 0.0;
-    float wnew = 0.0f;
-    if (j < D) {
-        double s = 0.0;
-        for (int p = 0; p < P; ++p) s += (double)gs2[(size_t)p * D + j];
-        const float wj = w[j];
-        const double g = s * invN + (double)lambda * (double)wj;
-        grad[j] = (float)g;
-        ww = (double)wj * (double)wj;
-        wnew = wj;
-        if (step != 0.0) { wnew = (float)((double)wj - step * g); w[j] = wnew; }
+    float wmag = 0.0f;
+#pragma unroll
+    for (int q = 0; q < kEpi; ++q) {
+        const long long j = ((long long)blockIdx.x * kEpi + q) * 256 + threadIdx.x;
+        if (j < D) {
+            double s = 0.0;
+            for (int p = 0; p < P; ++p) s += (double)gs2[(size_t)p * D + j];
+            const float wj = w[j];
+            const double g = s * invN + (double)lambda * (double)wj;
+            grad[j] = (float)g;
+            ww += (double)wj * (double)wj;
+            float wnew = wj;
+            if (step != 0.0) { wnew = (float)((double)wj - step * g); w[j] = wnew; }
+            wmag = __builtin_fmaxf(wmag, __builtin_fabsf(wnew));
+        }
     }
-    block_absmax(wnew, maxslot, zeroslot);
+    block_absmax(wmag, maxslot, zeroslot);
     const double tot = block_sum_256(ww, red);
     if (threadIdx.x == 0) wwP[blockIdx.x] = tot;
 }
@@ -515,7 +531,7 @@ hipError_t launch_sparse_iteration_panels(const SparseArgs &a, const SparsePanel
     if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
     if ((e = seg_pass(a.row_ptr, a.col_idx, a.row_val, a.w, a.N, a.nnz, a.nch, a.seg0R, a.z, rec, st)) != hipSuccess)
         return e;
-    const unsigned nbR = (unsigned)((a.N + 255) / 256), nbC = (unsigned)((a.D + 255) / 256);
+    const unsigned nbR = (unsigned)((a.N + 256 * kEpi - 1) / (256 * kEpi)), nbC = (unsigned)((a.D + 256 * kEpi - 1) / (256 * kEpi));
     hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP, nullptr, nullptr);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = seg_pass(pn.ptr2, pn.idx2, pn.val2, a.r, S2, a.nnz, a.nch, pn.seg0, pn.gs2, rec, st)) != hipSuccess)
@@ -553,7 +569,7 @@ hipError_t launch_sparse_iteration_any(const SparseArgs &a, const SparsePanels &
     if (fx.row.on) e = launch_sparse_fx_pass(fx, true, a.w, a.D, a.nnz, a.z, st);
     else e = seg_pass(a.row_ptr, a.col_idx, a.row_val, a.w, a.N, a.nnz, a.nch, a.seg0R, a.z, rec, st);
     if (e != hipSuccess) return e;
-    const unsigned nbR = (unsigned)((a.N + 255) / 256), nbC = (unsigned)((a.D + 255) / 256);
+    const unsigned nbR = (unsigned)((a.N + 256 * kEpi - 1) / (256 * kEpi)), nbC = (unsigned)((a.D + 256 * kEpi - 1) / (256 * kEpi));
     // max |r| feeds the column pass's scale; max |w| is cleared here and refilled by the column epilogue
     hipLaunchKernelGGL(sparse_row_epilogue, dim3(nbR), dim3(256), 0, st, a.z, a.y, a.N, a.loss, a.r, a.lossP,
                        fx.col.on ? fx.slots + kFxSlotMaxR : nullptr, fx.row.on ? fx.slots + kFxSlotMaxW : nullptr);

@@ -327,26 +327,45 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
     for (int i = tid; i < kFxPanel; i += kFxThreads) dst[i] = (long long)fx_sums[i];
 }
 
-// out[i] = (sum over the slices of i's panel) * 2^-e.  A block takes 32 outputs; its eight
-// groups of 32 lanes share the slices (a popular panel has hundreds), integer sums in any order.
+// out[i] = (sum over the slices of i's panel) * 2^-e.  A block takes 256 outputs, 32 at a time;
+// its eight groups of 32 lanes share the slices (a popular panel has hundreds), integer sums in
+// any order.
 __global__ __launch_bounds__(256) void fx_finish_kernel(const long long *__restrict__ part,
                                                         const long long *__restrict__ cstart, int P, long long out_len,
                                                         const unsigned *__restrict__ slots, int e_slot,
                                                         float *__restrict__ out) {
-    __shared__ long long red[8][32];
+    __shared__ long long red[8][8][32];
     const int o32 = threadIdx.x & 31, sl = threadIdx.x >> 5;
-    const long long i = blockIdx.x * 32LL + o32;               // 32 divides the panel: a block is in one panel
-    long long s = 0;
-    if (i < out_len) {
-        const int p = (int)(i / kFxPanel);
+    const long long base = blockIdx.x * 256LL;                 // 256 divides the panel: a block is in one panel
+    if (base >= out_len) return;
+    const int p = (int)(base / kFxPanel);
+    const long long c0 = cstart[p], c1 = cstart[p < P ? p + 1 : p];
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        const long long i = base + g * 32 + o32;
         const int o = (int)(i - (long long)p * kFxPanel);
-        const long long c0 = cstart[p], c1 = cstart[p < P ? p + 1 : p];
-        for (long long c = c0 + sl; c < c1; c += 8) s += part[c * kFxPanel + o];
+        long long s = 0;
+        if (i < out_len) {
+            // four independent loads in flight per lane
+            long long s1 = 0, s2 = 0, s3 = 0, c = c0 + sl;
+            for (; c + 24 < c1; c += 32) {
+                s += part[c * kFxPanel + o];
+                s1 += part[(c + 8) * kFxPanel + o];
+                s2 += part[(c + 16) * kFxPanel + o];
+                s3 += part[(c + 24) * kFxPanel + o];
+            }
+            for (; c < c1; c += 8) s += part[c * kFxPanel + o];
+            s += (s1 + s2) + s3;
+        }
+        red[g][sl][o32] = s;
     }
-    red[sl][o32] = s;
     __syncthreads();
-    if (sl == 0 && i < out_len) {
-        for (int q = 1; q < 8; ++q) s += red[q][o32];
+    // thread t finishes output base + t
+    const long long i = base + threadIdx.x;
+    if (i < out_len) {
+        const int g = threadIdx.x >> 5;
+        long long s = 0;
+        for (int q = 0; q < 8; ++q) s += red[g][q][o32];
         out[i] = (float)ldexp((double)s, -(int)slots[e_slot]);
     }
 }
@@ -440,7 +459,7 @@ hipError_t launch_sparse_fx_pass(const SparseFx &fx, bool row, const float *vec,
                        row ? kFxSlotMaxW : kFxSlotMaxR, row ? kFxSlotLenRow : kFxSlotLenCol,
                        row ? kFxSlotERow : kFxSlotECol, ps.part);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_finish_kernel, dim3((unsigned)((ps.out_len + 31) / 32)), dim3(256), 0, st, ps.part, ps.cstart,
+    hipLaunchKernelGGL(fx_finish_kernel, dim3((unsigned)((ps.out_len + 255) / 256)), dim3(256), 0, st, ps.part, ps.cstart,
                        ps.P, ps.out_len, fx.slots, row ? kFxSlotERow : kFxSlotECol, out);
     return hipGetLastError();
 }
