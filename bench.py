@@ -484,10 +484,15 @@ def bench_sparse(args):
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": p.name, "config_index": 6, "N": N, "D": D, "nnz": p.nnz, "loss": "logistic",
                    "bytes_per_iteration": alg, "scale": args.scale},
-        "roofline": {"bound": "hbm", "kernel": "seg_sum_kernel (rows, then columns) + fix-up + row epilogue",
+        "roofline": {"bound": "hbm",
+                     "kernel": ("fx_pass_kernel (rows, then columns) + conversion + row epilogue" if job.c.prepared == 1
+                                and p.nnz >= (1 << 22) else "seg_sum_kernel (rows, then columns) + fix-up + row epilogue"),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None, "avg_launch_ms": avg_ms, "launches": len(ms),
-                     "whole_step_GBps": alg * K / sec / 1e9},
+                     "whole_step_GBps": alg * K / sec / 1e9,
+                     # the scatter layouts store 10 bytes per entry and product (value, gathered index, 16-bit
+                     # output index) against the 8 of the caller's layouts
+                     "executed_bytes_per_iteration": alg + 4.0 * p.nnz},
         "rerun_bit_identical": rerun_identical, "loss_first": float(hist[0]), "loss_last": float(hist[-1]),
     }
     if not args.no_cpu_baseline:

@@ -235,17 +235,23 @@ typedef struct {
     int32_t        schedule; /* glm_step_schedule_t, as in glm_job_t                                */
 } glm_sparse_job_t;
 
-/* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz only).  With more than 786,432
- * rows this includes room for a second copy of the column layout (8 bytes per entry). */
+/* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz only).  From 4,194,304 stored
+ * entries on this includes room for the library's own copies of the matrix (20 bytes per entry and
+ * a few hundred MB of partial sums); with more than 786,432 rows, below that, for a second copy of
+ * the column layout (8 bytes per entry). */
 int glm_sparse_workspace_bytes(const glm_sparse_job_t *job /*HOST*/, size_t *out_bytes /*HOST*/);
 
 /* `iters` gradient-descent iterations of one sparse job: the same iteration as glm_step, with
  * absent entries counting as zeros.  Reads each stored entry twice per iteration (once per
- * layout).  With more than 786,432 rows the first call (job->prepared == 0) copies the column
- * layout into the workspace ordered by panels of 524,288 rows, so that the gathers of the column
- * pass stay inside L2; this needs the rows of every column in ascending order (checked on the
- * device; otherwise the caller's layout is used as it is) and synchronises with hip_stream once.  The contents of the index arrays are trusted (they live on the device); sizes,
- * pointers and hyper-parameters are validated as in glm_step, with the same error codes. */
+ * layout).  The first call on a matrix (job->prepared == 0) may build auxiliary layouts in the
+ * workspace: from 4,194,304 stored entries on, one copy per product ordered by panels of 16384
+ * outputs, whose sums are then formed in LDS as 64-bit fixed-point integers (order-free, hence
+ * bit-identical from run to run, and finer than the fp32 products they add); below that, with more
+ * than 786,432 rows, a copy of the column layout ordered by panels of 524,288 rows, which needs the
+ * rows of every column in ascending order (checked on the device; otherwise the caller's layout is
+ * used as it is) and synchronises with hip_stream once.  The contents of the index arrays are
+ * trusted (they live on the device); sizes, pointers and hyper-parameters are validated as in
+ * glm_step, with the same error codes. */
 int glm_step_sparse(glm_sparse_job_t *job /*HOST*/, int32_t iters, void *ws /*DEVICE*/, size_t ws_bytes,
                     void *hip_stream);
 
