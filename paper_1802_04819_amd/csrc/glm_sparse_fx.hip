@@ -137,6 +137,17 @@ __device__ __forceinline__ long long fx_owner(const long long *__restrict__ ptr,
     return lo;
 }
 
+// The same, starting from a lower bound that is usually close: gallop upwards, then bisect.
+__device__ __forceinline__ long long fx_owner_from(const long long *__restrict__ ptr, long long lo, long long M,
+                                                   long long e) {
+    long long step = 1, hi = lo;
+    while (hi < M - 1) {
+        const long long nxt = hi + step < M - 1 ? hi + step : M - 1;
+        if (ptr[nxt] <= e) { lo = nxt; hi = nxt; step <<= 1; } else { hi = nxt - 1; break; }
+    }
+    return fx_owner(ptr, lo, hi < lo ? lo : hi, e);
+}
+
 // Stable split: entry e of the source layout goes to the next free place of its panel.  One wave
 // per tile, 64 entries per step in source order; inside a step the lanes with the same panel
 // are ranked by lane.
@@ -155,6 +166,7 @@ __global__ __launch_bounds__(256) void fx_scatter_kernel(const long long *__rest
     if (tile >= ntiles) return;                        // whole waves leave: no block-wide barrier below
     const long long e0 = tile * kFxTile;
     const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    long long mprev = 0;
     for (int s = 0; s < kFxTile / 64; ++s) {
         const long long eb = e0 + s * 64;
         if (eb >= nnz) break;
@@ -162,8 +174,9 @@ __global__ __launch_bounds__(256) void fx_scatter_kernel(const long long *__rest
         const bool ok = e < nnz;
         const long long elast = eb + 63 < nnz ? eb + 63 : nnz - 1;
         // owners (row of a CSR entry, column of a CSC entry): between those of the step's ends
-        const long long m0 = fx_owner(ptr, 0, M - 1, eb);
-        const long long m1 = fx_owner(ptr, m0, M - 1, elast);
+        const long long m0 = fx_owner_from(ptr, mprev, M, eb);      // owners ascend with the entries
+        const long long m1 = fx_owner_from(ptr, m0, M, elast);
+        mprev = m1;
         const long long m = ok ? fx_owner(ptr, m0, m1, e) : m0;
         const int raw = ok ? idx[e] : 0;
         const unsigned key = min((unsigned)raw >> 14, (unsigned)(P - 1));
