@@ -200,6 +200,38 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
     return hipSuccess;
 }
 
+// One job: the descriptor travels in the kernel arguments, so nothing is staged or copied and
+// the host never waits; block b of the row pass is row block b.  Same kernel bodies and the same
+// workspace slots as run_rounds, hence the same bits.
+hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st) {
+    if (iters <= 0) return hipSuccess;
+    const Layout L = make_layout(&src, 1);
+    const JobSlots &s = L.slots[0];
+    char *base = static_cast<char *>(ws);
+    DevJob d;
+    std::memset(&d, 0, sizeof(d));
+    d.X = src.X; d.y = src.y; d.w = src.w; d.grad = src.grad;
+    d.loss_out = src.loss_hist + src.hist_len;
+    d.gpart = reinterpret_cast<float *>(base + s.gpart);
+    d.lpart = reinterpret_cast<float *>(base + s.lpart);
+    d.wn2 = reinterpret_cast<double *>(base + s.wn2);
+    d.N = src.N; d.invN = 1.0 / (double)src.N; d.D = src.D; d.loss = src.loss;
+    d.lambda = src.lambda; d.step = src.step; d.sched = src.schedule; d.k0 = src.hist_len;
+    d.P = s.P; d.cls = s.cls; d.iters = iters; d.blk0 = 0;
+    hipError_t e;
+    for (int r = 0; r < iters; ++r) {
+        const bool prof = g_prof.on && g_prof.used < g_prof.cap;
+        if (prof && (e = hipEventRecord(g_prof.ev[2 * g_prof.used], st)) != hipSuccess) return e;
+        if ((e = launch_row_pass_one(d, st)) != hipSuccess) return e;
+        if (prof) {
+            if ((e = hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st)) != hipSuccess) return e;
+            ++g_prof.used;
+        }
+        if ((e = launch_finalize_one(d, r, st)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 // Workspace layout of the sweep: [lambdas | steps][R][lossP][Gpart].
 struct SweepLayout { size_t hyper, R, lossP, Gpart, total; int T, S; };
 
@@ -231,6 +263,7 @@ int api_validate_shape(long long N, int D) { return validate_shape(N, D); }
 int api_validate_job(const glm_job_t &j) { return validate_job(j); }
 size_t api_dense_workspace_bytes(const glm_job_t &job) { return make_layout(&job, 1).total; }
 hipError_t api_run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, hipStream_t st) {
+    if (J == 1) return run_single(jobs[0], iters[0], ws, st);
     return run_rounds(jobs, J, iters, ws, st);
 }
 hipEvent_t *api_profile_take(int launches) {
@@ -270,7 +303,8 @@ int glm_step_batched(glm_job_t *jobs, int32_t J, const int32_t *alloc, void *ws,
         if (jobs[j].hist_len + (int64_t)alloc[j] > jobs[j].hist_cap) return GLM_ENOSPC;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
     if (ws_bytes < make_layout(jobs, J).total) return GLM_ENOSPC;
-    const hipError_t e = run_rounds(jobs, J, alloc, ws, static_cast<hipStream_t>(hip_stream));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = J == 1 ? run_single(jobs[0], alloc[0], ws, st) : run_rounds(jobs, J, alloc, ws, st);
     if (e != hipSuccess) return GLM_EHIP;
     for (int j = 0; j < J; ++j) jobs[j].hist_len += alloc[j];
     return GLM_OK;

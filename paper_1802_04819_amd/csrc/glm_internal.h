@@ -66,6 +66,9 @@ hipError_t launch_row_pass(const DevJob *jobs, const int *blk_job, int total_blo
                            int max_cls, hipStream_t st);
 hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int total_blocks,
                            int round, hipStream_t st);
+// One job passed by value (its blk0 is 0): grid = jb.P row blocks, resp. ceil(D / kFinCols) blocks.
+hipError_t launch_row_pass_one(const DevJob &jb, hipStream_t st);
+hipError_t launch_finalize_one(const DevJob &jb, int round, hipStream_t st);
 hipError_t launch_read_probe(const float *src, size_t n, float *sink, hipStream_t st);
 constexpr int kProbeBlocks = 512;   // two per compute unit, as the row pass: measured best for 1 GB and 16 GB
 

@@ -347,17 +347,36 @@ hipError_t launch_row_pass(const DevJob *jobs, const int *blk_job, int total_blo
     return hipGetLastError();
 }
 
+// One job, handed over by value in the kernel arguments: no table in device memory, block b is
+// row block b.  Same body as above, so the job's sums are formed in the same order.
+template <int CLS>
+__global__ __launch_bounds__(kRowBlockThreads) void row_pass_one_kernel(const DevJob jb) {
+    constexpr ClassInfo ci = class_info(CLS);
+    __shared__ float4 gred4[4 * 64 * ci.c];
+    __shared__ float lred[256];
+    row_pass_body<ci.lpr, ci.c, ci.b>(jb, (int)blockIdx.x, reinterpret_cast<float *>(gred4), lred);
+}
+
+hipError_t launch_row_pass_one(const DevJob &jb, hipStream_t st) {
+    dim3 grid((unsigned)jb.P), block(kRowBlockThreads);
+    switch (jb.cls) {
+#define SLAQ_CASE(K) case K: hipLaunchKernelGGL(row_pass_one_kernel<K>, grid, block, 0, st, jb); break;
+        SLAQ_CASE(0) SLAQ_CASE(1) SLAQ_CASE(2) SLAQ_CASE(3) SLAQ_CASE(4)
+        SLAQ_CASE(5) SLAQ_CASE(6) SLAQ_CASE(7) SLAQ_CASE(8)
+#undef SLAQ_CASE
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ finalize
 
-__global__ __launch_bounds__(kFinCols * kFinSegs) void finalize_kernel(
-    const DevJob *__restrict__ jobs, const int *__restrict__ cblk0, int nact, int round) {
+// Column block cb (kFinCols columns) of one job; the job's first column block also forms the loss.
+__device__ __forceinline__ void finalize_body(const DevJob &jb, const int cb, const int round) {
     constexpr int T = kFinCols * kFinSegs;
     __shared__ double sred[kFinSegs][kFinCols];
     __shared__ double lred[T];
     __shared__ double lred2[32];
-    const int a = find_segment(cblk0, nact, blockIdx.x);
-    const DevJob &jb = jobs[a];
-    const int cb = blockIdx.x - cblk0[a];
     const int tid = threadIdx.x;
     const int cl = tid & (kFinCols - 1);
     const int seg = tid / kFinCols;
@@ -420,6 +439,22 @@ __global__ __launch_bounds__(kFinCols * kFinSegs) void finalize_kernel(
             jb.loss_out[round] = (float)L;
         }
     }
+}
+
+__global__ __launch_bounds__(kFinCols * kFinSegs) void finalize_kernel(
+    const DevJob *__restrict__ jobs, const int *__restrict__ cblk0, int nact, int round) {
+    const int a = find_segment(cblk0, nact, blockIdx.x);
+    finalize_body(jobs[a], (int)blockIdx.x - cblk0[a], round);
+}
+
+__global__ __launch_bounds__(kFinCols * kFinSegs) void finalize_one_kernel(const DevJob jb, int round) {
+    finalize_body(jb, (int)blockIdx.x, round);
+}
+
+hipError_t launch_finalize_one(const DevJob &jb, int round, hipStream_t st) {
+    hipLaunchKernelGGL(finalize_one_kernel, dim3((unsigned)((jb.D + kFinCols - 1) / kFinCols)),
+                       dim3(kFinCols * kFinSegs), 0, st, jb, round);
+    return hipGetLastError();
 }
 
 hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int total_blocks,
