@@ -112,6 +112,20 @@ int glm_workspace_bytes(const glm_job_t *jobs /*HOST [J]*/, int32_t J, int32_t M
 int glm_step(glm_job_t *job /*HOST*/, int32_t iters, void *ws /*DEVICE*/, size_t ws_bytes,
              void *hip_stream);
 
+/* glm_step for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results; the per-row-block partial sums live in a device array that is
+ * part of the library's image (glm_step_noalloc_scratch_bytes() bytes, 8.06 MiB, held by every GPU
+ * the library runs on until the process ends), which covers every shape glm_step accepts; a shape
+ * whose partial sums would not fit returns GLM_ENOSPC and enqueues nothing.  The call allocates
+ * and frees nothing, copies nothing and never waits for the device (the first call on a device
+ * looks the array's address up once).  All calls on one GPU share the array: they must be ordered
+ * on one stream, or otherwise not overlap; two calls in flight at once on one GPU race.  Nothing in
+ * the array has to start at zero (every slot a round reads is written earlier in that round), so
+ * whatever an earlier call left there is harmless.  Errors otherwise as glm_step. */
+int glm_step_noalloc(glm_job_t *job /*HOST*/, int32_t iters, void *hip_stream);
+size_t glm_step_noalloc_scratch_bytes(void);
+
 /* One scheduling epoch for J concurrent jobs (Sec. 2 "Scheduling Based on
  * Quality Improvements": jobs j in J, allocation a_j): job j runs alloc[j] >= 0
  * iterations (0 = idle this epoch).  The jobs may differ in every field.  All

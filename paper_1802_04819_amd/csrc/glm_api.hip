@@ -9,6 +9,10 @@
 #include "api_internal.h"
 #include "glm_internal.h"
 
+// Device-resident scratch of glm_step_noalloc (one copy per GPU, held until the process ends).
+// In host code this name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[(8u << 20) + (64u << 10)];
+
 namespace slaqglm {
 
 int class_of_D(int D) {
@@ -232,6 +236,17 @@ hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st)
     return hipSuccess;
 }
 
+// Scratch of glm_step_noalloc: the dense step's workspace (per-row-block partial sums) held in the
+// library's own device image instead of a caller's buffer.  The largest layout of any supported
+// shape is D = 4096 with 512 row blocks: 8 MiB of partial gradients plus a few KiB.
+constexpr size_t kScratchBytes = (8u << 20) + (64u << 10);
+constexpr int kScratchDevices = 64;
+struct ScratchPtrs {
+    std::mutex mu;
+    void *ptr[kScratchDevices] = {};       // device address of `scratch` on each device, once known
+};
+ScratchPtrs g_scratch;
+
 // Workspace layout of the sweep: [lambdas | steps][R][lossP][Gpart].
 struct SweepLayout { size_t hyper, R, lossP, Gpart, total; int T, S; };
 
@@ -313,6 +328,60 @@ int glm_step_batched(glm_job_t *jobs, int32_t J, const int32_t *alloc, void *ws,
 int glm_step(glm_job_t *job, int32_t iters, void *ws, size_t ws_bytes, void *hip_stream) {
     if (!job) return GLM_EINVAL;
     return glm_step_batched(job, 1, &iters, ws, ws_bytes, hip_stream);
+}
+
+size_t glm_step_noalloc_scratch_bytes(void) { return kScratchBytes; }
+
+int glm_step_noalloc(glm_job_t *job, int32_t iters, void *hip_stream) {
+    if (!job || iters < 0) return GLM_EINVAL;
+    const int rc = validate_job(*job);
+    if (rc != GLM_OK) return rc;
+    if (job->hist_len + (int64_t)iters > job->hist_cap) return GLM_ENOSPC;
+    // the layout of one job, computed without touching the heap: gpart [P, D], lpart [P], |w|^2
+    const int cls = class_of_D(job->D);
+    const int P = row_blocks(job->N, cls);
+    size_t off = 0;
+    const size_t o_gpart = off; off = align_up(off + sizeof(float) * (size_t)P * job->D);
+    const size_t o_lpart = off; off = align_up(off + sizeof(float) * (size_t)P);
+    const size_t o_wn2 = off;   off = align_up(off + sizeof(double));
+    if (off > kScratchBytes) return GLM_ENOSPC;      // shape needs more scratch than the library holds
+
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kScratchDevices) return GLM_EHIP;
+    char *base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch.mu);
+        if (!g_scratch.ptr[dev]) {
+            // each device holds its own copy of the array at its own address; the symbol itself is
+            // only a host-side handle
+            void *p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GLM_EHIP;
+            g_scratch.ptr[dev] = p;
+        }
+        base = static_cast<char *>(g_scratch.ptr[dev]);
+    }
+    if (iters == 0) return GLM_OK;
+
+    DevJob d;
+    std::memset(&d, 0, sizeof(d));
+    d.X = job->X; d.y = job->y; d.w = job->w; d.grad = job->grad;
+    d.loss_out = job->loss_hist + job->hist_len;
+    d.gpart = reinterpret_cast<float *>(base + o_gpart);
+    d.lpart = reinterpret_cast<float *>(base + o_lpart);
+    d.wn2 = reinterpret_cast<double *>(base + o_wn2);
+    d.N = job->N; d.invN = 1.0 / (double)job->N; d.D = job->D; d.loss = job->loss;
+    d.lambda = job->lambda; d.step = job->step; d.sched = job->schedule; d.k0 = job->hist_len;
+    d.P = P; d.cls = cls; d.iters = iters; d.blk0 = 0;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // Every slot of the scratch that a round reads has been written earlier in the same round
+    // (each row block writes its partial row and loss, row block 0 writes |w|^2), so nothing has
+    // to be cleared although the array keeps the previous call's contents.
+    for (int r = 0; r < iters; ++r) {
+        if (launch_row_pass_one(d, st) != hipSuccess) return GLM_EHIP;
+        if (launch_finalize_one(d, r, st) != hipSuccess) return GLM_EHIP;
+    }
+    job->hist_len += iters;
+    return GLM_OK;
 }
 
 int glm_sweep(const float *X, const float *y, int64_t N, int32_t D, int32_t M, int32_t loss, float *W,

@@ -26,6 +26,7 @@ EXPORTS = (
     "glm_sparse_workspace_bytes", "glm_step_sparse",
     "glm_kmeans_workspace_bytes", "glm_kmeans_step",
     "glm_lbfgs_workspace_bytes", "glm_lbfgs",
+    "glm_step_noalloc", "glm_step_noalloc_scratch_bytes",
 )
 GLM_CURVE_SUBLINEAR, GLM_CURVE_LINEAR = 1, 2
 GLM_STEP_CONSTANT, GLM_STEP_INV_SQRT = 0, 1
@@ -99,6 +100,10 @@ def load():
     lib.glm_workspace_bytes.argtypes = [jp, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(sz)]
     lib.glm_step.restype = ctypes.c_int
     lib.glm_step.argtypes = [jp, ctypes.c_int32, vp, sz, vp]
+    lib.glm_step_noalloc.restype = ctypes.c_int
+    lib.glm_step_noalloc.argtypes = [jp, ctypes.c_int32, vp]
+    lib.glm_step_noalloc_scratch_bytes.restype = ctypes.c_size_t
+    lib.glm_step_noalloc_scratch_bytes.argtypes = []
     lib.glm_step_batched.restype = ctypes.c_int
     lib.glm_step_batched.argtypes = [jp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), vp, sz, vp]
     lib.glm_sweep.restype = ctypes.c_int
@@ -238,6 +243,16 @@ def glm_step(job: Job, iters: int, ws: torch.Tensor, stream=None) -> None:
     _require_gpu()
     _check(load().glm_step(ctypes.byref(job.c), int(iters), ctypes.c_void_p(ws.data_ptr()),
                            ws.numel() * ws.element_size(), _stream_handle(stream)), "glm_step")
+
+
+def glm_step_noalloc(job: Job, iters: int, stream=None) -> None:
+    """glm_step on the library's own device-resident scratch (no workspace argument)."""
+    _require_gpu()
+    _check(load().glm_step_noalloc(ctypes.byref(job.c), int(iters), _stream_handle(stream)), "glm_step_noalloc")
+
+
+def glm_step_noalloc_scratch_bytes() -> int:
+    return int(load().glm_step_noalloc_scratch_bytes())
 
 
 def glm_step_batched(jobs: Sequence[Job], alloc, ws: torch.Tensor, stream=None) -> None:
