@@ -25,7 +25,7 @@ LOGISTIC, HINGE, SQUARED = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "glm_oracle.c")
-_SRCS = [_SRC, os.path.join(_HERE, "kmeans_oracle.c")]
+_SRCS = [_SRC, os.path.join(_HERE, "kmeans_oracle.c"), os.path.join(_HERE, "sched_fit.c")]
 _LIB_PATH = os.path.join(_HERE, "libglm_oracle.so")
 _lib = None
 
@@ -77,10 +77,22 @@ def _load():
         lib.oracle_kmeans_assign.argtypes = [fp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, i32p, dp, dp]
         lib.oracle_kmeans_step.restype = ctypes.c_int
         lib.oracle_kmeans_step.argtypes = [fp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, i32p, i64p, dp]
+        lib.oracle_fit_curve.restype = ctypes.c_int
+        lib.oracle_fit_curve.argtypes = [ctypes.c_int, dp, ctypes.c_int, ctypes.c_double, dp]
         lib.oracle_max_threads.restype = ctypes.c_int
         lib.oracle_max_threads.argtypes = []
         _lib = lib
     return _lib
+
+
+def fit_curve_raw(cls: int, L, gamma: float, lib=None):
+    """The convergence-curve fit of sched_fit.c on the window L (fp64, 4..128 values):
+    (ok, offset, p0, p1, p2, E, e).  `lib` lets a test run a separately compiled copy."""
+    L = np.ascontiguousarray(np.asarray(L, dtype=np.float64))
+    out = np.zeros(7, dtype=np.float64)
+    (lib or _load()).oracle_fit_curve(int(cls), L.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), int(L.shape[0]),
+                                     float(gamma), out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    return out
 
 
 def max_threads() -> int:

@@ -6,32 +6,32 @@ Follows Sec. 2 of the paper:
     largest change seen so far.
   * "Predicting Quality Improvement": a curve f(k) = 1/(a k^2 + b k + c) + d (sublinear
     convergence, class I) or f(k) = mu^(k-b) + c (linear/superlinear, class II) is fitted to the
-    exponentially weighted loss history and evaluated at future iterations.
+    exponentially weighted loss history and evaluated at future iterations.  The fit itself --
+    the weighted least-squares problem over all parameters of the curve, the box that keeps the
+    asymptote below the observed losses, and how its minimiser is found -- is sched_fit.c (plain
+    C loops; it is called several hundred times per test run).
   * "Scheduling Based on Quality Improvements": start from one unit per job, repeatedly give
     one more unit to the job whose predicted loss reduction for that unit is largest, until the
     capacity is used up.
 
-The paper states neither the weight decay, nor how the curve is fitted, nor what "normalised
-loss reduction" is exactly; the readings taken here (and in the library) are:
+The paper states neither the weight decay, nor what "normalised loss reduction" is exactly; the
+readings taken here (and in the library):
   - weight of history point i of n is gamma^(n-1-i); only the last `window` points are used;
-  - the fit is a variable projection: for a candidate offset (d, resp. c) the remaining
-    parameters enter linearly after the transform u = 1/(L-d) (resp. v = log(L-c)) and are found
-    by weighted linear least squares with the first-order weights w (L-d)^4 (resp. w (L-c)^2);
-    the offset is chosen on a two-level logarithmic grid of 64 candidates each by the weighted
-    squared error of the untransformed curve; ties go to the lower candidate index;
   - iteration numbers are scaled to t = i/(m-1) over the window of m points;
   - the predicted reduction of the h-th further iteration is (f(m-2+h) - f(m-1+h)) divided by
     the largest single-iteration change seen so far in the whole history.
 The paper prints no numeric example of any of this: "parity unpinned" against paper values;
-the CPU tests pin the routines with exact curves, hand examples and brute force.
+the CPU tests pin the routines with exact curves, an independent minimiser, hand examples and
+brute force.
 """
 from __future__ import annotations
 
 import numpy as np
 
+import oracle
+
 CLASS_SUBLINEAR, CLASS_LINEAR = 1, 2
-N_CAND = 64
-EXP_LO, EXP_HI = -4.0, 2.0          # first-level offsets: gap = span * 10**e, e in [EXP_LO, EXP_HI]
+FIT_LIB = None          # a test may point this at a separately compiled copy of sched_fit.c
 
 
 def normalized_changes(L):
@@ -43,80 +43,42 @@ def normalized_changes(L):
     return nu, (float(run[-1]) if len(run) else 0.0)
 
 
-def _fit_for_offset(cls, t, L, w, off):
-    """Weighted linear least squares in the transformed space for one offset candidate.
-    Returns (params, sse) with sse the weighted squared error of the untransformed curve,
-    or (None, inf) when the candidate is not admissible."""
-    g = L - off
-    if np.any(g <= 0):
-        return None, np.inf
+def weighted_error(L, cls, gamma, window, off, p):
+    """E = sum_i w_i (f(t_i) - L_i)^2 of a given curve on the window: the quantity the fit minimises,
+    evaluated directly (used to judge a fit someone else produced)."""
+    L = np.asarray(L, dtype=np.float64)[-window:]
+    m = len(L)
+    t = np.arange(m, dtype=np.float64) / (m - 1)
+    w = gamma ** np.arange(m - 1, -1, -1, dtype=np.float64)
     if cls == CLASS_SUBLINEAR:
-        u = 1.0 / g
-        W = w * g ** 4
-        A = np.stack([t * t, t, np.ones_like(t)], axis=1)
+        q = (p[0] * t + p[1]) * t + p[2]
+        if np.any(q <= 0):
+            return np.inf
+        f = 1.0 / q + off
     else:
-        u = np.log(g)
-        W = w * g ** 2
-        A = np.stack([t, np.ones_like(t)], axis=1)
-    AtW = A.T * W
-    N = AtW @ A
-    rhs = AtW @ u
-    try:
-        p = np.linalg.solve(N, rhs)
-    except np.linalg.LinAlgError:
-        return None, np.inf
-    lin = A @ p
-    if cls == CLASS_SUBLINEAR:
-        if np.any(lin <= 0) or not np.all(np.isfinite(lin)):
-            return None, np.inf
-        f = 1.0 / lin + off
-    else:
-        if not np.all(np.isfinite(lin)):
-            return None, np.inf
-        f = np.exp(lin) + off
-    sse = float(np.sum(w * (f - L) ** 2))
-    if not np.isfinite(sse):
-        return None, np.inf
-    return p, sse
+        f = np.exp(p[0] * t + p[1]) + off
+    return float(np.sum(w * (f - L) ** 2))
 
 
 def fit_curve(L, cls=CLASS_SUBLINEAR, gamma=0.9, window=128):
     """Fit the convergence curve of class `cls` to the last `window` losses.
 
-    Returns a dict with `ok`, `off` (d or c), `p` (linear parameters in scaled time), `m`
-    (points used), `sse`.  ok is False when there are fewer than 4 points, the history is
-    flat, or no candidate was admissible; predictions then repeat the last loss."""
+    Returns a dict with `ok`, `off` (d or c), `p` (the other parameters, in scaled time and in the
+    units of L: class I (a, b, c) with f = 1/(a t^2 + b t + c) + off, class II (p, q) with
+    f = exp(p t + q) + off), `e` (offset = min L - span 10^e), `m` (points used), `sse`.  ok is
+    False when there are fewer than 5 points, the history is flat or not finite, or nothing
+    admissible was found; predictions then repeat the last loss."""
     L = np.asarray(L, dtype=np.float64)
     L = L[-window:]
     m = len(L)
     out = {"ok": False, "m": m, "cls": cls, "last": float(L[-1]) if m else 0.0}
-    if m < 4:
+    if m < 5:
         return out
-    lo, hi = float(L.min()), float(L.max())
-    span = hi - lo
-    if not span > 0:
+    r = oracle.fit_curve_raw(cls, L, gamma, FIT_LIB)
+    if r[0] != 1.0:
         return out
-    t = np.arange(m, dtype=np.float64) / (m - 1)
-    w = gamma ** np.arange(m - 1, -1, -1, dtype=np.float64)
-    best = (np.inf, None, None, None)      # sse, exponent, offset, params
-    step = (EXP_HI - EXP_LO) / (N_CAND - 1)
-    for g in range(N_CAND):                # level 1
-        e = EXP_LO + step * g
-        off = lo - span * 10.0 ** e
-        p, sse = _fit_for_offset(cls, t, L, w, off)
-        if sse < best[0]:
-            best = (sse, e, off, p)
-    if best[1] is None:
-        return out
-    e0 = best[1]
-    step2 = 2.0 * step / (N_CAND - 1)
-    for g in range(N_CAND):                # level 2: 64 exponents in [e0 - step, e0 + step]
-        e = (e0 - step) + step2 * g
-        off = lo - span * 10.0 ** e
-        p, sse = _fit_for_offset(cls, t, L, w, off)
-        if sse < best[0]:
-            best = (sse, e, off, p)
-    out.update(ok=True, off=float(best[2]), p=np.asarray(best[3]), sse=float(best[0]))
+    p = r[2:5] if cls == CLASS_SUBLINEAR else r[2:4]
+    out.update(ok=True, off=float(r[1]), p=np.array(p), sse=float(r[5]), e=float(r[6]))
     return out
 
 
