@@ -280,16 +280,25 @@ typedef enum { GLM_CURVE_SUBLINEAR = 1, GLM_CURVE_LINEAR = 2 } glm_curve_t;
  * "Normalizing Quality Metrics"), fit the job's convergence curve to its exponentially weighted
  * loss history and evaluate it at the next `horizon` iterations (Sec. 2, "Predicting Quality
  * Improvement").  Of each job only loss_hist (DEVICE) and hist_len are read.
+ * The fit is the weighted least-squares problem over all parameters of the curve: with the last
+ * m <= window losses L_i at scaled times t_i = i/(m-1) and weights gamma^(m-1-i),
+ *     minimise sum_i w_i (f(t_i) - L_i)^2,
+ *     class I  f(t) = 1/(p0 t^2 + p1 t + p2) + offset  (positive denominator on the window),
+ *     class II f(t) = exp(p0 t + p1) + offset,
+ * the offset (the asymptote d, resp. c) confined to min L - span 10^e with -4 <= e <= 2, span the
+ * range of the window (the paper gives no domain; without one a history that falls along a
+ * straight line has no minimiser).  The problem is not convex; the library scans e, refines the
+ * deepest valleys and returns the best local minimum it finds.
  *   curve   HOST [J] glm_curve_t per job
  *   gamma   weight decay per iteration, 0 < gamma <= 1: history point i of n weighs gamma^(n-1-i)
- *   window  most recent losses used for the fit, 4 <= window <= 128
+ *   window  most recent losses used for the fit, 5 <= window <= 128
  *   pred    DEVICE [J, horizon] fp64: predicted loss after h = 1..horizon further iterations
  *   gain    DEVICE [J, horizon] fp64: predicted reduction contributed by the h-th further
  *           iteration, divided by the largest single-iteration change in the job's history
- *   fit     DEVICE [J, 8] fp64: {fitted (1/0), offset d or c, p0, p1, p2, weighted squared error,
- *           largest change, points used}; the linear parameters refer to time scaled to
- *           t = i/(m-1) over the m points used.  A job with fewer than 4 losses, a flat history
- *           or no admissible fit gets fitted = 0, pred = its last loss, gain = 0.
+ *   fit     DEVICE [J, 8] fp64: {fitted (1/0), offset, p0, p1, p2 (0 for class II), weighted squared
+ *           error, largest change, points used}.  A job with fewer than 5 losses (class I has four
+ *           parameters: fewer points would be interpolated, not fitted), a flat or non-finite
+ *           history or no admissible fit gets fitted = 0, pred = its last loss, gain = 0.
  *   ws      DEVICE workspace of glm_predict_workspace_bytes(J) bytes, 256-byte aligned
  * Every job needs hist_len >= 1.  Errors: GLM_EINVAL, GLM_ENOSPC (workspace), GLM_EHIP. */
 int glm_predict_batched(const glm_job_t *jobs /*HOST [J]*/, int32_t J, const int32_t *curve /*HOST*/,

@@ -449,7 +449,7 @@ int glm_predict_batched(const glm_job_t *jobs, int32_t J, const int32_t *curve, 
                         void *ws, size_t ws_bytes, void *hip_stream) {
     if (!jobs || !curve || !pred || !gain || !fit || J < 1) return GLM_EINVAL;
     if (!(gamma > 0.0) || !(gamma <= 1.0)) return GLM_EINVAL;
-    if (window < 4 || window > kPredWindowMax || horizon < 1 || horizon > kPredHorizonMax) return GLM_EINVAL;
+    if (window < kPredMinPoints || window > kPredWindowMax || horizon < 1 || horizon > kPredHorizonMax) return GLM_EINVAL;
     if ((reinterpret_cast<uintptr_t>(pred) & 7u) || (reinterpret_cast<uintptr_t>(gain) & 7u) ||
         (reinterpret_cast<uintptr_t>(fit) & 7u))
         return GLM_EINVAL;

@@ -93,6 +93,7 @@ hipError_t launch_sweep_iteration(const SweepArgs &a, int k, hipEvent_t *ev, hip
 
 // Scheduler-side steps (glm_sched.hip).
 constexpr int kPredWindowMax = 128;     // most recent losses a fit may use
+constexpr int kPredMinPoints = 5;       // one more than the curve with the most parameters has: fewer points are interpolated, not fitted
 constexpr int kPredHorizonMax = 4096;   // future iterations a call may predict
 struct PredJob {
     const float *hist;      // device: the job's loss history

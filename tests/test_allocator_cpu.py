@@ -76,7 +76,7 @@ def test_predict_rejects_bad_arguments_before_touching_the_gpu():
         return lib.glm_predict_batched(jobs, J, curve, gamma, window, horizon, pred, gain, fit, ws, nbytes, None)
 
     assert call(gamma=0.0) == glm.GLM_EINVAL and call(gamma=1.5) == glm.GLM_EINVAL
-    assert call(window=3) == glm.GLM_EINVAL and call(window=129) == glm.GLM_EINVAL
+    assert call(window=4) == glm.GLM_EINVAL and call(window=129) == glm.GLM_EINVAL
     assert call(horizon=0) == glm.GLM_EINVAL
     assert call(pred=None) == glm.GLM_EINVAL and call(ws=None) == glm.GLM_EINVAL
     assert call(nbytes=8) == glm.GLM_ENOSPC
