@@ -56,12 +56,13 @@ extern "C" {
  * (logistic regression, linear SVM and linear regression of Sec. 3 "Setup"). */
 typedef enum { GLM_LOGISTIC = 0, GLM_HINGE = 1, GLM_SQUARED = 2 } glm_loss_t;
 
-/* Step of iteration k, k counted from the start of the job (= its index in loss_hist):
+/* Step of iteration k, k counted from the start of the job (= its index in loss_hist).  The paper
+ * states no step schedule; both are options of this library, constant being the default:
  *   GLM_STEP_CONSTANT  step
- *   GLM_STEP_INV_SQRT  step / sqrt(k + 1): the decay of MLlib's gradient descent, the library the
- *                      paper's jobs ran on (Sec. 3 "Setup"); with it subgradient descent on the
- *                      hinge loss shows the diminishing returns the scheduler relies on (Sec. 1),
- *                      which it does not with a constant step. */
+ *   GLM_STEP_INV_SQRT  step / sqrt(k + 1), the usual decay for subgradient methods.  With it
+ *                      subgradient descent on the hinge loss shows the diminishing returns that a
+ *                      quality-driven scheduler relies on (Sec. 1); with a constant step its loss
+ *                      falls almost linearly for hundreds of iterations. */
 typedef enum { GLM_STEP_CONSTANT = 0, GLM_STEP_INV_SQRT = 1 } glm_step_schedule_t;
 
 typedef enum {
@@ -169,7 +170,8 @@ int glm_lbfgs_workspace_bytes(const glm_job_t *job /*HOST*/, int32_t memory, siz
 /* `iters` L-BFGS iterations on the objective of glm_step (job->step is ignored): two-loop recursion
  * over the last `memory` (0 .. 32) curvature pairs scaled by s.y / y.y of the newest, then a
  * backtracking line search: the first trial step is 1 (min(1, 1/|g|) while no pair is stored) and is
- * halved, at most 30 times, until f(w + a p) <= f(w) + 1e-4 a g.p + 1e-6 |f(w)|; a pair with
+ * halved, at most 30 times, until f(w + a p) <= f(w) + 1e-4 a g.p (the losses compared here are the
+ * fp64 sums of the evaluation, before they are rounded to the fp32 history entries); a pair with
  * s.y <= 1e-10 y.y is not stored.  Every evaluation is one row pass with step = 0.
  * loss_hist[hist_len + k] receives the loss at the iterate that enters iteration k; job->w and
  * job->grad are the current iterate and its gradient when the call returns.  The call synchronises

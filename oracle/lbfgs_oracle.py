@@ -9,9 +9,9 @@ recursion over the last m curvature pairs with the initial scaling s.y / y.y, an
 line search on the sufficient-decrease condition), with these readings, shared with the library:
   - the objective and its gradient are those of the GLM oracle (`oracle.loss_grad`);
   - first iteration: direction -g, first trial step min(1, 1/|g|); later iterations start at 1;
-  - a trial step alpha is accepted when f(w + alpha p) <= f(w) + c1 alpha g.p + eps_f |f(w)|
-    (c1 = 1e-4; eps_f = 1e-6 absorbs the resolution of a loss held in single precision); otherwise
-    alpha is halved, at most 30 times, after which the step is taken anyway;
+  - a trial step alpha is accepted when it satisfies the sufficient-decrease condition
+    f(w + alpha p) <= f(w) + c1 alpha g.p  with c1 = 1e-4; otherwise alpha is halved, at most 30
+    times, after which the step is taken anyway;
   - a curvature pair with s.y <= 1e-10 y.y is not stored;
   - the history entry of iteration k is the loss at the iterate that enters it.
 Against values printed by the paper: "parity unpinned".  The CPU tests pin the two-loop recursion
@@ -24,7 +24,6 @@ import numpy as np
 import oracle
 
 C1 = 1e-4
-EPS_F = 1e-6
 MAX_HALVINGS = 30
 CURV_EPS = 1e-10
 
@@ -64,7 +63,7 @@ def minimize(f_and_g, w0, iters, memory=10):
             wt = w + alpha * p
             ft, gt = f_and_g(wt)
             evals += 1
-            if ft <= f + C1 * alpha * gtp + EPS_F * abs(f) or h == MAX_HALVINGS:
+            if ft <= f + C1 * alpha * gtp or h == MAX_HALVINGS:
                 break
             alpha *= 0.5
         s, y = wt - w, gt - g

@@ -207,7 +207,7 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
 // One job: the descriptor travels in the kernel arguments, so nothing is staged or copied and
 // the host never waits; block b of the row pass is row block b.  Same kernel bodies and the same
 // workspace slots as run_rounds, hence the same bits.
-hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st) {
+hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st, double *loss64 = nullptr) {
     if (iters <= 0) return hipSuccess;
     const Layout L = make_layout(&src, 1);
     const JobSlots &s = L.slots[0];
@@ -222,6 +222,7 @@ hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st)
     d.N = src.N; d.invN = 1.0 / (double)src.N; d.D = src.D; d.loss = src.loss;
     d.lambda = src.lambda; d.step = src.step; d.sched = src.schedule; d.k0 = src.hist_len;
     d.P = s.P; d.cls = s.cls; d.iters = iters; d.blk0 = 0;
+    d.loss64 = loss64;
     hipError_t e;
     for (int r = 0; r < iters; ++r) {
         const bool prof = g_prof.on && g_prof.used < g_prof.cap;
@@ -280,6 +281,11 @@ size_t api_dense_workspace_bytes(const glm_job_t &job) { return make_layout(&job
 hipError_t api_run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, hipStream_t st) {
     if (J == 1) return run_single(jobs[0], iters[0], ws, st);
     return run_rounds(jobs, J, iters, ws, st);
+}
+hipError_t api_evaluate(const glm_job_t &job, void *ws, double *loss64, hipStream_t st) {
+    glm_job_t tmp = job;
+    tmp.step = 0.0f;
+    return run_single(tmp, 1, ws, st, loss64);
 }
 hipEvent_t *api_profile_take(int launches) {
     if (!g_prof.on || g_prof.used + launches > g_prof.cap) return nullptr;

@@ -304,7 +304,7 @@ LbLayout make_lbfgs_layout(const glm_job_t &job, int memory) {
     L.wt = off;    off = api_align_up(off + sizeof(float) * D);
     L.gt = off;    off = api_align_up(off + sizeof(float) * D);
     L.scal = off;  off = api_align_up(off + sizeof(double) * kLbScalars);
-    L.fslot = off; off = api_align_up(off + sizeof(float));
+    L.fslot = off; off = api_align_up(off + 16);      // fp32 loss at +0, the same loss before rounding (fp64) at +8
     L.total = off;
     return L;
 }
@@ -346,16 +346,17 @@ int glm_lbfgs(glm_job_t *job, glm_lbfgs_state_t *state, int32_t iters, int32_t m
 
     std::lock_guard<std::mutex> lock(g_lb.mu);
     if (!g_lb.buf && hipHostMalloc(&g_lb.buf, 256, hipHostMallocDefault) != hipSuccess) return GLM_EHIP;
-    float *h_f = static_cast<float *>(g_lb.buf);
+    double *h_f = reinterpret_cast<double *>(static_cast<char *>(g_lb.buf) + 8);
+    double *d_f = reinterpret_cast<double *>(base + L.fslot + 8);
     double *h_scal = reinterpret_cast<double *>(static_cast<char *>(g_lb.buf) + 64);
 
-    // one evaluation: loss and gradient at w_at (step = 0 leaves w_at untouched), loss read back
+    // one evaluation: loss and gradient at w_at (step = 0 leaves w_at untouched); the loss is read back as
+    // the fp64 value the finalize kernel forms before it rounds the history entry to fp32
     auto evaluate = [&](float *w_at, float *g_out, bool with_scalars) -> int {
         glm_job_t tmp = *job;
         tmp.w = w_at; tmp.grad = g_out; tmp.loss_hist = a.fslot; tmp.hist_len = 0; tmp.hist_cap = 1; tmp.step = 0.0f;
-        const int one = 1;
-        if (api_run_rounds(&tmp, 1, &one, base + L.dense, st) != hipSuccess) return GLM_EHIP;
-        if (hipMemcpyAsync(h_f, a.fslot, sizeof(float), hipMemcpyDeviceToHost, st) != hipSuccess) return GLM_EHIP;
+        if (api_evaluate(tmp, base + L.dense, d_f, st) != hipSuccess) return GLM_EHIP;
+        if (hipMemcpyAsync(h_f, d_f, sizeof(double), hipMemcpyDeviceToHost, st) != hipSuccess) return GLM_EHIP;
         if (with_scalars &&
             hipMemcpyAsync(h_scal, a.scal, sizeof(double) * kLbScalars, hipMemcpyDeviceToHost, st) != hipSuccess)
             return GLM_EHIP;
@@ -368,7 +369,7 @@ int glm_lbfgs(glm_job_t *job, glm_lbfgs_state_t *state, int32_t iters, int32_t m
     if (fresh) {
         const int e = evaluate(job->w, job->grad, false);
         if (e != GLM_OK) return e;
-        state->f = (double)*h_f;
+        state->f = *h_f;
         state->memory = memory;
         state->started = 1;
     }
@@ -381,9 +382,9 @@ int glm_lbfgs(glm_job_t *job, glm_lbfgs_state_t *state, int32_t iters, int32_t m
             if (launch_lbfgs_trial(a, job->w, h, st) != hipSuccess) return GLM_EHIP;
             const int e = evaluate(a.wt, a.gt, true);
             if (e != GLM_OK) return e;
-            ft = (double)*h_f;
+            ft = *h_f;
             const double alpha = std::ldexp(h_scal[2], -h);
-            if (ft <= state->f + 1e-4 * alpha * h_scal[0] + 1e-6 * std::fabs(state->f) || h == 30) break;
+            if (ft <= state->f + 1e-4 * alpha * h_scal[0] || h == 30) break;
         }
         if (launch_lbfgs_accept(a, job->w, job->grad, st) != hipSuccess) return GLM_EHIP;
         state->f = ft;

@@ -20,6 +20,7 @@ struct DevJob {
     float       *gpart;      // [P, D]  per-row-block partial sums of X^T r
     float       *lpart;      // [P]     per-row-block partial sums of the per-sample loss
     double      *wn2;        // [1]     |w|^2 of the iterate that entered the round
+    double      *loss64;     // if not null: receives the loss of the call's last round before it is rounded to fp32
     long long    N;
     double       invN;
     int          D;

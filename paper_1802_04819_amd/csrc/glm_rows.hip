@@ -437,6 +437,7 @@ __device__ __forceinline__ void finalize_body(const DevJob &jb, const int cb, co
             for (int q = 0; q < 32; ++q) S += lred2[q];
             const double L = S * jb.invN + 0.5 * (double)jb.lambda * (*jb.wn2);
             jb.loss_out[round] = (float)L;
+            if (jb.loss64) *jb.loss64 = L;
         }
     }
 }

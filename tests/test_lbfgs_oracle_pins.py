@@ -126,7 +126,7 @@ MUTANTS = {
     "oldest_pair_kept_forever": ("                S.pop(0); Y.pop(0)", "                S.pop(1); Y.pop(1)"),
     "memory_off_by_one": ("            if len(S) > memory:", "            if len(S) > memory + 1:"),
     "first_step_is_one": ("        alpha = 1.0 if S else min(1.0, 1.0 / max(gn[-1], 1e-300))", "        alpha = 1.0"),
-    "armijo_ignores_slope": ("            if ft <= f + C1 * alpha * gtp + EPS_F * abs(f) or h == MAX_HALVINGS:", "            if ft <= f + 0.9 * abs(f) or h == MAX_HALVINGS:"),
+    "armijo_ignores_slope": ("            if ft <= f + C1 * alpha * gtp or h == MAX_HALVINGS:", "            if ft <= f + 0.9 * abs(f) or h == MAX_HALVINGS:"),
     "history_after_the_step": ("        hist[k] = f\n        gn.append", "        gn.append"),
     "step_doubled_on_reject": ("            alpha *= 0.5", "            alpha *= 2.0"),
 }
