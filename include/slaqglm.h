@@ -102,6 +102,10 @@ typedef struct {
  * glm_sweep (M_sweep > 0: jobs[0] gives N and D, only those two fields are read)
  * need for these shapes.  The workspace holds per-block partial sums and launch
  * tables; it carries no state between calls and must be 256-byte aligned.
+ * A job of a few MB (every wave holds at most one tile of rows and the partial sums
+ * number at most 16384) runs a whole glm_step call in one launch whose blocks stay on
+ * the chip and exchange their partial sums through the workspace; its results are
+ * bit-identical to the general path.
  * Errors: GLM_EINVAL for a null pointer, J < 1, or a shape outside the limits. */
 int glm_workspace_bytes(const glm_job_t *jobs /*HOST [J]*/, int32_t J, int32_t M_sweep,
                         size_t *out_bytes /*HOST*/);

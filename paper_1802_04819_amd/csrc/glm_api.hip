@@ -59,8 +59,44 @@ int validate_job(const glm_job_t &j) {
     return GLM_OK;
 }
 
+// Workspace slots of one job (offsets from `off0`): partial gradients [P, D], partial losses [P],
+// |w|^2; for a job small enough for the resident kernel also the second pair of partial buffers and
+// the barrier words.  A function of (N, D) only.
+struct JobSlots { size_t gpart, lpart, wn2, gpart2, lpart2, ctl, end; int P, cls; bool tiny; };
+
+// Tiny: every wave of the job has at most one tile of rows (the row blocks are not capped) and
+// the partials are few enough for every block to add all of them.
+bool job_is_tiny(long long N, int D, int P, int cls) {
+    const ClassInfo ci = class_info(cls);
+    const long long rows_per_block_trip = 4LL * ci.b * (64 / ci.lpr);
+    return (long long)P * D <= kResidentMaxPartials && P <= 1024 && N <= rows_per_block_trip * P;
+}
+
+JobSlots job_slots(long long N, int D, size_t off0) {
+    JobSlots s;
+    s.cls = class_of_D(D);
+    s.P = row_blocks(N, s.cls);
+    s.tiny = job_is_tiny(N, D, s.P, s.cls);
+    size_t off = off0;
+    // a tiny job keeps its partial losses right behind its partial gradients, and the resident kernel
+    // stores every partial as a 64-bit word (tag, value)
+    const size_t gbytes = s.tiny ? sizeof(unsigned long long) * ((size_t)s.P * D + (size_t)s.P)
+                                 : sizeof(float) * (size_t)s.P * D;
+    s.gpart = off; off = align_up(off + gbytes);
+    if (s.tiny) s.lpart = s.gpart + sizeof(float) * (size_t)s.P * D;
+    else { s.lpart = off; off = align_up(off + sizeof(float) * (size_t)s.P); }
+    s.wn2 = off;   off = align_up(off + sizeof(double));
+    s.gpart2 = s.lpart2 = s.ctl = 0;
+    if (s.tiny) {
+        s.gpart2 = off; off = align_up(off + gbytes);
+        s.lpart2 = s.gpart2 + sizeof(float) * (size_t)s.P * D;
+        s.ctl = off;    off = align_up(off + 2 * sizeof(unsigned));
+    }
+    s.end = off;
+    return s;
+}
+
 // Workspace layout for a set of jobs: [launch tables][job 0 partials][job 1 partials]...
-struct JobSlots { size_t gpart, lpart, wn2; int P, cls; };
 struct Layout {
     size_t tab_jobs = 0, tab_map = 0, tab_cblk0 = 0;    // byte offsets
     size_t tab_end = 0;                                 // tables occupy [0, tab_end)
@@ -75,18 +111,12 @@ Layout make_layout(const glm_job_t *jobs, int J) {
     L.tab_cblk0 = off; off = align_up(off + sizeof(int) * (size_t)(J + 1));
     L.slots.resize(J);
     size_t blocks = 0;
-    for (int j = 0; j < J; ++j) {
-        L.slots[j].cls = class_of_D(jobs[j].D);
-        L.slots[j].P = row_blocks(jobs[j].N, L.slots[j].cls);
-        blocks += (size_t)L.slots[j].P;
-    }
+    for (int j = 0; j < J; ++j) blocks += (size_t)row_blocks(jobs[j].N, class_of_D(jobs[j].D));
     L.tab_map = off;   off = align_up(off + sizeof(int) * blocks);   // block -> job, one int per row block
     L.tab_end = off;
     for (int j = 0; j < J; ++j) {
-        JobSlots &s = L.slots[j];
-        s.gpart = off; off = align_up(off + sizeof(float) * (size_t)s.P * jobs[j].D);
-        s.lpart = off; off = align_up(off + sizeof(float) * (size_t)s.P);
-        s.wn2 = off;   off = align_up(off + sizeof(double));
+        L.slots[j] = job_slots(jobs[j].N, jobs[j].D, off);
+        off = L.slots[j].end;
     }
     L.total = off;
     return L;
@@ -207,11 +237,8 @@ hipError_t run_rounds(const glm_job_t *jobs, int J, const int *iters, void *ws, 
 // One job: the descriptor travels in the kernel arguments, so nothing is staged or copied and
 // the host never waits; block b of the row pass is row block b.  Same kernel bodies and the same
 // workspace slots as run_rounds, hence the same bits.
-hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st, double *loss64 = nullptr) {
-    if (iters <= 0) return hipSuccess;
-    const Layout L = make_layout(&src, 1);
-    const JobSlots &s = L.slots[0];
-    char *base = static_cast<char *>(ws);
+// Device-side descriptor of one job whose slots start at `base`.
+DevJob device_job(const glm_job_t &src, const JobSlots &s, char *base, int iters) {
     DevJob d;
     std::memset(&d, 0, sizeof(d));
     d.X = src.X; d.y = src.y; d.w = src.w; d.grad = src.grad;
@@ -219,11 +246,39 @@ hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st,
     d.gpart = reinterpret_cast<float *>(base + s.gpart);
     d.lpart = reinterpret_cast<float *>(base + s.lpart);
     d.wn2 = reinterpret_cast<double *>(base + s.wn2);
+    if (s.tiny) {
+        d.gpart2 = reinterpret_cast<float *>(base + s.gpart2);
+        d.lpart2 = reinterpret_cast<float *>(base + s.lpart2);
+        d.ctl = base + s.ctl;
+    }
     d.N = src.N; d.invN = 1.0 / (double)src.N; d.D = src.D; d.loss = src.loss;
     d.lambda = src.lambda; d.step = src.step; d.sched = src.schedule; d.k0 = src.hist_len;
     d.P = s.P; d.cls = s.cls; d.iters = iters; d.blk0 = 0;
+    return d;
+}
+
+// A tiny job runs its whole call in one resident launch when all its row blocks fit on the chip at
+// once (and the barrier count cannot overflow); everything else takes two launches per iteration.
+bool use_resident(const JobSlots &s, int iters) {
+    return s.tiny && (long long)iters * s.P < (1LL << 31) && s.P <= resident_capacity(s.cls);
+}
+
+hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st, double *loss64 = nullptr) {
+    if (iters <= 0) return hipSuccess;
+    const JobSlots s = job_slots(src.N, src.D, make_layout(&src, 1).tab_end);
+    DevJob d = device_job(src, s, static_cast<char *>(ws), iters);
     d.loss64 = loss64;
     hipError_t e;
+    if (use_resident(s, iters)) {
+        const bool prof = g_prof.on && g_prof.used < g_prof.cap;
+        if (prof && (e = hipEventRecord(g_prof.ev[2 * g_prof.used], st)) != hipSuccess) return e;
+        if ((e = launch_resident(d, st)) != hipSuccess) return e;
+        if (prof) {
+            if ((e = hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st)) != hipSuccess) return e;
+            ++g_prof.used;
+        }
+        return hipSuccess;
+    }
     for (int r = 0; r < iters; ++r) {
         const bool prof = g_prof.on && g_prof.used < g_prof.cap;
         if (prof && (e = hipEventRecord(g_prof.ev[2 * g_prof.used], st)) != hipSuccess) return e;
@@ -343,14 +398,9 @@ int glm_step_noalloc(glm_job_t *job, int32_t iters, void *hip_stream) {
     const int rc = validate_job(*job);
     if (rc != GLM_OK) return rc;
     if (job->hist_len + (int64_t)iters > job->hist_cap) return GLM_ENOSPC;
-    // the layout of one job, computed without touching the heap: gpart [P, D], lpart [P], |w|^2
-    const int cls = class_of_D(job->D);
-    const int P = row_blocks(job->N, cls);
-    size_t off = 0;
-    const size_t o_gpart = off; off = align_up(off + sizeof(float) * (size_t)P * job->D);
-    const size_t o_lpart = off; off = align_up(off + sizeof(float) * (size_t)P);
-    const size_t o_wn2 = off;   off = align_up(off + sizeof(double));
-    if (off > kScratchBytes) return GLM_ENOSPC;      // shape needs more scratch than the library holds
+    // the slots of one job from offset 0, computed without touching the heap
+    const JobSlots sl = job_slots(job->N, job->D, 0);
+    if (sl.end > kScratchBytes) return GLM_ENOSPC;   // shape needs more scratch than the library holds
 
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kScratchDevices) return GLM_EHIP;
@@ -368,23 +418,19 @@ int glm_step_noalloc(glm_job_t *job, int32_t iters, void *hip_stream) {
     }
     if (iters == 0) return GLM_OK;
 
-    DevJob d;
-    std::memset(&d, 0, sizeof(d));
-    d.X = job->X; d.y = job->y; d.w = job->w; d.grad = job->grad;
-    d.loss_out = job->loss_hist + job->hist_len;
-    d.gpart = reinterpret_cast<float *>(base + o_gpart);
-    d.lpart = reinterpret_cast<float *>(base + o_lpart);
-    d.wn2 = reinterpret_cast<double *>(base + o_wn2);
-    d.N = job->N; d.invN = 1.0 / (double)job->N; d.D = job->D; d.loss = job->loss;
-    d.lambda = job->lambda; d.step = job->step; d.sched = job->schedule; d.k0 = job->hist_len;
-    d.P = P; d.cls = cls; d.iters = iters; d.blk0 = 0;
+    const DevJob d = device_job(*job, sl, base, iters);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     // Every slot of the scratch that a round reads has been written earlier in the same round
-    // (each row block writes its partial row and loss, row block 0 writes |w|^2), so nothing has
-    // to be cleared although the array keeps the previous call's contents.
-    for (int r = 0; r < iters; ++r) {
-        if (launch_row_pass_one(d, st) != hipSuccess) return GLM_EHIP;
-        if (launch_finalize_one(d, r, st) != hipSuccess) return GLM_EHIP;
+    // (each row block writes its partial row and loss, row block 0 writes |w|^2), and the barrier
+    // words of the resident kernel are cleared by a kernel of their own before it starts, so
+    // nothing else has to be cleared although the array keeps the previous call's contents.
+    if (use_resident(sl, iters)) {
+        if (launch_resident(d, st) != hipSuccess) return GLM_EHIP;
+    } else {
+        for (int r = 0; r < iters; ++r) {
+            if (launch_row_pass_one(d, st) != hipSuccess) return GLM_EHIP;
+            if (launch_finalize_one(d, r, st) != hipSuccess) return GLM_EHIP;
+        }
     }
     job->hist_len += iters;
     return GLM_OK;

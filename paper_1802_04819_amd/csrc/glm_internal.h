@@ -21,6 +21,9 @@ struct DevJob {
     float       *lpart;      // [P]     per-row-block partial sums of the per-sample loss
     double      *wn2;        // [1]     |w|^2 of the iterate that entered the round
     double      *loss64;     // if not null: receives the loss of the call's last round before it is rounded to fp32
+    float       *gpart2;     // resident kernel only: second buffers for the partials (odd rounds)
+    float       *lpart2;
+    void        *ctl;        // resident kernel only: barrier counter and failure flag
     long long    N;
     double       invN;
     int          D;
@@ -70,6 +73,13 @@ hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int t
 // One job passed by value (its blk0 is 0): grid = jb.P row blocks, resp. ceil(D / kFinCols) blocks.
 hipError_t launch_row_pass_one(const DevJob &jb, hipStream_t st);
 hipError_t launch_finalize_one(const DevJob &jb, int round, hipStream_t st);
+// Whole call of one tiny job in one launch (iters = jb.iters); needs gpart2, lpart2, ctl and
+// jb.P <= resident_capacity(jb.cls).
+hipError_t launch_resident(const DevJob &jb, hipStream_t st);
+int resident_capacity(int cls);
+// A job is run by the resident kernel when its partials are small enough for every block to add all
+// of them (P * D floats) and all its row blocks fit on the chip at once.
+constexpr long long kResidentMaxPartials = 16384;
 hipError_t launch_read_probe(const float *src, size_t n, float *sink, hipStream_t st);
 constexpr int kProbeBlocks = 512;   // two per compute unit, as the row pass: measured best for 1 GB and 16 GB
 

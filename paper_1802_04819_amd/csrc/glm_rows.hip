@@ -158,18 +158,23 @@ __device__ __forceinline__ void loss_batches(std::integer_sequence<int, Qs...>, 
 // the row of wave-load 4*batch + q (QB = min(B, 4) rows per batch) and the residual is then
 // handed to the other lanes with quad_perm broadcasts, so the transcendental work is done
 // once per QB rows instead of once per row.
-template <int LPR, int C, int B, int LOSS, bool FULL>
-__device__ __forceinline__ void process_tile(gmem_f4 X4, gmem_f yv, const long long D4,
-                                             const long long N, const long long row0,
-                                             const int (&fidx)[C], const f4 (&wv)[C], f4 (&ga)[C],
-                                             float &lsum, const int lane) {
-    constexpr int RPL = 64 / LPR;
-    constexpr int QB = B < 4 ? B : 4;
-    constexpr int NBATCH = B / QB;
+//
+// A trip is two steps: tile_load brings the rows and labels into registers, tile_compute does
+// everything else.  The resident kernel loads once and computes once per iteration.
+template <int B> struct TileQ {
+    static constexpr int QB = B < 4 ? B : 4;
+    static constexpr int NBATCH = B / QB;
     static_assert(B % QB == 0, "wave-loads per trip must be a multiple of the loss batch");
-    const int ql = lane & (QB - 1);
+};
 
-    f4 xv[B][C];
+template <int LPR, int C, int B, bool FULL>
+__device__ __forceinline__ void tile_load(gmem_f4 X4, gmem_f yv, const long long D4, const long long N,
+                                          const long long row0, const int (&fidx)[C], const int lane,
+                                          f4 (&xv)[B][C], float (&ysel)[TileQ<B>::NBATCH],
+                                          long long (&rsel)[TileQ<B>::NBATCH]) {
+    constexpr int RPL = 64 / LPR;
+    constexpr int QB = TileQ<B>::QB;
+    const int ql = lane & (QB - 1);
 #pragma unroll
     for (int b = 0; b < B; ++b) {
         long long row = row0 + (long long)b * RPL;
@@ -178,16 +183,21 @@ __device__ __forceinline__ void process_tile(gmem_f4 X4, gmem_f yv, const long l
 #pragma unroll
         for (int c = 0; c < C; ++c) xv[b][c] = __builtin_nontemporal_load(base + fidx[c]);
     }
-    float ysel[NBATCH];
-    long long rsel[NBATCH];
 #pragma unroll
-    for (int q = 0; q < NBATCH; ++q) {
+    for (int q = 0; q < TileQ<B>::NBATCH; ++q) {
         rsel[q] = row0 + (long long)(QB * q + ql) * RPL;
         long long rc = rsel[q];
         if constexpr (!FULL) rc = rc < N ? rc : (N - 1);
         ysel[q] = __builtin_nontemporal_load(yv + rc);
     }
+}
 
+template <int LPR, int C, int B, int LOSS, bool FULL>
+__device__ __forceinline__ void tile_compute(const f4 (&xv)[B][C], const float (&ysel)[TileQ<B>::NBATCH],
+                                             const long long (&rsel)[TileQ<B>::NBATCH], const long long N,
+                                             const f4 (&wv)[C], f4 (&ga)[C], float &lsum, const int lane) {
+    constexpr int QB = TileQ<B>::QB;
+    const int ql = lane & (QB - 1);
     float z[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) {
@@ -207,8 +217,20 @@ __device__ __forceinline__ void process_tile(gmem_f4 X4, gmem_f yv, const long l
 #pragma unroll
     for (int b = 0; b < B; ++b) z[b] = group_allreduce<LPR>(z[b], lane);
 
-    loss_batches<C, B, QB, LOSS, FULL>(std::make_integer_sequence<int, NBATCH>{}, xv, z, ysel, rsel, N,
+    loss_batches<C, B, QB, LOSS, FULL>(std::make_integer_sequence<int, TileQ<B>::NBATCH>{}, xv, z, ysel, rsel, N,
                                        ql, ga, lsum);
+}
+
+template <int LPR, int C, int B, int LOSS, bool FULL>
+__device__ __forceinline__ void process_tile(gmem_f4 X4, gmem_f yv, const long long D4,
+                                             const long long N, const long long row0,
+                                             const int (&fidx)[C], const f4 (&wv)[C], f4 (&ga)[C],
+                                             float &lsum, const int lane) {
+    f4 xv[B][C];
+    float ysel[TileQ<B>::NBATCH];
+    long long rsel[TileQ<B>::NBATCH];
+    tile_load<LPR, C, B, FULL>(X4, yv, D4, N, row0, fidx, lane, xv, ysel, rsel);
+    tile_compute<LPR, C, B, LOSS, FULL>(xv, ysel, rsel, N, wv, ga, lsum, lane);
 }
 
 template <int LPR, int C, int B, int LOSS>
@@ -230,22 +252,16 @@ __device__ __forceinline__ void row_loop(const DevJob &jb, const int vb, const i
         process_tile<LPR, C, B, LOSS, false>(X4, yv, D4, N, t * RT + rgrp, fidx, wv, ga, lsum, lane);
 }
 
-template <int LPR, int C, int B>
-__device__ __forceinline__ void row_pass_body(const DevJob &jb, const int vb, float *gred,
-                                              float *lred) {
-    constexpr int RPL = 64 / LPR;          // rows side by side in one wave-load
-    constexpr int DP = 4 * LPR * C;        // padded row length covered by the lane layout
-    constexpr int QB = B < 4 ? B : 4;      // lanes of a group that carry loss sums
-    const int lane = threadIdx.x & 63;
-    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+// The weights of the lane's slots and zeroed accumulators.  Slots beyond the real row length read a
+// clamped (valid) slot and get weight 0, so they add nothing to the margin; their accumulators are
+// never written out.  One wave of the job (`forms_wn2`; the first wave of row block 0 outside the
+// resident kernel) also forms |w|^2 of the entering iterate, for the L2 term of the loss.
+template <int LPR, int C>
+__device__ __forceinline__ void row_setup(const DevJob &jb, const bool forms_wn2, const int lane,
+                                          int (&fidx)[C], f4 (&wv)[C], f4 (&ga)[C]) {
     const int sub = lane & (LPR - 1);
     const int rgrp = (LPR == 64) ? 0 : (lane / LPR);
     const int D4 = jb.D >> 2;
-
-    // Slots beyond the real row length read a clamped (valid) slot and get weight 0, so they
-    // add nothing to the margin; their accumulators are never written out.
-    int fidx[C];
-    f4 wv[C], ga[C];
 #pragma unroll
     for (int c = 0; c < C; ++c) {
         const int f = c * LPR + sub;
@@ -255,9 +271,7 @@ __device__ __forceinline__ void row_pass_body(const DevJob &jb, const int vb, fl
         wv[c] = ok ? t : f4{0.f, 0.f, 0.f, 0.f};
         ga[c] = f4{0.f, 0.f, 0.f, 0.f};
     }
-    float lsum = 0.0f;
-
-    if (vb == 0 && wid == 0) {   // |w|^2 of the entering iterate, for the L2 term of the loss
+    if (forms_wn2) {
         double ww = 0.0;
         if (rgrp == 0) {
 #pragma unroll
@@ -271,6 +285,62 @@ __device__ __forceinline__ void row_pass_body(const DevJob &jb, const int vb, fl
         ww = wave_sum_f64(ww);
         if (lane == 0) *jb.wn2 = ww;
     }
+}
+
+// A value with an iteration tag above it: the unit of exchange between the blocks of the resident kernel.
+__device__ __forceinline__ unsigned long long tagged_word(const float v, const unsigned tag) {
+    return ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+}
+
+// Block reduction in a fixed order: (wave 0, group 0), (wave 0, group 1), ... (wave 3, last); the
+// block's partial gradient row and partial loss go to gp[0 .. D) and *lp.  Loss sums live in the
+// first QB lanes of each group (each carries different rows).  TAGGED (resident kernel): gp and lp
+// point at 64-bit words and every value is stored with `tag` above it, device-coherently.
+template <int LPR, int C, int B, bool TAGGED>
+__device__ __forceinline__ void row_reduce_store(const f4 (&ga)[C], const float lsum, const int D, float *gp,
+                                                 float *lp, float *gred, float *lred, const int wid,
+                                                 const int lane, const unsigned tag = 0u) {
+    constexpr int RPL = 64 / LPR;
+    constexpr int DP = 4 * LPR * C;
+    constexpr int QB = TileQ<B>::QB;
+    const int sub = lane & (LPR - 1);
+    const int rgrp = (LPR == 64) ? 0 : (lane / LPR);
+    f4 *gred4 = reinterpret_cast<f4 *>(gred);
+    const int slot = wid * RPL + rgrp;
+#pragma unroll
+    for (int c = 0; c < C; ++c) gred4[slot * (DP / 4) + c * LPR + sub] = ga[c];
+    if (sub < QB) lred[slot * QB + sub] = lsum;
+    __syncthreads();
+    for (int j = threadIdx.x; j < D; j += kRowBlockThreads) {
+        float s = gred[j];
+#pragma unroll
+        for (int q = 1; q < 4 * RPL; ++q) s = s + gred[q * DP + j];       // loads together, additions in order
+        if constexpr (TAGGED)
+            __hip_atomic_store(reinterpret_cast<unsigned long long *>(gp) + j, tagged_word(s, tag), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        else gp[j] = s;
+    }
+    if (threadIdx.x == 0) {
+        float s = lred[0];
+#pragma unroll
+        for (int q = 1; q < 4 * RPL * QB; ++q) s = s + lred[q];
+        if constexpr (TAGGED)
+            __hip_atomic_store(reinterpret_cast<unsigned long long *>(lp), tagged_word(s, tag), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        else *lp = s;
+    }
+}
+
+template <int LPR, int C, int B>
+__device__ __forceinline__ void row_pass_body(const DevJob &jb, const int vb, float *gred,
+                                              float *lred) {
+    const int lane = threadIdx.x & 63;
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int rgrp = (LPR == 64) ? 0 : (lane / LPR);
+    int fidx[C];
+    f4 wv[C], ga[C];
+    row_setup<LPR, C>(jb, vb == 0 && wid == 0, lane, fidx, wv, ga);
+    float lsum = 0.0f;
 
     if (jb.loss == GLM_LOGISTIC)
         row_loop<LPR, C, B, GLM_LOGISTIC>(jb, vb, wid, rgrp, fidx, wv, ga, lsum, lane);
@@ -279,27 +349,8 @@ __device__ __forceinline__ void row_pass_body(const DevJob &jb, const int vb, fl
     else
         row_loop<LPR, C, B, GLM_SQUARED>(jb, vb, wid, rgrp, fidx, wv, ga, lsum, lane);
 
-    // Block reduction in a fixed order: (wave 0, group 0), (wave 0, group 1), ... (wave 3, last).
-    // Loss sums live in the first QB lanes of each group (each carries different rows).
-    f4 *gred4 = reinterpret_cast<f4 *>(gred);
-    const int slot = wid * RPL + rgrp;
-#pragma unroll
-    for (int c = 0; c < C; ++c) gred4[slot * (DP / 4) + c * LPR + sub] = ga[c];
-    if (sub < QB) lred[slot * QB + sub] = lsum;
-    __syncthreads();
-    const int D = jb.D;
-    float *__restrict__ gp = jb.gpart + (size_t)vb * D;
-    for (int j = threadIdx.x; j < D; j += kRowBlockThreads) {
-        float s = gred[j];
-#pragma unroll 4
-        for (int q = 1; q < 4 * RPL; ++q) s = s + gred[q * DP + j];
-        gp[j] = s;
-    }
-    if (threadIdx.x == 0) {
-        float s = lred[0];
-        for (int q = 1; q < 4 * RPL * QB; ++q) s = s + lred[q];
-        jb.lpart[vb] = s;
-    }
+    row_reduce_store<LPR, C, B, false>(ga, lsum, jb.D, jb.gpart + (size_t)vb * jb.D, jb.lpart + vb, gred, lred,
+                                       wid, lane);
 }
 
 // Index a such that tab[a] <= x < tab[a+1]; tab has n+1 increasing entries, tab[0] = 0.
@@ -371,6 +422,53 @@ hipError_t launch_row_pass_one(const DevJob &jb, hipStream_t st) {
 
 // ------------------------------------------------------------------ finalize
 
+// The arithmetic of the finalize step, shared by the stand-alone kernel and the resident kernel so
+// that both form every sum in the same order.
+
+// Sum over row blocks [p0, p1) of one column of the partial gradients, index order, fp64.
+__device__ __forceinline__ double column_segment_sum(const float *gp, const int D, const int p0, const int p1) {
+    double s = 0.0;
+    int p = p0;
+    for (; p + 16 <= p1; p += 16) {          // 16 loads in flight, added in index order
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = gp[(size_t)(p + u) * D];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += (double)v[u];
+    }
+    for (; p < p1; ++p) s += (double)gp[(size_t)p * D];
+    return s;
+}
+
+__device__ __forceinline__ int fin_seg_begin(const int P, const int seg) { return (int)((long long)P * seg / kFinSegs); }
+
+// Loss partial of "thread" t of kFinCols * kFinSegs: a contiguous run of row blocks.
+__device__ __forceinline__ double loss_run_sum(const float *lpart, const int P, const int t) {
+    constexpr int T = kFinCols * kFinSegs;
+    const int p0 = (int)((long long)P * t / T);
+    const int p1 = (int)((long long)P * (t + 1) / T);
+    double ls = 0.0;
+    for (int p = p0; p < p1; ++p) ls += (double)lpart[p];
+    return ls;
+}
+
+// Gradient entry and updated weight of one column from the column's total over all row blocks.
+__device__ __forceinline__ void column_update(const DevJob &jb, const int round, const double tot, const float wj,
+                                              float &g_out, float &w_out) {
+    const double g = tot * jb.invN + (double)jb.lambda * (double)wj;
+    g_out = (float)g;
+    w_out = wj;
+    if (jb.step != 0.0f) {
+        double eta = (double)jb.step;
+        if (jb.sched == GLM_STEP_INV_SQRT) eta = eta / sqrt((double)(jb.k0 + round + 1));
+        w_out = (float)((double)wj - eta * g);
+    }
+}
+
+__device__ __forceinline__ double loss_value(const DevJob &jb, const double S, const double wn2) {
+    return S * jb.invN + 0.5 * (double)jb.lambda * wn2;
+}
+
 // Column block cb (kFinCols columns) of one job; the job's first column block also forms the loss.
 __device__ __forceinline__ void finalize_body(const DevJob &jb, const int cb, const int round) {
     constexpr int T = kFinCols * kFinSegs;
@@ -385,45 +483,27 @@ __device__ __forceinline__ void finalize_body(const DevJob &jb, const int cb, co
 
     // column sums: segment `seg` adds row blocks [P*seg/S, P*(seg+1)/S) in index order
     double s = 0.0;
-    if (col < D) {
-        const int p0 = (int)((long long)P * seg / kFinSegs);
-        const int p1 = (int)((long long)P * (seg + 1) / kFinSegs);
-        const float *__restrict__ gp = jb.gpart + col;
-        int p = p0;
-        for (; p + 16 <= p1; p += 16) {          // 16 loads in flight, added in index order
-            float v[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) v[u] = gp[(size_t)(p + u) * D];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) s += (double)v[u];
-        }
-        for (; p < p1; ++p) s += (double)gp[(size_t)p * D];
-    }
+    if (col < D) s = column_segment_sum(jb.gpart + col, D, fin_seg_begin(P, seg), fin_seg_begin(P, seg + 1));
     sred[seg][cl] = s;
 
     // loss sum (first column block of the job only): thread t adds a contiguous run of blocks
     const bool does_loss = (cb == 0);
-    if (does_loss) {
-        const int p0 = (int)((long long)P * tid / T);
-        const int p1 = (int)((long long)P * (tid + 1) / T);
-        double ls = 0.0;
-        for (int p = p0; p < p1; ++p) ls += (double)jb.lpart[p];
-        lred[tid] = ls;
-    }
+    if (does_loss) lred[tid] = loss_run_sum(jb.lpart, P, tid);
     __syncthreads();
 
     if (seg == 0 && col < D) {
-        double tot = sred[0][cl];
-#pragma unroll 8
-        for (int q = 1; q < kFinSegs; ++q) tot += sred[q][cl];
-        const float wj = jb.w[col];
-        const double g = tot * jb.invN + (double)jb.lambda * (double)wj;
-        jb.grad[col] = (float)g;
-        if (jb.step != 0.0f) {
-            double eta = (double)jb.step;
-            if (jb.sched == GLM_STEP_INV_SQRT) eta = eta / sqrt((double)(jb.k0 + round + 1));
-            jb.w[col] = (float)((double)wj - eta * g);
+        double c[4];                        // four runs of 16 segments each, then (c0 + c1) + (c2 + c3)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            c[k] = sred[16 * k][cl];
+#pragma unroll
+            for (int q = 1; q < 16; ++q) c[k] += sred[16 * k + q][cl];
         }
+        const double tot = (c[0] + c[1]) + (c[2] + c[3]);
+        float g, wn;
+        column_update(jb, round, tot, jb.w[col], g, wn);
+        jb.grad[col] = g;
+        if (jb.step != 0.0f) jb.w[col] = wn;
     }
     if (does_loss) {                       // fixed two-level sum of the T thread partials
         if (tid < 32) {
@@ -435,7 +515,7 @@ __device__ __forceinline__ void finalize_body(const DevJob &jb, const int cb, co
         if (tid == 0) {
             double S = 0.0;
             for (int q = 0; q < 32; ++q) S += lred2[q];
-            const double L = S * jb.invN + 0.5 * (double)jb.lambda * (*jb.wn2);
+            const double L = loss_value(jb, S, *jb.wn2);
             jb.loss_out[round] = (float)L;
             if (jb.loss64) *jb.loss64 = L;
         }
@@ -463,6 +543,288 @@ hipError_t launch_finalize(const DevJob *jobs, const int *cblk0, int nact, int t
     if (total_blocks <= 0) return hipSuccess;
     hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)total_blocks), dim3(kFinCols * kFinSegs), 0,
                        st, jobs, cblk0, nact, round);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ resident kernel (tiny jobs)
+
+// For a job so small that an iteration is nothing but launch and dependency latency, the whole
+// call runs in ONE launch: the job's P row blocks stay resident and loop over the iterations.
+// Every wave has at most one tile of rows (that is part of what makes a job tiny) and keeps it in
+// registers for the whole call.  Per iteration: the row pass of the block on that tile (same
+// arithmetic as above; the weights come from the block's own copy in LDS), one barrier among the
+// job's blocks, then EVERY block copies all partials of the job into LDS and forms the complete
+// finalize step for itself (same order of additions as finalize_body), so it owns the next weights
+// without a second barrier; partials alternate between two buffers, so a block that is still
+// reading iteration k's cannot be overtaken by iteration k+2's writes.  The last block writes the
+// loss history, block 0 after the last iteration the gradient and the weights.
+//
+// Exchange of the partials.  A barrier with a cache-wide release/acquire pair costs 10 us and more
+// with 64 blocks on this part (each acquire drops the L2 of its XCD), and even a counter barrier
+// built from device-coherent accesses puts four dependent trips to memory between a block's last
+// store and its first load.  So there is no barrier: every partial travels as one 64-bit word
+// {iteration tag, value}, written with a device-coherent relaxed atomic store; a reader loads the
+// words it needs with device-coherent relaxed atomic loads and loads a word again until its tag is
+// the tag of the iteration it is in.  A word is stored and loaded whole, so a matching tag
+// guarantees its value.  Tags are r + 1; a kernel of its own clears both buffers to tag 0 before the
+// launch.  Why two buffers suffice: a block writes iteration r + 2 only after it has read every
+// block's iteration r + 1 word, which each block writes only after it has finished reading
+// iteration r.
+//
+// All P blocks must be on the chip at once: the launcher only takes this path when P fits the
+// device's capacity for this kernel.  Every wait is bounded: after kResidentSpinLimit reloads a
+// thread gives up and sets the job's `failed` flag, which every other waiting thread sees at its next
+// reload; the remaining history entries are then filled with NaN.
+constexpr unsigned kResidentSpinLimit = 1u << 22;
+
+struct ResidentCtl { unsigned failed; unsigned pad; };
+
+// Total of one column over all row blocks, in the order of finalize_body: each of the 64 segments
+// added up from zero in index order; four runs of 16 consecutive segments, each run added up in
+// segment order starting from its first segment; then (c0 + c1) + (c2 + c3).  The values come from
+// LDS (row block p at base[p * stride]), sixteen loads in flight.
+static_assert(kFinSegs == 64, "the combine below is written for 64 segments");
+__device__ __forceinline__ double column_total(const float *base, const int stride, const int P) {
+    double c[4] = {0.0, 0.0, 0.0, 0.0};
+    if (P <= kFinSegs) {                        // no segment holds more than one row block
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float v[16];
+            bool has[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int seg = 16 * k + u;
+                const int p0 = (P * seg) / kFinSegs, p1 = (P * (seg + 1)) / kFinSegs;
+                has[u] = p1 > p0;
+                v[u] = base[(size_t)(has[u] ? p0 : 0) * stride];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const double s = has[u] ? 0.0 + (double)v[u] : 0.0;     // a segment starts from zero
+                c[k] = u == 0 ? s : c[k] + s;
+            }
+        }
+        return (c[0] + c[1]) + (c[2] + c[3]);
+    }
+    double s = 0.0;
+    int seg = 0, seg_end = fin_seg_begin(P, 1);
+    auto close = [&]() {                        // segment `seg` is complete (it may be empty)
+        const int k = seg >> 4;
+        const double upd = (seg & 15) == 0 ? s : c[k] + s;
+        c[0] = k == 0 ? upd : c[0]; c[1] = k == 1 ? upd : c[1]; c[2] = k == 2 ? upd : c[2]; c[3] = k == 3 ? upd : c[3];
+        s = 0.0; ++seg; seg_end = fin_seg_begin(P, seg + 1);
+    };
+    for (int p = 0; p < P; p += 16) {
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = base[(size_t)(p + u < P ? p + u : P - 1) * stride];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            if (p + u < P) {
+                while (p + u == seg_end) close();
+                s += (double)v[u];
+            }
+        }
+    }
+    while (seg < kFinSegs) close();
+    return (c[0] + c[1]) + (c[2] + c[3]);
+}
+
+constexpr int kResidentStage = kResidentMaxPartials + 1032;    // partial gradients + partial losses of a tiny job
+
+template <int LPR, int C, int B, int LOSS>
+__device__ __forceinline__ void resident_iterations(const DevJob &jb0, float *gred, float *lred, float *w_lds,
+                                                    double *wn2_lds, float *stage, double *lsum2, int *abandoned) {
+    constexpr int RPL = 64 / LPR;
+    constexpr long long RT = (long long)B * RPL;
+    constexpr int T = kFinCols * kFinSegs;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sub = lane & (LPR - 1);
+    const int rgrp = (LPR == 64) ? 0 : (lane / LPR);
+    const int vb = blockIdx.x;
+    const int D = jb0.D, P = jb0.P, D4 = jb0.D >> 2;
+    const long long N = jb0.N;
+    ResidentCtl *ctl = reinterpret_cast<ResidentCtl *>(jb0.ctl);
+    const int lossb = P - 1;                        // the block that forms the loss; block 0 writes the results
+
+    // the wave's tile of rows, loaded once (rows past the end read a clamped row and are masked later)
+    const long long t = (long long)vb * 4 + wid;
+    const bool has_tile = t * RT < N;
+    int fidx[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) { const int f = c * LPR + sub; fidx[c] = f < D4 ? f : (D4 - 1); }
+    f4 xv[B][C];
+    float ysel[TileQ<B>::NBATCH];
+    long long rsel[TileQ<B>::NBATCH];
+    if (has_tile)
+        tile_load<LPR, C, B, false>((gmem_f4)(uintptr_t)jb0.X, (gmem_f)(uintptr_t)jb0.y, D4, N, t * RT + rgrp, fidx,
+                                    lane, xv, ysel, rsel);
+
+    DevJob jb = jb0;
+    jb.w = w_lds;                                   // flat pointers into LDS
+    jb.wn2 = wn2_lds;
+    const int n_words = P * D + P;                  // one buffer: [P, D] gradients, then [P] losses, a word each
+    for (int r = 0; r < jb0.iters; ++r) {
+        unsigned long long *buf = reinterpret_cast<unsigned long long *>((r & 1) ? jb0.gpart2 : jb0.gpart);
+        const unsigned tag = (unsigned)r + 1u;
+        f4 wv[C], ga[C];
+        row_setup<LPR, C>(jb, vb == lossb && wid == 0, lane, fidx, wv, ga);
+        float lsum = 0.0f;
+        if (has_tile) tile_compute<LPR, C, B, LOSS, false>(xv, ysel, rsel, N, wv, ga, lsum, lane);
+        row_reduce_store<LPR, C, B, true>(ga, lsum, D, reinterpret_cast<float *>(buf + (size_t)vb * D),
+                                          reinterpret_cast<float *>(buf + (size_t)P * D + vb), gred, lred, wid, lane, tag);
+        // every partial of the job into LDS: sixteen words in flight per thread, each loaded again until
+        // it carries this iteration's tag
+        bool gave_up = false;
+        for (int i = tid; i < n_words; i += 16 * kRowBlockThreads) {
+            unsigned long long v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int k = i + u * kRowBlockThreads;
+                v[u] = k < n_words ? __hip_atomic_load(buf + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                   : ((unsigned long long)tag << 32);
+            }
+            unsigned spins = 0;
+            while (true) {
+                bool all = true;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    if ((unsigned)(v[u] >> 32) != tag) {
+                        v[u] = __hip_atomic_load(buf + i + u * kRowBlockThreads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        all = false;
+                    }
+                }
+                if (all) break;
+                if (++spins > kResidentSpinLimit ||
+                    __hip_atomic_load(&ctl->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                    __hip_atomic_store(&ctl->failed, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    gave_up = true;
+                    break;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int k = i + u * kRowBlockThreads;
+                if (k < n_words) stage[k] = __uint_as_float((unsigned)v[u]);
+            }
+        }
+        if (gave_up) *abandoned = 1;
+        __syncthreads();
+        if (*abandoned) {                           // written before the barrier by whoever gave up: one way for all
+            if (vb == lossb)
+                for (int k = r + tid; k < jb0.iters; k += kRowBlockThreads) jb0.loss_out[k] = __builtin_nanf("");
+            return;
+        }
+        // finalize, complete, in every block: one thread per column, from thread 0 upwards.  The last
+        // block also forms the loss as finalize_body does (1024 runs of row blocks, 32 sums of 32 runs,
+        // their sum): its last 32 threads take one sum each while the others work on the columns.  With
+        // at most 1024 row blocks a run holds one row block or none.
+        const bool last = r == jb0.iters - 1;
+        if (vb == lossb && tid >= kRowBlockThreads - 32) {
+            const int t32 = tid - (kRowBlockThreads - 32);
+            const float *lp = stage + (size_t)P * D;
+            float x[T / 32];
+            bool has[T / 32];
+#pragma unroll
+            for (int q = 0; q < T / 32; ++q) {
+                const int v = t32 * (T / 32) + q;
+                const int p0 = (P * v) / T, p1 = (P * (v + 1)) / T;
+                has[q] = p1 > p0;
+                x[q] = lp[has[q] ? p0 : 0];
+            }
+            double S = 0.0;
+#pragma unroll
+            for (int q = 0; q < T / 32; ++q) S += has[q] ? 0.0 + (double)x[q] : 0.0;
+            lsum2[t32] = S;
+        }
+        for (int col = tid; col < D; col += kRowBlockThreads) {
+            const double tot = column_total(stage + col, D, P);
+            float g, wn;
+            column_update(jb0, r, tot, w_lds[col], g, wn);
+            w_lds[col] = wn;                    // read again by the next row pass, after the barrier below
+            if (vb == 0 && last) { jb0.grad[col] = g; jb0.w[col] = wn; }
+        }
+        __syncthreads();
+        if (vb == lossb && tid == kRowBlockThreads - 1) {
+            double part[32];
+#pragma unroll
+            for (int q = 0; q < 32; ++q) part[q] = lsum2[q];
+            double S = 0.0;
+#pragma unroll
+            for (int q = 0; q < 32; ++q) S += part[q];
+            const double L = loss_value(jb0, S, *wn2_lds);
+            jb0.loss_out[r] = (float)L;
+            if (jb0.loss64 && last) *jb0.loss64 = L;
+        }
+    }
+}
+
+template <int CLS>
+__global__ __launch_bounds__(kRowBlockThreads) void resident_kernel(const DevJob jb0) {
+    constexpr ClassInfo ci = class_info(CLS);
+    __shared__ float4 gred4[4 * 64 * ci.c];
+    __shared__ float lred[256];
+    __shared__ __align__(16) float w_lds[4 * 64 * ci.c];       // the block's copy of the weights (padded row)
+    __shared__ double wn2_lds[1];
+    __shared__ double lsum2[32];
+    __shared__ __align__(16) float stage[kResidentStage];
+    __shared__ int abandoned;
+    if (threadIdx.x == 0) abandoned = 0;
+    for (int j = threadIdx.x; j < jb0.D; j += kRowBlockThreads) w_lds[j] = jb0.w[j];
+    __syncthreads();
+    float *gred = reinterpret_cast<float *>(gred4);
+    if (jb0.loss == GLM_LOGISTIC)
+        resident_iterations<ci.lpr, ci.c, ci.b, GLM_LOGISTIC>(jb0, gred, lred, w_lds, wn2_lds, stage, lsum2, &abandoned);
+    else if (jb0.loss == GLM_HINGE)
+        resident_iterations<ci.lpr, ci.c, ci.b, GLM_HINGE>(jb0, gred, lred, w_lds, wn2_lds, stage, lsum2, &abandoned);
+    else
+        resident_iterations<ci.lpr, ci.c, ci.b, GLM_SQUARED>(jb0, gred, lred, w_lds, wn2_lds, stage, lsum2, &abandoned);
+}
+
+// Tag 0 in every word of both buffers, and the failure flag down.
+__global__ __launch_bounds__(256) void resident_clear_kernel(unsigned long long *a, unsigned long long *b, int n_words,
+                                                             ResidentCtl *ctl) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n_words) { a[i] = 0ull; b[i] = 0ull; }
+    if (i == 0) { ctl->failed = 0u; ctl->pad = 0u; }
+}
+
+// Blocks of resident_kernel<cls> that the current device holds at once (0 on error).
+int resident_capacity(int cls) {
+    static int cap[64][kNumClasses];            // per device; 0 = not asked yet, -1 = asked and failed
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cap[dev][cls] == 0) {
+        int per_cu = 0, cus = 0;
+        hipError_t e = hipErrorInvalidValue;
+        switch (cls) {
+#define SLAQ_CASE(K) case K: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel<K>, kRowBlockThreads, 0); break;
+            SLAQ_CASE(0) SLAQ_CASE(1) SLAQ_CASE(2) SLAQ_CASE(3) SLAQ_CASE(4)
+            SLAQ_CASE(5) SLAQ_CASE(6) SLAQ_CASE(7) SLAQ_CASE(8)
+#undef SLAQ_CASE
+            default: break;
+        }
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        cap[dev][cls] = (e == hipSuccess && per_cu > 0 && cus > 0) ? per_cu * cus : -1;
+    }
+    return cap[dev][cls] > 0 ? cap[dev][cls] : 0;
+}
+
+hipError_t launch_resident(const DevJob &jb, hipStream_t st) {
+    const int n_words = jb.P * jb.D + jb.P;
+    hipLaunchKernelGGL(resident_clear_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<unsigned long long *>(jb.gpart), reinterpret_cast<unsigned long long *>(jb.gpart2),
+                       n_words, reinterpret_cast<ResidentCtl *>(jb.ctl));
+    dim3 grid((unsigned)jb.P), block(kRowBlockThreads);
+    switch (jb.cls) {
+#define SLAQ_CASE(K) case K: hipLaunchKernelGGL(resident_kernel<K>, grid, block, 0, st, jb); break;
+        SLAQ_CASE(0) SLAQ_CASE(1) SLAQ_CASE(2) SLAQ_CASE(3) SLAQ_CASE(4)
+        SLAQ_CASE(5) SLAQ_CASE(6) SLAQ_CASE(7) SLAQ_CASE(8)
+#undef SLAQ_CASE
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
