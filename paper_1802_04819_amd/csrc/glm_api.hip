@@ -122,14 +122,15 @@ Layout make_layout(const glm_job_t *jobs, int J) {
     return L;
 }
 
-// Pinned host staging for the launch tables.  One buffer per process, grown on demand; an
-// event marks the last copy that read it so that the next call does not overwrite it early.
+// Pinned host staging for the launch tables: a ring of slots, each with an event that marks the
+// copy that last read it.  A call takes the next slot and waits only if the copy issued
+// kStageSlots calls ago has not finished, so the host can run that many calls ahead of the device.
+constexpr int kStageSlots = 8;
 struct Staging {
     std::mutex mu;
-    void *host = nullptr;
-    size_t cap = 0;
-    hipEvent_t ev = nullptr;
-    bool pending = false;
+    struct Slot { void *host = nullptr; size_t cap = 0; hipEvent_t ev = nullptr; bool pending = false; };
+    Slot slot[kStageSlots];
+    int next = 0, cur = 0;
 };
 Staging g_stage;
 
@@ -142,30 +143,35 @@ struct Profile {
 };
 Profile g_prof;
 
-// Waits until the staging buffer is free, makes it at least `bytes` large and returns it.
-// Caller holds g_stage.mu, fills the buffer, enqueues the copy and calls stage_mark().
+// Takes the next slot of the ring, waits until the copy that last used it is done, makes it at
+// least `bytes` large and returns it.  Caller holds g_stage.mu, fills the buffer, enqueues the copy
+// and calls stage_mark().
 hipError_t stage_acquire(size_t bytes, char **out) {
     hipError_t e;
-    if (g_stage.pending) {
-        if ((e = hipEventSynchronize(g_stage.ev)) != hipSuccess) return e;
-        g_stage.pending = false;
+    g_stage.cur = g_stage.next;
+    g_stage.next = (g_stage.next + 1) % kStageSlots;
+    Staging::Slot &sl = g_stage.slot[g_stage.cur];
+    if (sl.pending) {
+        if ((e = hipEventSynchronize(sl.ev)) != hipSuccess) return e;
+        sl.pending = false;
     }
-    if (g_stage.cap < bytes) {
-        if (g_stage.host) { (void)hipHostFree(g_stage.host); g_stage.host = nullptr; g_stage.cap = 0; }
+    if (sl.cap < bytes) {
+        if (sl.host) { (void)hipHostFree(sl.host); sl.host = nullptr; sl.cap = 0; }
         const size_t want = std::max<size_t>(bytes, 1 << 16);
-        if ((e = hipHostMalloc(&g_stage.host, want, hipHostMallocDefault)) != hipSuccess) return e;
-        g_stage.cap = want;
+        if ((e = hipHostMalloc(&sl.host, want, hipHostMallocDefault)) != hipSuccess) return e;
+        sl.cap = want;
     }
-    if (!g_stage.ev) {
-        if ((e = hipEventCreateWithFlags(&g_stage.ev, hipEventDisableTiming)) != hipSuccess) return e;
+    if (!sl.ev) {
+        if ((e = hipEventCreateWithFlags(&sl.ev, hipEventDisableTiming)) != hipSuccess) return e;
     }
-    *out = static_cast<char *>(g_stage.host);
+    *out = static_cast<char *>(sl.host);
     return hipSuccess;
 }
 
 hipError_t stage_mark(hipStream_t st) {
-    const hipError_t e = hipEventRecord(g_stage.ev, st);
-    if (e == hipSuccess) g_stage.pending = true;
+    Staging::Slot &sl = g_stage.slot[g_stage.cur];
+    const hipError_t e = hipEventRecord(sl.ev, st);
+    if (e == hipSuccess) sl.pending = true;
     return e;
 }
 
