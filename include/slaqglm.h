@@ -149,7 +149,9 @@ int glm_step_batched(glm_job_t *jobs /*HOST [J]*/, int32_t J, const int32_t *all
  *   W         DEVICE [M, D] model-major, in/out          G  DEVICE [M, D] out, last gradients
  *   loss_hist DEVICE [iters, M], entry [k, m] = L_m at the iterate entering iteration k
  *   lambdas, steps  HOST [M]
- * Limits: 1 <= M <= 64, D multiple of 32 and <= 4096 (else GLM_EINVAL). */
+ * Models run in groups of 64 that take turns on the workspace (the time grows with ceil(M / 64); a
+ * group of at most 32 models costs about half a full one).
+ * Limits: 1 <= M <= 65536, D a multiple of 4, 4 <= D <= 4096 (else GLM_EINVAL). */
 int glm_sweep(const float *X /*DEVICE*/, const float *y /*DEVICE*/, int64_t N, int32_t D, int32_t M,
               int32_t loss, float *W /*DEVICE*/, float *G /*DEVICE*/,
               const float *lambdas /*HOST*/, const float *steps /*HOST*/, int32_t iters,

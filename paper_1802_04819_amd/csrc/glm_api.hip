@@ -312,13 +312,16 @@ ScratchPtrs g_scratch;
 // Workspace layout of the sweep: [lambdas | steps][R][lossP][Gpart].
 struct SweepLayout { size_t hyper, R, lossP, Gpart, total; int T, S; };
 
-SweepLayout make_sweep_layout(long long N, int D) {
+constexpr int kSweepModelsMax = 1 << 16;
+
+SweepLayout make_sweep_layout(long long N, int D, int M) {
     SweepLayout L;
     L.T = (int)((N + kSweepFwdRows - 1) / kSweepFwdRows);
     const long long chunks = (N + kSweepBwdRows - 1) / kSweepBwdRows;
     L.S = (int)std::min<long long>(chunks, kSweepSplitMax);
     size_t off = 0;
-    L.hyper = off; off = align_up(off + sizeof(float) * 2 * kSweepM);
+    const size_t Mpad = (size_t)(M + kSweepM - 1) / kSweepM * kSweepM;
+    L.hyper = off; off = align_up(off + sizeof(float) * 2 * Mpad);
     L.R = off;     off = align_up(off + sizeof(float) * (size_t)N * kSweepM);
     L.lossP = off; off = align_up(off + sizeof(float) * (size_t)kSweepM * L.T);
     L.Gpart = off; off = align_up(off + sizeof(float) * (size_t)L.S * kSweepM * D);
@@ -328,7 +331,7 @@ SweepLayout make_sweep_layout(long long N, int D) {
 
 int validate_sweep_shape(long long N, int D, int M) {
     if (N < 1 || N > (1LL << 31) * kSweepFwdRows - 1) return GLM_EINVAL;
-    if (D < 32 || D > 4096 || (D % 32) != 0 || M < 1 || M > kSweepM) return GLM_EINVAL;
+    if (D < 4 || D > 4096 || (D % 4) != 0 || M < 1 || M > kSweepModelsMax) return GLM_EINVAL;
     return GLM_OK;
 }
 
@@ -364,7 +367,7 @@ int glm_workspace_bytes(const glm_job_t *jobs, int32_t J, int32_t M_sweep, size_
     if (!jobs || !out_bytes || J < 1 || M_sweep < 0) return GLM_EINVAL;
     if (M_sweep > 0) {
         if (validate_sweep_shape(jobs[0].N, jobs[0].D, M_sweep) != GLM_OK) return GLM_EINVAL;
-        *out_bytes = make_sweep_layout(jobs[0].N, jobs[0].D).total;
+        *out_bytes = make_sweep_layout(jobs[0].N, jobs[0].D, M_sweep).total;
         return GLM_OK;
     }
     for (int j = 0; j < J; ++j)
@@ -457,41 +460,46 @@ int glm_sweep(const float *X, const float *y, int64_t N, int32_t D, int32_t M, i
         if (!std::isfinite(steps[m]) || steps[m] < 0.0f) return GLM_EINVAL;
     }
     if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
-    const SweepLayout L = make_sweep_layout(N, D);
+    const SweepLayout L = make_sweep_layout(N, D, M);
     if (ws_bytes < L.total) return GLM_ENOSPC;
     if (iters == 0) return GLM_OK;
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *base = static_cast<char *>(ws);
+    const int Mpad = (M + kSweepM - 1) / kSweepM * kSweepM;
     {
         std::lock_guard<std::mutex> lock(g_stage.mu);
         char *h = nullptr;
-        if (stage_acquire(sizeof(float) * 2 * kSweepM, &h) != hipSuccess) return GLM_EHIP;
+        if (stage_acquire(sizeof(float) * 2 * (size_t)Mpad, &h) != hipSuccess) return GLM_EHIP;
         float *hf = reinterpret_cast<float *>(h);
-        for (int m = 0; m < kSweepM; ++m) {
+        for (int m = 0; m < Mpad; ++m) {
             hf[m] = m < M ? lambdas[m] : 0.0f;
-            hf[kSweepM + m] = m < M ? steps[m] : 0.0f;
+            hf[Mpad + m] = m < M ? steps[m] : 0.0f;
         }
-        if (hipMemcpyAsync(base + L.hyper, h, sizeof(float) * 2 * kSweepM, hipMemcpyHostToDevice, st) !=
+        if (hipMemcpyAsync(base + L.hyper, h, sizeof(float) * 2 * (size_t)Mpad, hipMemcpyHostToDevice, st) !=
             hipSuccess)
             return GLM_EHIP;
         if (stage_mark(st) != hipSuccess) return GLM_EHIP;
     }
-    SweepArgs a;
-    a.X = X; a.y = y; a.W = W; a.G = G; a.loss_hist = loss_hist;
-    a.lambdas = reinterpret_cast<const float *>(base + L.hyper);
-    a.steps = a.lambdas + kSweepM;
-    a.R = reinterpret_cast<float *>(base + L.R);
-    a.lossP = reinterpret_cast<float *>(base + L.lossP);
-    a.Gpart = reinterpret_cast<float *>(base + L.Gpart);
-    a.N = N; a.D = D; a.M = M; a.loss = loss; a.T = L.T; a.S = L.S;
+    // groups of kSweepM models take turns on the same R, lossP and Gpart (stream order keeps them apart)
     for (int k = 0; k < iters; ++k) {
-        hipEvent_t *ev = nullptr;
-        if (g_prof.on && g_prof.used + 2 <= g_prof.cap) {
-            ev = &g_prof.ev[2 * g_prof.used];
-            g_prof.used += 2;
+        for (int g0 = 0; g0 < M; g0 += kSweepM) {
+            SweepArgs a;
+            a.X = X; a.y = y; a.W = W + (size_t)g0 * D; a.G = G + (size_t)g0 * D;
+            a.loss_row = loss_hist + (size_t)k * M + g0;
+            a.lambdas = reinterpret_cast<const float *>(base + L.hyper) + g0;
+            a.steps = reinterpret_cast<const float *>(base + L.hyper) + Mpad + g0;
+            a.R = reinterpret_cast<float *>(base + L.R);
+            a.lossP = reinterpret_cast<float *>(base + L.lossP);
+            a.Gpart = reinterpret_cast<float *>(base + L.Gpart);
+            a.N = N; a.D = D; a.M = std::min(kSweepM, M - g0); a.loss = loss; a.T = L.T; a.S = L.S;
+            hipEvent_t *ev = nullptr;
+            if (g_prof.on && g_prof.used + 2 <= g_prof.cap) {
+                ev = &g_prof.ev[2 * g_prof.used];
+                g_prof.used += 2;
+            }
+            if (launch_sweep_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
         }
-        if (launch_sweep_iteration(a, k, ev, st) != hipSuccess) return GLM_EHIP;
     }
     return GLM_OK;
 }

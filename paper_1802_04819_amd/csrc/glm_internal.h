@@ -83,14 +83,16 @@ constexpr long long kResidentMaxPartials = 16384;
 hipError_t launch_read_probe(const float *src, size_t n, float *sink, hipStream_t st);
 constexpr int kProbeBlocks = 512;   // two per compute unit, as the row pass: measured best for 1 GB and 16 GB
 
-// Sweep (glm_sweep.hip).  M models are padded to kSweepM columns of R and rows of Gpart.
+// Sweep (glm_sweep.hip).  Models run in groups of kSweepM; a group is padded to kSweepM columns of R
+// and rows of Gpart.
 constexpr int kSweepM = 64;
 constexpr int kSweepFwdRows = 128;      // rows per forward tile
 constexpr int kSweepBwdRows = 32;       // rows per backward chunk
 constexpr int kSweepBwdCols = 256;      // columns per backward slab
 constexpr int kSweepSplitMax = 128;     // row splits of the backward contraction
-struct SweepArgs {
-    const float *X; const float *y; float *W; float *G; float *loss_hist;
+struct SweepArgs {            // one group of at most kSweepM models
+    const float *X; const float *y; float *W; float *G;
+    float *loss_row;                                // [M] the group's entries of this iteration's history row
     const float *lambdas; const float *steps;       // device copies, [M]
     float *R;        // [N, kSweepM] residuals
     float *lossP;    // [M, T] per-tile loss sums

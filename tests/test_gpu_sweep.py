@@ -30,6 +30,9 @@ def _run_sweep(p, lams, etas, K, W0=None):
     (synth.LOGISTIC, 1000, 64, 5), (synth.LOGISTIC, 4097, 256, 64), (synth.HINGE, 3000, 96, 17),
     (synth.SQUARED, 2500, 320, 33), (synth.LOGISTIC, 129, 32, 1), (synth.SQUARED, 31, 1024, 64),
     (synth.HINGE, 20000, 512, 64),
+    # more than one group of 64 models, a last group of at most 32, row lengths that are not multiples of 32
+    (synth.LOGISTIC, 3000, 128, 128), (synth.SQUARED, 2000, 96, 100), (synth.LOGISTIC, 5000, 256, 16),
+    (synth.HINGE, 1500, 48, 32), (synth.LOGISTIC, 2222, 100, 70), (synth.SQUARED, 900, 4, 3), (synth.LOGISTIC, 700, 1028, 9),
 ])
 def test_sweep_matches_oracle_trajectories(loss, N, D, M):
     _say(f"[case] sweep parity loss={loss} N={N} D={D} M={M}")
@@ -109,10 +112,10 @@ def test_sweep_argument_errors():
     with pytest.raises(glm.GlmError) as e:
         glm.glm_sweep(X, y, 5, W, G, ok, ok, 1, h, ws)
     assert e.value.status == glm.GLM_EINVAL
-    X48 = torch.zeros(10, 48, device="cuda")
     with pytest.raises(glm.GlmError):
-        glm.sweep_workspace_bytes(10, 48, 3)          # D must be a multiple of 32
+        glm.sweep_workspace_bytes(10, 46, 3)          # D must be a multiple of 4
     with pytest.raises(glm.GlmError):
-        glm.sweep_workspace_bytes(10, 64, 65)         # at most 64 models
+        glm.sweep_workspace_bytes(10, 64, 70000)      # more models than a call takes
+    assert glm.sweep_workspace_bytes(10, 48, 3) > 0 and glm.sweep_workspace_bytes(10, 64, 65) > 0
     torch.cuda.synchronize()
     assert W.abs().sum().item() == 0
