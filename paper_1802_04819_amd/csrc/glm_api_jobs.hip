@@ -25,8 +25,9 @@ struct SparseLayout {
     FxPass fx_row, fx_col;
     long long nch;
     int P;
+    size_t csc_ptr, csc_idx, csc_val, csc_keys[2], csc_vals[2], csc_temp, csc_temp_bytes;   // CSR-only callers
 };
-SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
+SparseLayout make_sparse_layout(long long N, long long D, long long nnz, bool csr_only) {
     SparseLayout L{};
     L.nch = (nnz + kSparseChunk - 1) / kSparseChunk;
     const size_t nc = (size_t)L.nch;
@@ -82,6 +83,18 @@ SparseLayout make_sparse_layout(long long N, long long D, long long nnz) {
             L.fx_part[i] = off;   off = api_align_up(off + sizeof(long long) * (size_t)ps[i]->max_chunks * kFxPanel);
         }
     }
+    L.csc_ptr = L.csc_idx = L.csc_val = L.csc_keys[0] = L.csc_keys[1] = L.csc_vals[0] = L.csc_vals[1] = L.csc_temp = off;
+    L.csc_temp_bytes = 0;
+    if (csr_only) {                 // the library's own column layout and the buffers of the sort that makes it
+        const size_t n = (size_t)nnz;
+        L.csc_ptr = off; off = api_align_up(off + sizeof(long long) * (size_t)(D + 1));
+        L.csc_idx = off; off = api_align_up(off + sizeof(int) * n);
+        L.csc_val = off; off = api_align_up(off + sizeof(float) * n);
+        for (int i = 0; i < 2; ++i) { L.csc_keys[i] = off; off = api_align_up(off + sizeof(int) * n); }
+        for (int i = 0; i < 2; ++i) { L.csc_vals[i] = off; off = api_align_up(off + sizeof(unsigned long long) * n); }
+        L.csc_temp_bytes = sparse_csc_temp_bytes(nnz);
+        L.csc_temp = off; off = api_align_up(off + L.csc_temp_bytes);
+    }
     L.total = off;
     return L;
 }
@@ -123,7 +136,7 @@ int validate_sparse_shape(const glm_sparse_job_t &j) {
 int glm_sparse_workspace_bytes(const glm_sparse_job_t *job, size_t *out_bytes) {
     if (!job || !out_bytes) return GLM_EINVAL;
     if (validate_sparse_shape(*job) != GLM_OK) return GLM_EINVAL;
-    *out_bytes = make_sparse_layout(job->N, job->D, job->nnz).total;
+    *out_bytes = make_sparse_layout(job->N, job->D, job->nnz, job->col_ptr == nullptr).total;
     return GLM_OK;
 }
 
@@ -131,8 +144,11 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     if (!job || iters < 0) return GLM_EINVAL;
     const glm_sparse_job_t &j = *job;
     if (validate_sparse_shape(j) != GLM_OK) return GLM_EINVAL;
-    if (!j.row_ptr || !j.col_ptr || !j.y || !j.w || !j.grad || !j.loss_hist) return GLM_EINVAL;
-    if (j.nnz > 0 && (!j.col_idx || !j.row_val || !j.row_idx || !j.col_val)) return GLM_EINVAL;
+    if (!j.row_ptr || !j.y || !j.w || !j.grad || !j.loss_hist) return GLM_EINVAL;
+    const bool csr_only = j.col_ptr == nullptr;         // then the library builds the column layout itself
+    if (csr_only && (j.row_idx || j.col_val)) return GLM_EINVAL;
+    if (j.nnz > 0 && (!j.col_idx || !j.row_val)) return GLM_EINVAL;
+    if (j.nnz > 0 && !csr_only && (!j.row_idx || !j.col_val)) return GLM_EINVAL;
     const void *p4[] = {j.col_idx, j.row_val, j.row_idx, j.col_val, j.y, j.w, j.grad, j.loss_hist};
     for (const void *p : p4) if (reinterpret_cast<uintptr_t>(p) & 3u) return GLM_EINVAL;
     if ((reinterpret_cast<uintptr_t>(j.row_ptr) & 7u) || (reinterpret_cast<uintptr_t>(j.col_ptr) & 7u)) return GLM_EINVAL;
@@ -143,7 +159,7 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     if (j.prepared < 0 || j.prepared > 2) return GLM_EINVAL;
     if (j.schedule != GLM_STEP_CONSTANT && j.schedule != GLM_STEP_INV_SQRT) return GLM_EINVAL;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) % 256) != 0) return GLM_EINVAL;
-    const SparseLayout L = make_sparse_layout(j.N, j.D, j.nnz);
+    const SparseLayout L = make_sparse_layout(j.N, j.D, j.nnz, csr_only);
     if (ws_bytes < L.total) return GLM_ENOSPC;
     if (iters == 0) return GLM_OK;
 
@@ -152,6 +168,18 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     SparseArgs a;
     a.row_ptr = reinterpret_cast<const long long *>(j.row_ptr); a.col_idx = j.col_idx; a.row_val = j.row_val;
     a.col_ptr = reinterpret_cast<const long long *>(j.col_ptr); a.row_idx = j.row_idx; a.col_val = j.col_val;
+    SparseCsc csc{};
+    if (csr_only) {
+        csc.col_ptr = reinterpret_cast<long long *>(base + L.csc_ptr);
+        csc.row_idx = reinterpret_cast<int *>(base + L.csc_idx);
+        csc.col_val = reinterpret_cast<float *>(base + L.csc_val);
+        for (int i = 0; i < 2; ++i) {
+            csc.keys[i] = reinterpret_cast<int *>(base + L.csc_keys[i]);
+            csc.vals[i] = reinterpret_cast<unsigned long long *>(base + L.csc_vals[i]);
+        }
+        csc.temp = base + L.csc_temp; csc.temp_bytes = L.csc_temp_bytes;
+        a.col_ptr = csc.col_ptr; a.row_idx = csc.row_idx; a.col_val = csc.col_val;
+    }
     a.y = j.y; a.w = j.w; a.grad = j.grad; a.loss_out = j.loss_hist + j.hist_len;
     a.N = j.N; a.D = j.D; a.nnz = j.nnz; a.nch = L.nch;
     a.loss = j.loss; a.lambda = j.lambda; a.step = j.step; a.sched = j.schedule; a.k0 = j.hist_len;
@@ -162,6 +190,14 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     a.z = reinterpret_cast<float *>(base + L.z); a.gs = a.z + j.N;
     a.r = reinterpret_cast<float *>(base + L.r);
     a.lossP = reinterpret_cast<float *>(base + L.lossP); a.wwP = reinterpret_cast<double *>(base + L.wwP);
+    // (for a CSR-only job the record is keyed by the row arrays: the column layout is the library's own
+    // and lives in the workspace as well, so "2" cannot occur)
+    const PanelKey key = csr_only ? PanelKey{ws, j.row_ptr, j.col_idx, j.row_val, j.N, j.D, j.nnz}
+                                  : PanelKey{ws, j.col_ptr, j.row_idx, j.col_val, j.N, j.D, j.nnz};
+    if (csr_only) {
+        if (job->prepared != 1 || !panel_registry_has(key)) job->prepared = 0;
+        if (job->prepared == 0 && launch_sparse_csc_build(a, csc, st) != hipSuccess) return GLM_EHIP;
+    }
     if (launch_sparse_setup(a, st) != hipSuccess) return GLM_EHIP;
     SparsePanels pn;
     pn.P = L.P; pn.R = kSparsePanelRows;
@@ -188,8 +224,11 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     }
     const bool any_fx = (fx.row.on || fx.col.on) && j.nnz > 0;
     // job->prepared: 0 = nothing built yet, 1 = auxiliary layouts in the workspace, 2 = caller's layout is used
-    const PanelKey key{ws, j.col_ptr, j.row_idx, j.col_val, j.N, j.D, j.nnz};
-    if (job->prepared == 1 && !((pn.P > 1 || any_fx) && j.nnz > 0 && panel_registry_has(key))) job->prepared = 0;
+    if (csr_only) {
+        // (the layout itself was enqueued above, before anything that reads it)
+    } else if (job->prepared == 1 && !((pn.P > 1 || any_fx) && j.nnz > 0 && panel_registry_has(key))) {
+        job->prepared = 0;
+    }
     if (any_fx && job->prepared == 0) {
         if (launch_sparse_fx_build(a, fx, st) != hipSuccess) return GLM_EHIP;
         panel_registry_put(key);
@@ -210,7 +249,12 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     } else if (job->prepared == 0) {
         job->prepared = 2;
     }
-    if (job->prepared != 1) { pn.P = 1; fx.row.on = fx.col.on = 0; }
+    const bool aux_built = job->prepared == 1;          // panels or scatter layouts are in the workspace
+    if (csr_only) {                                     // the column layout is: remember it either way
+        if (job->prepared == 2) panel_registry_put(key);
+        job->prepared = 1;
+    }
+    if (!aux_built) { pn.P = 1; fx.row.on = fx.col.on = 0; }
     if (!any_fx) fx.row.on = fx.col.on = 0;
     if ((fx.row.on || fx.col.on) && launch_sparse_fx_begin(a, fx, st) != hipSuccess) return GLM_EHIP;
     for (int k = 0; k < iters; ++k) {

@@ -32,6 +32,19 @@ hipError_t launch_sparse_panel_build(const SparseArgs &a, const SparsePanels &pn
 hipError_t launch_sparse_iteration_panels(const SparseArgs &a, const SparsePanels &pn, int k, hipEvent_t *ev,
                                           hipStream_t st);
 
+// ---- column layout built by the library (glm_sparse_csc.hip), for callers that give CSR only ----
+struct SparseCsc {
+    long long *col_ptr;              // [D + 1]
+    int *row_idx;                    // [nnz]
+    float *col_val;                  // [nnz]
+    int *keys[2];                    // [nnz] each: column indices, the sort's two buffers
+    unsigned long long *vals[2];     // [nnz] each: (row << 32) | value bits
+    void *temp;                      // scratch of the sort
+    size_t temp_bytes;
+};
+size_t sparse_csc_temp_bytes(long long nnz);
+hipError_t launch_sparse_csc_build(const SparseArgs &a, const SparseCsc &c, hipStream_t st);
+
 // ---- scatter into LDS with fixed-point sums (glm_sparse_fx.hip) --------------------------------
 constexpr int kFxPanel = 16384;              // outputs per panel: their 64-bit sums fill 128 KB of LDS
 constexpr int kFxMaxPanels = 256;            // bins of the split that builds the layout

@@ -292,22 +292,30 @@ class SparseJob:
 
     def __init__(self, row_ptr, col_idx, row_val, col_ptr, row_idx, col_val, y, w, loss: int, lam: float,
                  step: float, hist_cap: int, schedule: int = 0):
-        for t, dt in ((row_ptr, torch.int64), (col_ptr, torch.int64), (col_idx, torch.int32),
-                      (row_idx, torch.int32), (row_val, torch.float32), (col_val, torch.float32),
-                      (y, torch.float32), (w, torch.float32)):
+        """col_ptr, row_idx and col_val may all be None: the library then builds the column layout itself."""
+        csr_only = col_ptr is None and row_idx is None and col_val is None
+        if not csr_only and (col_ptr is None or row_idx is None or col_val is None):
+            raise ValueError("give the whole column layout or none of it")
+        checks = [(row_ptr, torch.int64), (col_idx, torch.int32), (row_val, torch.float32), (y, torch.float32),
+                  (w, torch.float32)]
+        if not csr_only:
+            checks += [(col_ptr, torch.int64), (row_idx, torch.int32), (col_val, torch.float32)]
+        for t, dt in checks:
             if t.dtype != dt or not t.is_contiguous():
                 raise TypeError("sparse job tensors must be contiguous int64 / int32 / float32 as declared")
         N, D, nnz = int(y.shape[0]), int(w.shape[0]), int(col_idx.shape[0])
-        if row_ptr.shape != (N + 1,) or col_ptr.shape != (D + 1,) or row_idx.shape != (nnz,) \
-                or row_val.shape != (nnz,) or col_val.shape != (nnz,):
+        if row_ptr.shape != (N + 1,) or row_val.shape != (nnz,):
+            raise ValueError("inconsistent sparse array shapes")
+        if not csr_only and (col_ptr.shape != (D + 1,) or row_idx.shape != (nnz,) or col_val.shape != (nnz,)):
             raise ValueError("inconsistent sparse array shapes")
         dev = y.device
         self.tensors = (row_ptr, col_idx, row_val, col_ptr, row_idx, col_val, y)
         self.w = w
         self.grad = torch.zeros(D, dtype=torch.float32, device=dev)
         self.loss_hist = torch.zeros(max(int(hist_cap), 1), dtype=torch.float32, device=dev)
+        ptr = lambda t: None if t is None else t.data_ptr()
         self.c = glm_sparse_job_t(row_ptr.data_ptr(), col_idx.data_ptr(), row_val.data_ptr(),
-                                  col_ptr.data_ptr(), row_idx.data_ptr(), col_val.data_ptr(), y.data_ptr(),
+                                  ptr(col_ptr), ptr(row_idx), ptr(col_val), y.data_ptr(),
                                   w.data_ptr(), self.grad.data_ptr(), self.loss_hist.data_ptr(), N, D, nnz,
                                   int(loss), float(lam), float(step), 0, int(hist_cap), 0, int(schedule))
 

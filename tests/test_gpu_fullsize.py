@@ -5,6 +5,8 @@ large cases are checked per step: the oracle is evaluated (all host cores, chunk
 very fp32 iterate the GPU iteration started from, for a few iterations spread over the run.
 Inputs are drawn on the GPU and copied to the host, so both sides read the same bits.
 """
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -159,6 +161,16 @@ def test_sparse_config_full_size_steps():
             assert np.max(np.abs(got_g - g)) <= REL_TOL * np.max(np.abs(g))
     h = job.history().cpu().numpy()
     assert abs(h[0] - np.log(2.0)) < 2e-6 and np.all(np.diff(h) < 0)
+    _say("[case] sparse full size: the same matrix given as CSR alone (column layout built on the device)")
+    alone = glm.SparseJob(p.row_ptr, p.col_idx, p.row_val, None, None, None, p.y, p.w0.clone(), p.loss, p.lam, p.eta, 2)
+    del ws
+    ws2 = glm.alloc_sparse_workspace(alone)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    glm.glm_step_sparse(alone, 2, ws2)
+    torch.cuda.synchronize()
+    _say(f"[case] sparse full size: first call with the layouts built, 2 iterations: {time.perf_counter() - t0:.3f} s")
+    assert alone.loss_hist[:2].cpu().numpy().tobytes() == job.loss_hist[:2].cpu().numpy().tobytes()
 
 
 def test_kmeans_config_full_size_steps():

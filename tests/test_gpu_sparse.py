@@ -341,3 +341,75 @@ def test_scatter_path_reruns_split_calls_and_duplicates():
     jb = job()
     _check_steps(jb, (rp, ci, rv), y, D, synth.SQUARED, 1e-4, 1e-6, 2, "scatter duplicates")
     del coo
+
+
+# ---- CSR alone: the library builds the column layout itself -------------------------------------
+
+def _csr_only_twin(job):
+    """The same job without its column arrays (fresh weights, gradient and history)."""
+    rp, ci, rv, _, _, _, y = job.tensors
+    return glm.SparseJob(rp, ci, rv, None, None, None, y, torch.zeros_like(job.w), job.c.loss, job.c.lambda_,
+                         job.c.step, job.c.hist_cap, job.c.schedule)
+
+
+def _same_bits(a, b):
+    return (a.loss_hist.cpu().numpy().tobytes() == b.loss_hist.cpu().numpy().tobytes()
+            and a.w.cpu().numpy().tobytes() == b.w.cpu().numpy().tobytes()
+            and a.grad.cpu().numpy().tobytes() == b.grad.cpu().numpy().tobytes())
+
+
+@pytest.mark.parametrize("which", ["segmented sums", "row panels", "scatter"])
+def test_csr_only_input_equals_csr_plus_csc_bit_for_bit_and_matches_oracle(which):
+    """The column layout the library builds is the stable sort of the entries by column, which is what
+    the generators hand over as CSC: the two ways in must then agree bit for bit, on each of the three
+    internal paths; the CSR-only job is also held to the oracle step by step."""
+    _say(f"[case] sparse, CSR alone ({which})")
+    if which == "segmented sums":
+        p = synth.make_sparse_glm(synth.LOGISTIC, 5000, 700, 9.0, seed=5, lam=1e-3, eta=0.5, K=4)
+        full = _job_from_problem(p)
+        csr, y, D, loss, lam, eta = (p.row_ptr.numpy(), p.col_idx.numpy(), p.row_val.numpy()), p.y.numpy(), p.D, p.loss, p.lam, 0.5
+    elif which == "row panels":
+        A = _tall(13)
+        rng = np.random.default_rng(4)
+        y = _labels(synth.SQUARED, A.shape[0], rng)
+        full, csr = _job_from_scipy(A, y, synth.SQUARED, 1e-4, 0.05, 4)
+        D, loss, lam, eta = A.shape[1], synth.SQUARED, 1e-4, 0.05
+    else:
+        p = synth.make_sparse_glm(synth.LOGISTIC, 300_000, 200_000, 20.0, seed=43, lam=1e-4, eta=0.5, K=4)
+        full = _job_from_problem(p)
+        csr, y, D, loss, lam, eta = (p.row_ptr.numpy(), p.col_idx.numpy(), p.row_val.numpy()), p.y.numpy(), p.D, p.loss, p.lam, 0.5
+    alone = _csr_only_twin(full)
+    assert glm.glm_sparse_workspace_bytes(alone) > glm.glm_sparse_workspace_bytes(full)
+    ws_full, ws_alone = glm.alloc_sparse_workspace(full), glm.alloc_sparse_workspace(alone)
+    glm.glm_step_sparse(full, 3, ws_full)
+    glm.glm_step_sparse(alone, 2, ws_alone)          # split calls: the second one finds the layout in the workspace
+    assert alone.c.prepared == 1
+    glm.glm_step_sparse(alone, 1, ws_alone)
+    torch.cuda.synchronize()
+    assert _same_bits(full, alone), which
+    fresh = _csr_only_twin(full)
+    _check_steps(fresh, csr, y, D, loss, lam, eta, 2, f"csr only, {which}")
+
+
+def test_csr_only_hand_built_structures_and_errors():
+    _say("[case] sparse, CSR alone: duplicates, empty rows and columns, unsorted columns inside a row, nnz = 0")
+    T = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    rp = np.array([0, 3, 3, 6, 7], np.int64)                    # row 1 empty
+    ci = np.array([4, 0, 4, 2, 0, 2, 5], np.int32)              # column 4 twice in row 0, columns not ascending, 1 and 3 empty
+    rv = np.array([0.5, -1.0, 0.25, 2.0, 1.5, -0.5, 1.0], np.float32)
+    y = np.array([1, 0, 1, 0], np.float32)
+    job = glm.SparseJob(T(rp), T(ci), T(rv), None, None, None, T(y), torch.zeros(6, device="cuda"), synth.LOGISTIC,
+                        1e-2, 0.5, 4)
+    _check_steps(job, (rp, ci, rv), y, 6, synth.LOGISTIC, 1e-2, 0.5, 4, "csr only, hand-built")
+    empty = glm.SparseJob(T(np.zeros(4, np.int64)), T(np.zeros(0, np.int32)), T(np.zeros(0, np.float32)), None, None,
+                          None, T(np.array([1, 0, 1], np.float32)), torch.zeros(5, device="cuda"), synth.LOGISTIC, 0.0,
+                          0.5, 2)
+    glm.glm_step_sparse(empty, 2, glm.alloc_sparse_workspace(empty))
+    torch.cuda.synchronize()
+    assert abs(empty.loss_hist[0].item() - np.log(2.0)) < 1e-6 and empty.grad.abs().sum().item() == 0
+    half = glm.SparseJob(T(rp), T(ci), T(rv), None, None, None, T(y), torch.zeros(6, device="cuda"), synth.LOGISTIC,
+                         1e-2, 0.5, 4)
+    half.c.row_idx = T(np.zeros(7, np.int32)).data_ptr()         # a column array without the others
+    with pytest.raises(glm.GlmError) as e:
+        glm.glm_step_sparse(half, 1, glm.alloc_sparse_workspace(job))
+    assert e.value.status == glm.GLM_EINVAL
