@@ -112,6 +112,39 @@ __device__ bool transformed_start(const int cls, const int m, const double *__re
     return true;
 }
 
+// Error of the curve (p, off) on the window, +inf if it is not admissible, together with the
+// Gauss-Newton normal equations J^T W J, J^T W r there (J: derivatives of the curve by p).
+struct NormalEq { double A00, A01, A02, A11, A12, A22, g0, g1, g2; };
+__device__ double normal_equations(const int cls, const int m, const double *__restrict__ l,
+                                   const double *__restrict__ w, const double inv, const Lin p, const double off,
+                                   NormalEq &q) {
+    double A00 = 0, A01 = 0, A02 = 0, A11 = 0, A12 = 0, A22 = 0, g0 = 0, g1 = 0, g2 = 0, s = 0;
+    for (int i = 0; i < m; ++i) {
+        const double t = (double)i * inv;
+        double f, j0, j1, j2;
+        if (cls == GLM_CURVE_SUBLINEAR) {
+            const double den = (p.a * t + p.b) * t + p.c;
+            if (!(den > 0.0) || !isfinite(den)) return INFINITY;
+            const double iq = 1.0 / den;
+            f = iq + off;
+            j2 = -(iq * iq); j1 = j2 * t; j0 = j1 * t;
+        } else {
+            const double E = exp(p.a * t + p.b);
+            f = E + off;
+            j0 = E * t; j1 = E; j2 = 0.0;
+        }
+        const double wi = w[i];
+        const double r = f - l[i];
+        const double wr = wi * r;
+        s += wr * r;
+        g0 += j0 * wr; g1 += j1 * wr; g2 += j2 * wr;
+        const double w0 = wi * j0, w1 = wi * j1;
+        A00 += w0 * j0; A01 += w0 * j1; A02 += w0 * j2; A11 += w1 * j1; A12 += w1 * j2; A22 += wi * j2 * j2;
+    }
+    q.A00 = A00; q.A01 = A01; q.A02 = A02; q.A11 = A11; q.A12 = A12; q.A22 = A22; q.g0 = g0; q.g1 = g1; q.g2 = g2;
+    return isfinite(s) ? s : INFINITY;
+}
+
 // phi(e): damped Gauss-Newton on the parameters other than e.  Starts from p when `warm` and p is
 // admissible, else from the transformed problem's solution; with `both`, from whichever of the two
 // has the lower error; if neither is admissible, from the constant curve.  Returns phi, p = minimiser.
@@ -141,49 +174,35 @@ __device__ double profile(const int cls, const int m, const double *__restrict__
             if (!(sse < INFINITY)) return INFINITY;
         }
     }
+    // One pass over the window gives the error AND the Gauss-Newton normal equations at a point, so a
+    // trial step costs one pass: if it is accepted its equations are already there for the next step.
+    NormalEq cur;
+    sse = normal_equations(cls, m, l, w, inv, p, off, cur);
+    if (!(sse < INFINITY)) return INFINITY;
     double mu = 1e-4;
     for (int it = 0; it < max_iter; ++it) {
-        // normal equations J^T W J, J^T W r at p
-        double A00 = 0, A01 = 0, A02 = 0, A11 = 0, A12 = 0, A22 = 0, g0 = 0, g1 = 0, g2 = 0;
-        for (int i = 0; i < m; ++i) {
-            const double t = (double)i * inv;
-            double f, j0, j1, j2;
-            if (cls == GLM_CURVE_SUBLINEAR) {
-                const double q = (p.a * t + p.b) * t + p.c;
-                const double iq = 1.0 / q;
-                f = iq + off;
-                j2 = -(iq * iq); j1 = j2 * t; j0 = j1 * t;
-            } else {
-                const double E = exp(p.a * t + p.b);
-                f = E + off;
-                j0 = E * t; j1 = E; j2 = 0.0;
-            }
-            const double wi = w[i];
-            const double wr = wi * (f - l[i]);
-            g0 += j0 * wr; g1 += j1 * wr; g2 += j2 * wr;
-            const double w0 = wi * j0, w1 = wi * j1;
-            A00 += w0 * j0; A01 += w0 * j1; A02 += w0 * j2; A11 += w1 * j1; A12 += w1 * j2; A22 += wi * j2 * j2;
-        }
-        const double d0 = A00 > 0.0 ? sqrt(A00) : 1.0, d1 = A11 > 0.0 ? sqrt(A11) : 1.0,
-                     d2 = (n == 3 && A22 > 0.0) ? sqrt(A22) : 1.0;
-        const double a01 = A01 / (d0 * d1), a02 = A02 / (d0 * d2), a12 = A12 / (d1 * d2);
-        const double b0 = -g0 / d0, b1 = -g1 / d1, b2 = -g2 / d2;
+        const int nn = n;
+        const double d0 = cur.A00 > 0.0 ? sqrt(cur.A00) : 1.0, d1 = cur.A11 > 0.0 ? sqrt(cur.A11) : 1.0,
+                     d2 = (nn == 3 && cur.A22 > 0.0) ? sqrt(cur.A22) : 1.0;
+        const double a01 = cur.A01 / (d0 * d1), a02 = cur.A02 / (d0 * d2), a12 = cur.A12 / (d1 * d2);
+        const double b0 = -cur.g0 / d0, b1 = -cur.g1 / d1, b2 = -cur.g2 / d2;
         bool moved = false, done = false;
         while (mu <= 1e10) {
             double x0, x1, x2;
-            if (solve_scaled(n, mu, a01, a02, a12, b0, b1, b2, x0, x1, x2)) {
+            if (solve_scaled(nn, mu, a01, a02, a12, b0, b1, b2, x0, x1, x2)) {
                 Lin c;
-                const double s0 = x0 / d0, s1 = x1 / d1, s2 = n == 3 ? x2 / d2 : 0.0;
+                const double s0 = x0 / d0, s1 = x1 / d1, s2 = nn == 3 ? x2 / d2 : 0.0;
                 c.a = p.a + s0; c.b = p.b + s1; c.c = p.c + s2;
-                const double s_new = window_error(cls, m, l, w, inv, c, off);
+                NormalEq nxt;
+                const double s_new = normal_equations(cls, m, l, w, inv, c, off, nxt);
                 if (s_new <= sse) {
                     double rel = fmax(fabs(s0) / (fabs(c.a) + 1e-30), fabs(s1) / (fabs(c.b) + 1e-30));
-                    if (n == 3) rel = fmax(rel, fabs(s2) / (fabs(c.c) + 1e-30));
+                    if (nn == 3) rel = fmax(rel, fabs(s2) / (fabs(c.c) + 1e-30));
                     // decrease promised by the linearised model: -(g.s) - s.A.s/2 = b.x - (x.x + 2 (a01 x0 x1 + ...))/2
                     const double promised = (b0 * x0 + b1 * x1 + b2 * x2) -
                         0.5 * (x0 * x0 + x1 * x1 + x2 * x2 + 2.0 * (a01 * x0 * x1 + a02 * x0 * x2 + a12 * x1 * x2));
                     done = rel <= 1e-13 || s_new == sse || promised <= tol * s_new || s_new <= 1e-28;
-                    p = c; sse = s_new; moved = true;
+                    p = c; sse = s_new; cur = nxt; moved = true;
                     mu = fmax(mu * 0.1, 1e-14);
                     break;
                 }
