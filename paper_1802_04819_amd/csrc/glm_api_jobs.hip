@@ -21,7 +21,7 @@ struct SparseLayout {
     size_t seg0R, seg0C, closes, headless, slast, H, T, z, r, lossP, wwP, total;
     size_t pp, ptr2, bsum, idx2, val2, seg0P, gs2, flag;     // row-panelled column layout (P > 1)
     size_t fx_slots, fx_cnt, fx_bsum;                        // fixed-point scatter path
-    size_t fx_gidx[2], fx_loc[2], fx_val[2], fx_pstart[2], fx_shift[2], fx_cstart[2], fx_part[2];   // [0] row pass, [1] column pass
+    size_t fx_gidx[2], fx_loc[2], fx_val[2], fx_pstart[2], fx_shift[2], fx_part[2];   // [0] row pass, [1] column pass
     FxPass fx_row, fx_col;
     long long nch;
     int P;
@@ -61,7 +61,7 @@ SparseLayout make_sparse_layout(long long N, long long D, long long nnz, bool cs
         L.gs2 = off;   off = api_align_up(off + sizeof(float) * S2);
     }
     L.fx_slots = L.fx_cnt = L.fx_bsum = off;
-    for (int i = 0; i < 2; ++i) L.fx_gidx[i] = L.fx_loc[i] = L.fx_val[i] = L.fx_pstart[i] = L.fx_shift[i] = L.fx_cstart[i] = L.fx_part[i] = off;
+    for (int i = 0; i < 2; ++i) L.fx_gidx[i] = L.fx_loc[i] = L.fx_val[i] = L.fx_pstart[i] = L.fx_shift[i] = L.fx_part[i] = off;
     if (any_fx) {
         const FxPass *ps[2] = {&L.fx_row, &L.fx_col};
         long long maxP = 1, ntiles = 1;
@@ -79,8 +79,7 @@ SparseLayout make_sparse_layout(long long N, long long D, long long nnz, bool cs
             L.fx_val[i] = off;    off = api_align_up(off + sizeof(float) * cap);
             L.fx_shift[i] = off;  off = api_align_up(off + sizeof(long long) * (size_t)ps[i]->P);
             L.fx_pstart[i] = off; off = api_align_up(off + sizeof(long long) * ((size_t)ps[i]->P + 1));
-            L.fx_cstart[i] = off; off = api_align_up(off + sizeof(long long) * ((size_t)ps[i]->P + 1));
-            L.fx_part[i] = off;   off = api_align_up(off + sizeof(long long) * (size_t)ps[i]->max_chunks * kFxPanel);
+            L.fx_part[i] = off;   off = api_align_up(off + sizeof(long long) * (size_t)ps[i]->slices * kFxPanel);
         }
     }
     L.csc_ptr = L.csc_idx = L.csc_val = L.csc_keys[0] = L.csc_keys[1] = L.csc_vals[0] = L.csc_vals[1] = L.csc_temp = off;
@@ -217,7 +216,6 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
             ps[i]->loc = reinterpret_cast<unsigned short *>(base + L.fx_loc[i]);
             ps[i]->val = reinterpret_cast<float *>(base + L.fx_val[i]);
             ps[i]->pstart = reinterpret_cast<long long *>(base + L.fx_pstart[i]);
-            ps[i]->cstart = reinterpret_cast<long long *>(base + L.fx_cstart[i]);
             ps[i]->shift = reinterpret_cast<long long *>(base + L.fx_shift[i]);
             ps[i]->part = reinterpret_cast<long long *>(base + L.fx_part[i]);
         }

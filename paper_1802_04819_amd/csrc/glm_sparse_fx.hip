@@ -20,10 +20,10 @@
 // output index, position in the source layout).  For the row pass the source is the caller's
 // column layout (CSC: within a panel, columns ascend), for the column pass the row layout (CSR).
 // Per entry: the index into the gathered vector (int32), the output index inside its panel
-// (uint16) and the value (fp32): 10 bytes.  A panel is shared by as many blocks as its entries
-// call for (contiguous chunks of a fixed length: popular columns make some panels hundreds of
-// times larger than others); each block writes its 16384 partial sums, a small kernel adds the
-// slices of a panel and converts to fp32.
+// (uint16) and the value (fp32): 10 bytes.  The padded entry stream of all panels is cut into equal
+// spans, one per block (popular columns make some panels hundreds of times larger than others, so
+// work is shared by entries, not by panels): a block walks the panels its span touches and writes
+// 16384 partial sums for each; a small kernel adds the slices of a panel and converts to fp32.
 #include "sparse_internal.h"
 
 #include <cmath>
@@ -105,27 +105,22 @@ __global__ __launch_bounds__(256) void fx_scan_add_kernel(long long n, const lon
 
 // One thread (P <= 256): pstart[p] = first entry of panel p in the padded layout (every panel
 // starts at a multiple of four and is filled up to one with zero entries), shift[p] = how far its
-// entries move up for that, cstart[p] = first block of panel p when every block takes `chunk`
-// entries.  cnt[p * ntiles] is the exact start of panel p (p == P: the total).
-__global__ void fx_pstart_kernel(const long long *__restrict__ cnt, long long ntiles, int P, long long chunk,
+// entries move up for that.  cnt[p * ntiles] is the exact start of panel p (p == P: the total).
+__global__ void fx_pstart_kernel(const long long *__restrict__ cnt, long long ntiles, int P,
                                  long long *__restrict__ pstart, long long *__restrict__ shift,
-                                 long long *__restrict__ cstart, int *__restrict__ gidx,
-                                 unsigned short *__restrict__ loc, float *__restrict__ val) {
+                                 int *__restrict__ gidx, unsigned short *__restrict__ loc, float *__restrict__ val) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    long long blocks = 0, at = 0;
+    long long at = 0;
     for (int p = 0; p < P; ++p) {
         const long long s = cnt[(long long)p * ntiles];
         const long long len = cnt[(long long)(p + 1) * ntiles] - s;
         const long long padded = (len + 3) & ~3LL;
         pstart[p] = at;
         shift[p] = at - s;
-        cstart[p] = blocks;
         for (long long q = len; q < padded; ++q) { gidx[at + q] = 0; loc[at + q] = 0; val[at + q] = 0.0f; }
         at += padded;
-        blocks += (padded + chunk - 1) / chunk;
     }
     pstart[P] = at;
-    cstart[P] = blocks;
 }
 
 // largest m in [lo, hi] with ptr[m] <= e  (ptr[lo] <= e is given)
@@ -250,56 +245,58 @@ __device__ __forceinline__ int fx_exponent(unsigned maxval_bits, unsigned maxvec
     return e < -126 ? -126 : e > 126 ? 126 : e;
 }
 
+// The layout is the library's own, but it lives in the caller's workspace: whatever that memory
+// holds, panel starts are forced into [0, cap] and to multiples of four before they are used.
+__device__ __forceinline__ long long fx_panel_start(const long long *__restrict__ pstart, int p, long long cap) {
+    const long long s = pstart[p] & ~3LL;
+    return s < 0 ? 0 : s > cap ? cap : s;
+}
+
 __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
     const int *__restrict__ gidx, const unsigned short *__restrict__ loc, const float *__restrict__ val,
     const float *__restrict__ vec, long long vec_len, long long nnz, const long long *__restrict__ pstart,
-    const long long *__restrict__ cstart, int P, long long chunk, unsigned *slots, int vec_slot, int len_slot,
-    int e_slot, long long *__restrict__ part) {
+    int P, long long span, unsigned *slots, int vec_slot, int len_slot, int e_slot, long long *__restrict__ part) {
     extern __shared__ unsigned long long fx_sums[];    // [kFxPanel]
-    __shared__ int s_panel;
     const int tid = threadIdx.x;
-    // which panel this block belongs to: the last p with cstart[p] <= blockIdx (blocks past the
-    // last panel's have nothing to do: the grid is an upper bound known from the shape alone)
-    if (tid == 0) {
-        int p = -1;
-        if ((long long)blockIdx.x < cstart[P]) {
-            int lo = 0, hi = P - 1;
-            while (lo < hi) {
-                const int mid = lo + (hi - lo + 1) / 2;
-                if (cstart[mid] <= (long long)blockIdx.x) lo = mid; else hi = mid - 1;
-            }
-            p = lo;
-        }
-        s_panel = p;
-    }
-    for (int i = tid; i < kFxPanel; i += kFxThreads) fx_sums[i] = 0ull;
     const int e2 = fx_exponent(slots[kFxSlotMaxVal], slots[vec_slot], slots[len_slot]);
     if (blockIdx.x == 0 && tid == 0) slots[e_slot] = (unsigned)e2;          // for the kernel that converts back
     const float scale = __builtin_ldexpf(1.0f, e2);
     const unsigned vmax = (unsigned)(vec_len - 1);
-    __syncthreads();
-    const int p = s_panel;
-    if (p < 0) return;                                 // uniform over the block
     const long long cap = (nnz + 4LL * P) & ~3LL;     // the arrays hold nnz + 4 P entries
-    long long s0 = pstart[p] & ~3LL, s1 = pstart[p + 1] & ~3LL;
-    s0 = s0 < 0 ? 0 : s0 > cap ? cap : s0;
-    s1 = s1 < s0 ? s0 : s1 > cap ? cap : s1;
-    const long long c = (long long)blockIdx.x - cstart[p];
-    long long b0 = s0 + c * chunk, b1 = b0 + chunk;
-    b0 = b0 > s1 ? s1 : b0;
-    b1 = b1 > s1 ? s1 : b1;
-    // Two loads stand between an entry and its sum: the entry itself, then the element of the
-    // other vector it points at.  The entries of the next round are requested before the current
-    // round's elements are waited for, so that one latency is paid per round, not two.  A lane
-    // takes four consecutive entries with one 16-byte load per array (b0 and b1 are multiples
-    // of four: panels are padded, chunks are multiples of 4096).
+    const long long total = fx_panel_start(pstart, P, cap);
+    const long long r0 = (long long)blockIdx.x * span;
+    const long long r1 = r0 + span < total ? r0 + span : total;
+    if (r0 >= total) return;                           // uniform over the block
+    // first panel of the span: the last p with pstart[p] <= r0 (the same for every thread)
+    int p = 0;
+    {
+        int lo = 0, hi = P - 1;
+        while (lo < hi) {
+            const int mid = lo + (hi - lo + 1) / 2;
+            if (fx_panel_start(pstart, mid, cap) <= r0) lo = mid; else hi = mid - 1;
+        }
+        p = lo;
+    }
     typedef float f4 __attribute__((ext_vector_type(4)));
     typedef int i4 __attribute__((ext_vector_type(4)));
     typedef unsigned short us4 __attribute__((ext_vector_type(4)));
     const i4 *__restrict__ g4p = reinterpret_cast<const i4 *>(gidx);
     const us4 *__restrict__ l4p = reinterpret_cast<const us4 *>(loc);
     const f4 *__restrict__ v4p = reinterpret_cast<const f4 *>(val);
-    i4 g[kFxUnroll]; us4 l[kFxUnroll]; f4 v[kFxUnroll];
+    const long long stride = (long long)kFxThreads * kFxUnroll;
+    for (; p < P; ++p) {
+        const long long s0 = fx_panel_start(pstart, p, cap), s1 = fx_panel_start(pstart, p + 1, cap);
+        if (s0 >= r1) break;
+        const long long b0 = s0 > r0 ? s0 : r0, b1 = s1 < r1 ? s1 : r1;
+        if (b1 <= b0) continue;                        // an empty panel (or a start out of order)
+        for (int i = tid; i < kFxPanel; i += kFxThreads) fx_sums[i] = 0ull;
+        __syncthreads();
+        // Two loads stand between an entry and its sum: the entry itself, then the element of the
+        // other vector it points at.  The entries of the next round are requested before the current
+        // round's elements are waited for, so that one latency is paid per round, not two.  A lane
+        // takes four consecutive entries with one 16-byte load per array (b0 and b1 are multiples
+        // of four: panels are padded, spans are multiples of 4096).
+        i4 g[kFxUnroll]; us4 l[kFxUnroll]; f4 v[kFxUnroll];
 #define SLAQ_FX_LOAD(Q)                                                                      \
     _Pragma("unroll") for (int u = 0; u < kFxUnroll; ++u) {                                  \
         const long long q_ = (Q) + (long long)u * kFxThreads;                                \
@@ -308,43 +305,46 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
         l[u] = ok_ ? __builtin_nontemporal_load(l4p + q_) : us4{0, 0, 0, 0};                 \
         v[u] = ok_ ? __builtin_nontemporal_load(v4p + q_) : f4{0.0f, 0.0f, 0.0f, 0.0f};      \
     }
-    const long long q1 = b1 >> 2;
-    const long long stride = (long long)kFxThreads * kFxUnroll;
-    long long q = (b0 >> 2) + tid;
-    if (q < q1) SLAQ_FX_LOAD(q)
-    for (; q < q1; q += stride) {
-        f4 x[kFxUnroll], vv[kFxUnroll]; us4 ll[kFxUnroll];
+        const long long q1 = b1 >> 2;
+        long long q = (b0 >> 2) + tid;
+        if (q < q1) SLAQ_FX_LOAD(q)
+        for (; q < q1; q += stride) {
+            f4 x[kFxUnroll], vv[kFxUnroll]; us4 ll[kFxUnroll];
 #pragma unroll
-        for (int u = 0; u < kFxUnroll; ++u) {
-            // the layout is the library's own, but it lives in the caller's workspace: keep every
-            // index inside its array whatever the memory holds
+            for (int u = 0; u < kFxUnroll; ++u) {
+                // keep every index inside its array whatever the memory holds
 #pragma unroll
-            for (int c = 0; c < 4; ++c) x[u][c] = vec[min((unsigned)g[u][c], vmax)];
-            vv[u] = v[u]; ll[u] = l[u];
-        }
-        if (q + stride < q1) SLAQ_FX_LOAD(q + stride)
+                for (int c = 0; c < 4; ++c) x[u][c] = vec[min((unsigned)g[u][c], vmax)];
+                vv[u] = v[u]; ll[u] = l[u];
+            }
+            if (q + stride < q1) SLAQ_FX_LOAD(q + stride)
 #pragma unroll
-        for (int u = 0; u < kFxUnroll; ++u) {
-            if (q + (long long)u * kFxThreads < q1) {
+            for (int u = 0; u < kFxUnroll; ++u) {
+                if (q + (long long)u * kFxThreads < q1) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const long long t = __float2ll_rn((vv[u][c] * x[u][c]) * scale);
-                    atomicAdd(&fx_sums[(unsigned)ll[u][c] & (unsigned)(kFxPanel - 1)], (unsigned long long)t);
+                    for (int c = 0; c < 4; ++c) {
+                        const long long t = __float2ll_rn((vv[u][c] * x[u][c]) * scale);
+                        atomicAdd(&fx_sums[(unsigned)ll[u][c] & (unsigned)(kFxPanel - 1)], (unsigned long long)t);
+                    }
                 }
             }
         }
-    }
 #undef SLAQ_FX_LOAD
-    __syncthreads();
-    long long *__restrict__ dst = part + (long long)blockIdx.x * kFxPanel;
-    for (int i = tid; i < kFxPanel; i += kFxThreads) dst[i] = (long long)fx_sums[i];
+        __syncthreads();
+        // slice blockIdx + p: both count upwards along the stream, so the slices of a panel are
+        // neighbours and no two (block, panel) pairs share one
+        long long *__restrict__ dst = part + ((long long)blockIdx.x + p) * kFxPanel;
+        for (int i = tid; i < kFxPanel; i += kFxThreads) dst[i] = (long long)fx_sums[i];
+        __syncthreads();
+    }
 }
 
 // out[i] = (sum over the slices of i's panel) * 2^-e.  A block takes 256 outputs, 32 at a time;
 // its eight groups of 32 lanes share the slices (a popular panel has hundreds), integer sums in
 // any order.
 __global__ __launch_bounds__(256) void fx_finish_kernel(const long long *__restrict__ part,
-                                                        const long long *__restrict__ cstart, int P, long long out_len,
+                                                        const long long *__restrict__ pstart, int P, long long span,
+                                                        long long nnz, long long out_len,
                                                         const unsigned *__restrict__ slots, int e_slot,
                                                         float *__restrict__ out) {
     __shared__ long long red[8][8][32];
@@ -352,7 +352,10 @@ __global__ __launch_bounds__(256) void fx_finish_kernel(const long long *__restr
     const long long base = blockIdx.x * 256LL;                 // 256 divides the panel: a block is in one panel
     if (base >= out_len) return;
     const int p = (int)(base / kFxPanel);
-    const long long c0 = cstart[p], c1 = cstart[p < P ? p + 1 : p];
+    // the blocks whose spans meet the panel's entries [s0, s1): floor(s0 / span) .. floor((s1 - 1) / span)
+    const long long cap = (nnz + 4LL * P) & ~3LL;
+    const long long s0 = fx_panel_start(pstart, p, cap), s1 = fx_panel_start(pstart, p + 1, cap);
+    const long long c0 = s0 / span + p, c1 = s1 > s0 ? (s1 - 1) / span + p + 1 : c0;
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
         const long long i = base + g * 32 + o32;
@@ -398,8 +401,8 @@ hipError_t fx_build_pass(const FxPass &ps, const long long *ptr, long long M, co
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(fx_scan_add_kernel, dim3((unsigned)((n + 1 + 255) / 256)), dim3(256), 0, st, n, bsum, nb, cnt);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_pstart_kernel, dim3(1), dim3(64), 0, st, cnt, ntiles, ps.P, ps.chunk, ps.pstart, ps.shift,
-                       ps.cstart, ps.gidx, ps.loc, ps.val);
+    hipLaunchKernelGGL(fx_pstart_kernel, dim3(1), dim3(64), 0, st, cnt, ntiles, ps.P, ps.pstart, ps.shift, ps.gidx,
+                       ps.loc, ps.val);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(fx_scatter_kernel, dim3(tb), dim3(256), 0, st, ptr, M, idx, val, nnz, ntiles, ps.P, cnt, ps.shift,
                        ps.gidx, ps.loc, ps.val);
@@ -408,8 +411,7 @@ hipError_t fx_build_pass(const FxPass &ps, const long long *ptr, long long M, co
 
 }  // namespace
 
-// Which passes take this path, with how many panels and blocks per panel.  A function of the
-// shape alone.
+// Which passes take this path, with how many panels and blocks.  A function of the shape alone.
 void sparse_fx_plan(long long N, long long D, long long nnz, FxPass *row, FxPass *col) {
     FxPass *ps[2] = {row, col};
     const long long out_len[2] = {N, D};
@@ -421,10 +423,13 @@ void sparse_fx_plan(long long N, long long D, long long nnz, FxPass *row, FxPass
         f.on = nnz >= kFxMinEntries && P <= kFxMaxPanels;
         if (!f.on) continue;
         f.P = (int)P;
-        // about a thousand blocks in all (four per compute unit), whatever the sizes of the panels
-        long long chunk = ((nnz + 1023) / 1024 + 4095) / 4096 * 4096;
-        f.chunk = chunk < 32768 ? 32768 : chunk;
-        f.max_chunks = (nnz + f.chunk - 1) / f.chunk + P + 1;      // panels are padded by up to three entries each
+        // one block per compute unit at most, each with an equal share of the padded stream (panels
+        // are padded by up to three entries each), whatever the sizes of the panels
+        const long long cap = (nnz + 4 * P) & ~3LL;
+        const long long span = ((cap + kFxBlocks - 1) / kFxBlocks + 4095) / 4096 * 4096;
+        f.span = span < 32768 ? 32768 : span;
+        f.blocks = (int)((cap + f.span - 1) / f.span);
+        f.slices = f.blocks + P;
         f.ntiles = (nnz + kFxTile - 1) / kFxTile;
     }
 }
@@ -467,13 +472,13 @@ hipError_t launch_sparse_fx_pass(const SparseFx &fx, bool row, const float *vec,
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fx_pass_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kFxPanel * 8);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_pass_kernel, dim3((unsigned)ps.max_chunks), dim3(kFxThreads), kFxPanel * 8, st, ps.gidx, ps.loc,
-                       ps.val, vec, vec_len, nnz, ps.pstart, ps.cstart, ps.P, ps.chunk, fx.slots,
+    hipLaunchKernelGGL(fx_pass_kernel, dim3((unsigned)ps.blocks), dim3(kFxThreads), kFxPanel * 8, st, ps.gidx, ps.loc,
+                       ps.val, vec, vec_len, nnz, ps.pstart, ps.P, ps.span, fx.slots,
                        row ? kFxSlotMaxW : kFxSlotMaxR, row ? kFxSlotLenRow : kFxSlotLenCol,
                        row ? kFxSlotERow : kFxSlotECol, ps.part);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_finish_kernel, dim3((unsigned)((ps.out_len + 255) / 256)), dim3(256), 0, st, ps.part, ps.cstart,
-                       ps.P, ps.out_len, fx.slots, row ? kFxSlotERow : kFxSlotECol, out);
+    hipLaunchKernelGGL(fx_finish_kernel, dim3((unsigned)((ps.out_len + 255) / 256)), dim3(256), 0, st, ps.part, ps.pstart,
+                       ps.P, ps.span, nnz, ps.out_len, fx.slots, row ? kFxSlotERow : kFxSlotECol, out);
     return hipGetLastError();
 }
 

@@ -49,14 +49,16 @@ hipError_t launch_sparse_csc_build(const SparseArgs &a, const SparseCsc &c, hipS
 constexpr int kFxPanel = 16384;              // outputs per panel: their 64-bit sums fill 128 KB of LDS
 constexpr int kFxMaxPanels = 256;            // bins of the split that builds the layout
 constexpr long long kFxMinEntries = 1LL << 22;
+constexpr int kFxBlocks = 256;               // at most one block per compute unit: the sums of a panel fill its LDS
 // device scalars of the path (unsigned [kFxSlots])
 enum : int { kFxSlotMaxW = 0, kFxSlotMaxR = 1, kFxSlotMaxVal = 2, kFxSlotERow = 3, kFxSlotECol = 4, kFxSlotLenRow = 5,
              kFxSlotLenCol = 6, kFxSlots = 8 };
 struct FxPass {
     int on;                  // this pass takes the path
     int P;                   // panels
-    long long chunk;         // entries per block: a panel of n entries is shared by ceil(n / chunk) blocks
-    long long max_chunks;    // upper bound of the number of blocks, known from the shape alone
+    long long span;          // consecutive entries of the padded stream per block (a multiple of 4096)
+    int blocks;              // blocks of the pass: block k streams entries [k span, (k + 1) span)
+    long long slices;        // blocks + P: block k writes its sums for panel p to slice k + p
     long long out_len;       // N for the row pass, D for the column pass
     long long ntiles;        // tiles of the split
     int *gidx;               // [nnz + 4 P] index into the gathered vector
@@ -65,8 +67,7 @@ struct FxPass {
                              //   filled up to one with zero entries, so that lanes load four at a time
     long long *pstart;       // [P + 1] first entry of each panel
     long long *shift;        // [P] how far the panel's entries moved up for that alignment
-    long long *cstart;       // [P + 1] first block of each panel
-    long long *part;         // [max_chunks, kFxPanel] fixed-point partial sums, one slice per block
+    long long *part;         // [slices, kFxPanel] fixed-point partial sums
 };
 struct SparseFx {
     FxPass row, col;
