@@ -497,9 +497,9 @@ def bench_sparse(args):
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None, "avg_launch_ms": avg_ms, "launches": len(ms),
                      "whole_step_GBps": alg * K / sec / 1e9,
-                     # the scatter layouts store 10 bytes per entry and product (value, gathered index, 16-bit
-                     # output index) against the 8 of the caller's layouts
-                     "executed_bytes_per_iteration": alg + 4.0 * p.nnz},
+                     # the scatter layouts store 8 bytes per entry and product (value; output index and
+                     # gathered index packed into one word), as many as the caller's layouts
+                     "executed_bytes_per_iteration": alg},
         "rerun_bit_identical": rerun_identical, "loss_first": float(hist[0]), "loss_last": float(hist[-1]),
     }
     if not args.no_cpu_baseline:

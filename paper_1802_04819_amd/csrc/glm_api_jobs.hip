@@ -21,7 +21,8 @@ struct SparseLayout {
     size_t seg0R, seg0C, closes, headless, slast, H, T, z, r, lossP, wwP, total;
     size_t pp, ptr2, bsum, idx2, val2, seg0P, gs2, flag;     // row-panelled column layout (P > 1)
     size_t fx_slots, fx_cnt, fx_bsum;                        // fixed-point scatter path
-    size_t fx_gidx[2], fx_loc[2], fx_val[2], fx_pstart[2], fx_shift[2], fx_part[2];   // [0] row pass, [1] column pass
+    size_t fx_ent[2], fx_val[2], fx_tbase[2], fx_pstart[2], fx_shift[2], fx_rstart[2], fx_rlen[2], fx_wsrc[2], fx_tfirst[2],
+        fx_part[2];                                          // [0] row pass, [1] column pass
     FxPass fx_row, fx_col;
     long long nch;
     int P;
@@ -61,23 +62,28 @@ SparseLayout make_sparse_layout(long long N, long long D, long long nnz, bool cs
         L.gs2 = off;   off = api_align_up(off + sizeof(float) * S2);
     }
     L.fx_slots = L.fx_cnt = L.fx_bsum = off;
-    for (int i = 0; i < 2; ++i) L.fx_gidx[i] = L.fx_loc[i] = L.fx_val[i] = L.fx_pstart[i] = L.fx_shift[i] = L.fx_part[i] = off;
+    for (int i = 0; i < 2; ++i)
+        L.fx_ent[i] = L.fx_val[i] = L.fx_tbase[i] = L.fx_pstart[i] = L.fx_shift[i] = L.fx_rstart[i] = L.fx_rlen[i] =
+            L.fx_wsrc[i] = L.fx_tfirst[i] = L.fx_part[i] = off;
     if (any_fx) {
         const FxPass *ps[2] = {&L.fx_row, &L.fx_col};
-        long long maxP = 1, ntiles = 1;
+        size_t ncnt = 1;
         for (int i = 0; i < 2; ++i)
-            if (ps[i]->on) { maxP = std::max<long long>(maxP, ps[i]->P); ntiles = ps[i]->ntiles; }
-        const size_t ncnt = (size_t)maxP * (size_t)ntiles;
+            if (ps[i]->on) ncnt = std::max(ncnt, (size_t)ps[i]->P * (size_t)ps[i]->ntiles);
         L.fx_slots = off; off = api_align_up(off + sizeof(unsigned) * kFxSlots);
         L.fx_cnt = off;   off = api_align_up(off + sizeof(long long) * (ncnt + 1));
         L.fx_bsum = off;  off = api_align_up(off + sizeof(long long) * ((ncnt + kScanBlock - 1) / kScanBlock + 2));
         for (int i = 0; i < 2; ++i) {
             if (!ps[i]->on) continue;
-            const size_t cap = (size_t)nnz + 4 * (size_t)ps[i]->P + 4;       // panels padded to multiples of four
-            L.fx_gidx[i] = off;   off = api_align_up(off + sizeof(int) * cap);
-            L.fx_loc[i] = off;    off = api_align_up(off + sizeof(unsigned short) * cap);
+            const size_t cap = (size_t)ps[i]->cap, runs = (size_t)ps[i]->P * (size_t)ps[i]->W;
+            L.fx_ent[i] = off;    off = api_align_up(off + sizeof(unsigned) * cap);
             L.fx_val[i] = off;    off = api_align_up(off + sizeof(float) * cap);
-            L.fx_shift[i] = off;  off = api_align_up(off + sizeof(long long) * (size_t)ps[i]->P);
+            L.fx_tbase[i] = off;  off = api_align_up(off + sizeof(int) * (cap / kFxRun));
+            L.fx_shift[i] = off;  off = api_align_up(off + sizeof(long long) * runs);
+            L.fx_rstart[i] = off; off = api_align_up(off + sizeof(long long) * runs);
+            L.fx_rlen[i] = off;   off = api_align_up(off + sizeof(long long) * runs);
+            L.fx_wsrc[i] = off;   off = api_align_up(off + sizeof(long long) * ((size_t)ps[i]->W + 1));
+            L.fx_tfirst[i] = off; off = api_align_up(off + sizeof(long long) * ((size_t)ps[i]->W + 1));
             L.fx_pstart[i] = off; off = api_align_up(off + sizeof(long long) * ((size_t)ps[i]->P + 1));
             L.fx_part[i] = off;   off = api_align_up(off + sizeof(long long) * (size_t)ps[i]->slices * kFxPanel);
         }
@@ -212,11 +218,15 @@ int glm_step_sparse(glm_sparse_job_t *job, int32_t iters, void *ws, size_t ws_by
     {
         FxPass *ps[2] = {&fx.row, &fx.col};
         for (int i = 0; i < 2; ++i) {
-            ps[i]->gidx = reinterpret_cast<int *>(base + L.fx_gidx[i]);
-            ps[i]->loc = reinterpret_cast<unsigned short *>(base + L.fx_loc[i]);
+            ps[i]->ent = reinterpret_cast<unsigned *>(base + L.fx_ent[i]);
             ps[i]->val = reinterpret_cast<float *>(base + L.fx_val[i]);
+            ps[i]->tbase = reinterpret_cast<int *>(base + L.fx_tbase[i]);
             ps[i]->pstart = reinterpret_cast<long long *>(base + L.fx_pstart[i]);
             ps[i]->shift = reinterpret_cast<long long *>(base + L.fx_shift[i]);
+            ps[i]->rstart = reinterpret_cast<long long *>(base + L.fx_rstart[i]);
+            ps[i]->rlen = reinterpret_cast<long long *>(base + L.fx_rlen[i]);
+            ps[i]->wsrc = reinterpret_cast<long long *>(base + L.fx_wsrc[i]);
+            ps[i]->tfirst = reinterpret_cast<long long *>(base + L.fx_tfirst[i]);
             ps[i]->part = reinterpret_cast<long long *>(base + L.fx_part[i]);
         }
     }

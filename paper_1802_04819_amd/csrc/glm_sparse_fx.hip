@@ -19,8 +19,13 @@
 // Layout of a pass (built once per matrix, in the workspace): entries sorted by (panel of the
 // output index, position in the source layout).  For the row pass the source is the caller's
 // column layout (CSC: within a panel, columns ascend), for the column pass the row layout (CSR).
-// Per entry: the index into the gathered vector (int32), the output index inside its panel
-// (uint16) and the value (fp32): 10 bytes.  The padded entry stream of all panels is cut into equal
+// Per entry 8 bytes: one word with the output index inside its panel (14 bits) and the index into
+// the gathered vector relative to the start of its window of 2^18 elements (18 bits), and the value
+// (fp32).  Because the gathered index ascends along the source, a window is a contiguous piece of
+// the source, and the entries of one panel and one window form a contiguous run of the layout;
+// every run is padded with zero entries to a multiple of 4096, so that each group of 4096 entries
+// (what a block loads in one step) lies in one panel and one window, whose first index is kept
+// per group.  The padded entry stream of all panels is cut into equal
 // spans, one per block (popular columns make some panels hundreds of times larger than others, so
 // work is shared by entries, not by panels): a block walks the panels its span touches and writes
 // 16384 partial sums for each; a small kernel adds the slices of a panel and converts to fp32.
@@ -38,22 +43,52 @@ constexpr int kFxUnroll = 2;             // rounds of four entries per lane in f
 
 // ------------------------------------------------------------------ building the layout
 
+// The source is cut into tiles of at most kFxTile entries, none of which crosses the start of a
+// window: wsrc[w] = first source entry whose owner (the gathered index) is >= w 2^18, tfirst[w] =
+// first tile of window w.  One thread; W <= 16.
+__global__ void fx_tiles_kernel(const long long *__restrict__ ptr, long long M, long long nnz, int W,
+                                long long *__restrict__ wsrc, long long *__restrict__ tfirst) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    long long prev = 0, tiles = 0;
+    for (int w = 0; w <= W; ++w) {
+        const long long m = (long long)w << kFxWindowBits;
+        long long e = w == 0 ? 0 : w == W ? nnz : ptr[m < M ? m : M];
+        e = e < prev ? prev : e > nnz ? nnz : e;       // whatever the pointer array holds
+        wsrc[w] = e;
+        if (w > 0) tiles += (e - prev + kFxTile - 1) / kFxTile;
+        tfirst[w] = w == 0 ? 0 : tiles;
+        prev = e;
+    }
+}
+
+// The window of a tile and its source entries [e0, e1); tiles past the last window's are empty.
+__device__ __forceinline__ int fx_tile_range(const long long *__restrict__ wsrc, const long long *__restrict__ tfirst,
+                                             int W, long long tile, long long *e0, long long *e1) {
+    int w = 0;
+    for (int i = 1; i < W; ++i) w = tfirst[i] <= tile ? i : w;
+    const long long b = wsrc[w] + (tile - tfirst[w]) * kFxTile, end = wsrc[w + 1];
+    *e0 = b < end ? b : end;
+    *e1 = b + kFxTile < end ? b + kFxTile : end;
+    if (tile >= tfirst[W]) *e1 = *e0;
+    return w;
+}
+
 // cnt[key * ntiles + tile] = entries of the tile whose output index lies in panel `key`
-__global__ __launch_bounds__(256) void fx_hist_kernel(const int *__restrict__ idx, long long nnz, long long ntiles,
-                                                      int P, long long *__restrict__ cnt) {
+__global__ __launch_bounds__(256) void fx_hist_kernel(const int *__restrict__ idx, long long ntiles, int P, int W,
+                                                      const long long *__restrict__ wsrc,
+                                                      const long long *__restrict__ tfirst,
+                                                      long long *__restrict__ cnt) {
     __shared__ int hist[4][kFxMaxPanels];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int i = lane; i < kFxMaxPanels; i += 64) hist[wave][i] = 0;
     __syncthreads();
     const long long tile = blockIdx.x * 4LL + wave;
     if (tile < ntiles) {
-        const long long e0 = tile * kFxTile;
-        for (int s = 0; s < kFxTile / 64; ++s) {
-            const long long e = e0 + s * 64 + lane;
-            if (e < nnz) {
-                const unsigned key = min((unsigned)idx[e] >> 14, (unsigned)(P - 1));
-                atomicAdd(&hist[wave][key], 1);
-            }
+        long long e0, e1;
+        fx_tile_range(wsrc, tfirst, W, tile, &e0, &e1);
+        for (long long e = e0 + lane; e < e1; e += 64) {
+            const unsigned key = min((unsigned)idx[e] >> kFxPanelBits, (unsigned)(P - 1));
+            atomicAdd(&hist[wave][key], 1);
         }
     }
     __syncthreads();
@@ -103,24 +138,41 @@ __global__ __launch_bounds__(256) void fx_scan_add_kernel(long long n, const lon
     if (s == n) a[n] = bsum[nb];
 }
 
-// One thread (P <= 256): pstart[p] = first entry of panel p in the padded layout (every panel
-// starts at a multiple of four and is filled up to one with zero entries), shift[p] = how far its
-// entries move up for that.  cnt[p * ntiles] is the exact start of panel p (p == P: the total).
-__global__ void fx_pstart_kernel(const long long *__restrict__ cnt, long long ntiles, int P,
-                                 long long *__restrict__ pstart, long long *__restrict__ shift,
-                                 int *__restrict__ gidx, unsigned short *__restrict__ loc, float *__restrict__ val) {
+// One thread (P W <= 4096 runs): run (p, w) holds the entries of panel p whose source lies in window
+// w; after the prefix sum cnt[p * ntiles + tfirst[w]] is its exact start.  rstart = its start in the
+// padded layout (every run is filled up to a multiple of kFxRun), rlen = its entries, shift = how
+// far they move up, pstart[p] = start of panel p's first run.
+__global__ void fx_pstart_kernel(const long long *__restrict__ cnt, long long ntiles, int P, int W,
+                                 const long long *__restrict__ tfirst, long long *__restrict__ pstart,
+                                 long long *__restrict__ shift, long long *__restrict__ rstart,
+                                 long long *__restrict__ rlen) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     long long at = 0;
     for (int p = 0; p < P; ++p) {
-        const long long s = cnt[(long long)p * ntiles];
-        const long long len = cnt[(long long)(p + 1) * ntiles] - s;
-        const long long padded = (len + 3) & ~3LL;
         pstart[p] = at;
-        shift[p] = at - s;
-        for (long long q = len; q < padded; ++q) { gidx[at + q] = 0; loc[at + q] = 0; val[at + q] = 0.0f; }
-        at += padded;
+        for (int w = 0; w < W; ++w) {
+            const long long s = cnt[(long long)p * ntiles + tfirst[w]];
+            const long long len = cnt[(long long)p * ntiles + tfirst[w + 1]] - s;
+            rstart[p * W + w] = at;
+            rlen[p * W + w] = len;
+            shift[p * W + w] = at - s;
+            at += (len + kFxRun - 1) / kFxRun * kFxRun;
+        }
     }
     pstart[P] = at;
+}
+
+// One block per run: the zero entries that fill it up, and the window start of each of its groups.
+__global__ __launch_bounds__(256) void fx_pad_kernel(int W, long long cap, const long long *__restrict__ rstart,
+                                                     const long long *__restrict__ rlen, unsigned *__restrict__ ent,
+                                                     float *__restrict__ val, int *__restrict__ tbase) {
+    const int w = (int)(blockIdx.x % (unsigned)W);
+    const long long at = rstart[blockIdx.x], len = rlen[blockIdx.x];
+    if (at < 0 || len < 0 || at > cap || len > cap - at) return;
+    long long end = at + (len + kFxRun - 1) / kFxRun * kFxRun;
+    end = end > cap ? cap : end;
+    for (long long q = at + len + threadIdx.x; q < end; q += 256) { ent[q] = 0u; val[q] = 0.0f; }
+    for (long long g = at / kFxRun + threadIdx.x; g < end / kFxRun; g += 256) tbase[g] = w << kFxWindowBits;
 }
 
 // largest m in [lo, hi] with ptr[m] <= e  (ptr[lo] <= e is given)
@@ -143,38 +195,43 @@ __device__ __forceinline__ long long fx_owner_from(const long long *__restrict__
     return fx_owner(ptr, lo, hi < lo ? lo : hi, e);
 }
 
-// Stable split: entry e of the source layout goes to the next free place of its panel.  One wave
-// per tile, 64 entries per step in source order; inside a step the lanes with the same panel
-// are ranked by lane.
+// Stable split: entry e of the source layout goes to the next free place of its run.  One wave
+// per tile (a tile lies in one window), 64 entries per step in source order; inside a step the
+// lanes with the same panel are ranked by lane.
 __global__ __launch_bounds__(256) void fx_scatter_kernel(const long long *__restrict__ ptr, long long M,
                                                          const int *__restrict__ idx, const float *__restrict__ val,
-                                                         long long nnz, long long ntiles, int P,
+                                                         long long ntiles, int P, int W,
+                                                         const long long *__restrict__ wsrc,
+                                                         const long long *__restrict__ tfirst,
                                                          const long long *__restrict__ cnt,
-                                                         const long long *__restrict__ shift, int *__restrict__ gidx,
-                                                         unsigned short *__restrict__ loc, float *__restrict__ valo) {
+                                                         const long long *__restrict__ shift, long long cap,
+                                                         unsigned *__restrict__ ent, float *__restrict__ valo) {
     __shared__ long long cur[4][kFxMaxPanels];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long tile = blockIdx.x * 4LL + wave;
-    if (tile < ntiles)
-        for (int k = lane; k < P; k += 64) cur[wave][k] = cnt[(long long)k * ntiles + tile] + shift[k];
+    long long e0 = 0, e1 = 0;
+    int w = 0;
+    if (tile < ntiles) {
+        w = fx_tile_range(wsrc, tfirst, W, tile, &e0, &e1);
+        for (int k = lane; k < P; k += 64) cur[wave][k] = cnt[(long long)k * ntiles + tile] + shift[k * W + w];
+    }
     __syncthreads();
-    if (tile >= ntiles) return;                        // whole waves leave: no block-wide barrier below
-    const long long e0 = tile * kFxTile;
+    if (tile >= ntiles || e0 >= e1) return;            // whole waves leave: no block-wide barrier below
     const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    long long mprev = 0;
-    for (int s = 0; s < kFxTile / 64; ++s) {
-        const long long eb = e0 + s * 64;
-        if (eb >= nnz) break;
+    const long long wbase = (long long)w << kFxWindowBits;
+    long long mprev = wbase < M - 1 ? wbase : M - 1;  // owners of this tile's entries start at the window's
+    mprev = mprev < 0 ? 0 : mprev;
+    for (long long eb = e0; eb < e1; eb += 64) {
         const long long e = eb + lane;
-        const bool ok = e < nnz;
-        const long long elast = eb + 63 < nnz ? eb + 63 : nnz - 1;
+        const bool ok = e < e1;
+        const long long elast = eb + 63 < e1 ? eb + 63 : e1 - 1;
         // owners (row of a CSR entry, column of a CSC entry): between those of the step's ends
         const long long m0 = fx_owner_from(ptr, mprev, M, eb);      // owners ascend with the entries
         const long long m1 = fx_owner_from(ptr, m0, M, elast);
         mprev = m1;
         const long long m = ok ? fx_owner(ptr, m0, m1, e) : m0;
         const int raw = ok ? idx[e] : 0;
-        const unsigned key = min((unsigned)raw >> 14, (unsigned)(P - 1));
+        const unsigned key = min((unsigned)raw >> kFxPanelBits, (unsigned)(P - 1));
         long long pos = 0;
         unsigned long long todo = __ballot(ok);
         while (todo) {
@@ -186,9 +243,9 @@ __global__ __launch_bounds__(256) void fx_scatter_kernel(const long long *__rest
             if (lane == lead) cur[wave][kk] = base + __builtin_popcountll(same);
             todo &= ~same;
         }
-        if (ok) {
-            gidx[pos] = (int)m;
-            loc[pos] = (unsigned short)((unsigned)raw & (kFxPanel - 1));
+        if (ok && pos >= 0 && pos < cap) {
+            const unsigned delta = (unsigned)(m - wbase) & ((1u << kFxWindowBits) - 1u);
+            ent[pos] = ((unsigned)raw & (unsigned)(kFxPanel - 1)) | (delta << kFxPanelBits);
             valo[pos] = val[e];
         }
     }
@@ -253,8 +310,8 @@ __device__ __forceinline__ long long fx_panel_start(const long long *__restrict_
 }
 
 __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
-    const int *__restrict__ gidx, const unsigned short *__restrict__ loc, const float *__restrict__ val,
-    const float *__restrict__ vec, long long vec_len, long long nnz, const long long *__restrict__ pstart,
+    const unsigned *__restrict__ ent, const float *__restrict__ val, const int *__restrict__ tbase,
+    const float *__restrict__ vec, long long vec_len, long long cap, const long long *__restrict__ pstart,
     int P, long long span, unsigned *slots, int vec_slot, int len_slot, int e_slot, long long *__restrict__ part) {
     extern __shared__ unsigned long long fx_sums[];    // [kFxPanel]
     const int tid = threadIdx.x;
@@ -262,7 +319,6 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
     if (blockIdx.x == 0 && tid == 0) slots[e_slot] = (unsigned)e2;          // for the kernel that converts back
     const float scale = __builtin_ldexpf(1.0f, e2);
     const unsigned vmax = (unsigned)(vec_len - 1);
-    const long long cap = (nnz + 4LL * P) & ~3LL;     // the arrays hold nnz + 4 P entries
     const long long total = fx_panel_start(pstart, P, cap);
     const long long r0 = (long long)blockIdx.x * span;
     const long long r1 = r0 + span < total ? r0 + span : total;
@@ -278,10 +334,8 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
         p = lo;
     }
     typedef float f4 __attribute__((ext_vector_type(4)));
-    typedef int i4 __attribute__((ext_vector_type(4)));
-    typedef unsigned short us4 __attribute__((ext_vector_type(4)));
-    const i4 *__restrict__ g4p = reinterpret_cast<const i4 *>(gidx);
-    const us4 *__restrict__ l4p = reinterpret_cast<const us4 *>(loc);
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    const u4 *__restrict__ e4p = reinterpret_cast<const u4 *>(ent);
     const f4 *__restrict__ v4p = reinterpret_cast<const f4 *>(val);
     const long long stride = (long long)kFxThreads * kFxUnroll;
     for (; p < P; ++p) {
@@ -294,28 +348,29 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
         // Two loads stand between an entry and its sum: the entry itself, then the element of the
         // other vector it points at.  The entries of the next round are requested before the current
         // round's elements are waited for, so that one latency is paid per round, not two.  A lane
-        // takes four consecutive entries with one 16-byte load per array (b0 and b1 are multiples
-        // of four: panels are padded, spans are multiples of 4096).
-        i4 g[kFxUnroll]; us4 l[kFxUnroll]; f4 v[kFxUnroll];
+        // takes four consecutive entries with one 16-byte load per array; the 4096 entries the block
+        // takes in one step are one group of the layout (b0 is a multiple of 4096: runs are padded,
+        // spans are multiples of 4096) and share the start of their window.
+        u4 g[kFxUnroll]; f4 v[kFxUnroll]; unsigned wb[kFxUnroll];
 #define SLAQ_FX_LOAD(Q)                                                                      \
     _Pragma("unroll") for (int u = 0; u < kFxUnroll; ++u) {                                  \
         const long long q_ = (Q) + (long long)u * kFxThreads;                                \
         const bool ok_ = q_ < q1;                                                            \
-        g[u] = ok_ ? __builtin_nontemporal_load(g4p + q_) : i4{0, 0, 0, 0};                  \
-        l[u] = ok_ ? __builtin_nontemporal_load(l4p + q_) : us4{0, 0, 0, 0};                 \
+        g[u] = ok_ ? __builtin_nontemporal_load(e4p + q_) : u4{0u, 0u, 0u, 0u};              \
         v[u] = ok_ ? __builtin_nontemporal_load(v4p + q_) : f4{0.0f, 0.0f, 0.0f, 0.0f};      \
+        wb[u] = ok_ ? (unsigned)tbase[q_ >> 10] : 0u;                                        \
     }
         const long long q1 = b1 >> 2;
         long long q = (b0 >> 2) + tid;
         if (q < q1) SLAQ_FX_LOAD(q)
         for (; q < q1; q += stride) {
-            f4 x[kFxUnroll], vv[kFxUnroll]; us4 ll[kFxUnroll];
+            f4 x[kFxUnroll], vv[kFxUnroll]; u4 ll[kFxUnroll];
 #pragma unroll
             for (int u = 0; u < kFxUnroll; ++u) {
                 // keep every index inside its array whatever the memory holds
 #pragma unroll
-                for (int c = 0; c < 4; ++c) x[u][c] = vec[min((unsigned)g[u][c], vmax)];
-                vv[u] = v[u]; ll[u] = l[u];
+                for (int c = 0; c < 4; ++c) x[u][c] = vec[min(wb[u] + (g[u][c] >> kFxPanelBits), vmax)];
+                vv[u] = v[u]; ll[u] = g[u];
             }
             if (q + stride < q1) SLAQ_FX_LOAD(q + stride)
 #pragma unroll
@@ -324,7 +379,7 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const long long t = __float2ll_rn((vv[u][c] * x[u][c]) * scale);
-                        atomicAdd(&fx_sums[(unsigned)ll[u][c] & (unsigned)(kFxPanel - 1)], (unsigned long long)t);
+                        atomicAdd(&fx_sums[ll[u][c] & (unsigned)(kFxPanel - 1)], (unsigned long long)t);
                     }
                 }
             }
@@ -344,7 +399,7 @@ __global__ __launch_bounds__(kFxThreads) void fx_pass_kernel(
 // any order.
 __global__ __launch_bounds__(256) void fx_finish_kernel(const long long *__restrict__ part,
                                                         const long long *__restrict__ pstart, int P, long long span,
-                                                        long long nnz, long long out_len,
+                                                        long long cap, long long out_len,
                                                         const unsigned *__restrict__ slots, int e_slot,
                                                         float *__restrict__ out) {
     __shared__ long long red[8][8][32];
@@ -353,7 +408,6 @@ __global__ __launch_bounds__(256) void fx_finish_kernel(const long long *__restr
     if (base >= out_len) return;
     const int p = (int)(base / kFxPanel);
     // the blocks whose spans meet the panel's entries [s0, s1): floor(s0 / span) .. floor((s1 - 1) / span)
-    const long long cap = (nnz + 4LL * P) & ~3LL;
     const long long s0 = fx_panel_start(pstart, p, cap), s1 = fx_panel_start(pstart, p + 1, cap);
     const long long c0 = s0 / span + p, c1 = s1 > s0 ? (s1 - 1) / span + p + 1 : c0;
 #pragma unroll
@@ -391,7 +445,9 @@ hipError_t fx_build_pass(const FxPass &ps, const long long *ptr, long long M, co
     hipError_t e;
     const long long ntiles = ps.ntiles;
     const unsigned tb = (unsigned)((ntiles + 3) / 4);
-    hipLaunchKernelGGL(fx_hist_kernel, dim3(tb), dim3(256), 0, st, idx, nnz, ntiles, ps.P, cnt);
+    hipLaunchKernelGGL(fx_tiles_kernel, dim3(1), dim3(64), 0, st, ptr, M, nnz, ps.W, ps.wsrc, ps.tfirst);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_hist_kernel, dim3(tb), dim3(256), 0, st, idx, ntiles, ps.P, ps.W, ps.wsrc, ps.tfirst, cnt);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const long long n = (long long)ps.P * ntiles;
     const long long nb = (n + kScanBlock - 1) / kScanBlock;
@@ -401,11 +457,14 @@ hipError_t fx_build_pass(const FxPass &ps, const long long *ptr, long long M, co
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(fx_scan_add_kernel, dim3((unsigned)((n + 1 + 255) / 256)), dim3(256), 0, st, n, bsum, nb, cnt);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_pstart_kernel, dim3(1), dim3(64), 0, st, cnt, ntiles, ps.P, ps.pstart, ps.shift, ps.gidx,
-                       ps.loc, ps.val);
+    hipLaunchKernelGGL(fx_pstart_kernel, dim3(1), dim3(64), 0, st, cnt, ntiles, ps.P, ps.W, ps.tfirst, ps.pstart, ps.shift,
+                       ps.rstart, ps.rlen);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_scatter_kernel, dim3(tb), dim3(256), 0, st, ptr, M, idx, val, nnz, ntiles, ps.P, cnt, ps.shift,
-                       ps.gidx, ps.loc, ps.val);
+    hipLaunchKernelGGL(fx_pad_kernel, dim3((unsigned)(ps.P * ps.W)), dim3(256), 0, st, ps.W, ps.cap, ps.rstart, ps.rlen,
+                       ps.ent, ps.val, ps.tbase);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(fx_scatter_kernel, dim3(tb), dim3(256), 0, st, ptr, M, idx, val, ntiles, ps.P, ps.W, ps.wsrc,
+                       ps.tfirst, cnt, ps.shift, ps.cap, ps.ent, ps.val);
     return hipGetLastError();
 }
 
@@ -414,23 +473,27 @@ hipError_t fx_build_pass(const FxPass &ps, const long long *ptr, long long M, co
 // Which passes take this path, with how many panels and blocks.  A function of the shape alone.
 void sparse_fx_plan(long long N, long long D, long long nnz, FxPass *row, FxPass *col) {
     FxPass *ps[2] = {row, col};
-    const long long out_len[2] = {N, D};
+    const long long out_len[2] = {N, D}, gather_len[2] = {D, N};
     for (int i = 0; i < 2; ++i) {
         FxPass &f = *ps[i];
         f = FxPass{};
         f.out_len = out_len[i];
+        f.gather_len = gather_len[i];
         const long long P = (out_len[i] + kFxPanel - 1) / kFxPanel;
-        f.on = nnz >= kFxMinEntries && P <= kFxMaxPanels;
+        const long long W = (gather_len[i] + (1LL << kFxWindowBits) - 1) >> kFxWindowBits;
+        // enough entries that the padding of the P W runs (less than 4096 each) stays under a quarter
+        f.on = nnz >= kFxMinEntries && P <= kFxMaxPanels && W <= kFxMaxWindows && nnz >= 4 * kFxRun * P * W;
         if (!f.on) continue;
         f.P = (int)P;
-        // one block per compute unit at most, each with an equal share of the padded stream (panels
-        // are padded by up to three entries each), whatever the sizes of the panels
-        const long long cap = (nnz + 4 * P) & ~3LL;
-        const long long span = ((cap + kFxBlocks - 1) / kFxBlocks + 4095) / 4096 * 4096;
+        f.W = (int)W;
+        f.cap = ((nnz + kFxRun - 1) / kFxRun + P * W) * kFxRun;
+        // one block per compute unit at most, each with an equal share of the padded stream,
+        // whatever the sizes of the panels
+        const long long span = ((f.cap + kFxBlocks - 1) / kFxBlocks + kFxRun - 1) / kFxRun * kFxRun;
         f.span = span < 32768 ? 32768 : span;
-        f.blocks = (int)((cap + f.span - 1) / f.span);
+        f.blocks = (int)((f.cap + f.span - 1) / f.span);
         f.slices = f.blocks + P;
-        f.ntiles = (nnz + kFxTile - 1) / kFxTile;
+        f.ntiles = (nnz + kFxTile - 1) / kFxTile + W;       // no tile crosses the start of a window
     }
 }
 
@@ -472,13 +535,13 @@ hipError_t launch_sparse_fx_pass(const SparseFx &fx, bool row, const float *vec,
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fx_pass_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kFxPanel * 8);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fx_pass_kernel, dim3((unsigned)ps.blocks), dim3(kFxThreads), kFxPanel * 8, st, ps.gidx, ps.loc,
-                       ps.val, vec, vec_len, nnz, ps.pstart, ps.P, ps.span, fx.slots,
+    hipLaunchKernelGGL(fx_pass_kernel, dim3((unsigned)ps.blocks), dim3(kFxThreads), kFxPanel * 8, st, ps.ent, ps.val,
+                       ps.tbase, vec, vec_len, ps.cap, ps.pstart, ps.P, ps.span, fx.slots,
                        row ? kFxSlotMaxW : kFxSlotMaxR, row ? kFxSlotLenRow : kFxSlotLenCol,
                        row ? kFxSlotERow : kFxSlotECol, ps.part);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(fx_finish_kernel, dim3((unsigned)((ps.out_len + 255) / 256)), dim3(256), 0, st, ps.part, ps.pstart,
-                       ps.P, ps.span, nnz, ps.out_len, fx.slots, row ? kFxSlotERow : kFxSlotECol, out);
+                       ps.P, ps.span, ps.cap, ps.out_len, fx.slots, row ? kFxSlotERow : kFxSlotECol, out);
     return hipGetLastError();
 }
 

@@ -47,7 +47,11 @@ hipError_t launch_sparse_csc_build(const SparseArgs &a, const SparseCsc &c, hipS
 
 // ---- scatter into LDS with fixed-point sums (glm_sparse_fx.hip) --------------------------------
 constexpr int kFxPanel = 16384;              // outputs per panel: their 64-bit sums fill 128 KB of LDS
+constexpr int kFxPanelBits = 14;
 constexpr int kFxMaxPanels = 256;            // bins of the split that builds the layout
+constexpr int kFxWindowBits = 18;            // a window of the gathered vector: what 32 - kFxPanelBits bits address
+constexpr int kFxMaxWindows = 16;
+constexpr int kFxRun = 4096;                 // entries of one (panel, window) run are padded to a multiple of this
 constexpr long long kFxMinEntries = 1LL << 22;
 constexpr int kFxBlocks = 256;               // at most one block per compute unit: the sums of a panel fill its LDS
 // device scalars of the path (unsigned [kFxSlots])
@@ -55,18 +59,25 @@ enum : int { kFxSlotMaxW = 0, kFxSlotMaxR = 1, kFxSlotMaxVal = 2, kFxSlotERow = 
              kFxSlotLenCol = 6, kFxSlots = 8 };
 struct FxPass {
     int on;                  // this pass takes the path
-    int P;                   // panels
-    long long span;          // consecutive entries of the padded stream per block (a multiple of 4096)
+    int P;                   // panels of the output vector
+    int W;                   // windows of the gathered vector
+    long long span;          // consecutive entries of the padded stream per block (a multiple of kFxRun)
     int blocks;              // blocks of the pass: block k streams entries [k span, (k + 1) span)
     long long slices;        // blocks + P: block k writes its sums for panel p to slice k + p
     long long out_len;       // N for the row pass, D for the column pass
-    long long ntiles;        // tiles of the split
-    int *gidx;               // [nnz + 4 P] index into the gathered vector
-    unsigned short *loc;     // [nnz + 4 P] output index inside its panel
-    float *val;              // [nnz + 4 P]; every panel starts at a multiple of four entries and is
-                             //   filled up to one with zero entries, so that lanes load four at a time
+    long long gather_len;    // D for the row pass, N for the column pass
+    long long ntiles;        // tiles of the split (an upper bound: no tile crosses a window of the source)
+    long long cap;           // entries the padded stream can hold: a multiple of kFxRun
+    unsigned *ent;           // [cap] output index inside the panel | (gathered index - start of its window) << 14
+    float *val;              // [cap]; the entries of one panel and one window form a run, padded with zero
+                             //   entries to a multiple of kFxRun: a group of kFxRun entries has one window
+    int *tbase;              // [cap / kFxRun] first gathered index of the window of each such group
     long long *pstart;       // [P + 1] first entry of each panel
-    long long *shift;        // [P] how far the panel's entries moved up for that alignment
+    long long *shift;        // [P * W] how far the entries of a run move up for the padding before them
+    long long *rstart;       // [P * W] first entry of each run
+    long long *rlen;         // [P * W] entries of each run before padding
+    long long *wsrc;         // [W + 1] first source entry of each window
+    long long *tfirst;       // [W + 1] first tile of each window
     long long *part;         // [slices, kFxPanel] fixed-point partial sums
 };
 struct SparseFx {
