@@ -343,6 +343,31 @@ def test_scatter_path_reruns_split_calls_and_duplicates():
     del coo
 
 
+def test_scatter_path_with_an_empty_window_and_empty_panels():
+    _say("[case] sparse, fixed-point scatter path: 262144 consecutive empty rows (a whole window of the gathered "
+         "residuals, sixteen output panels), columns left empty at both ends")
+    rng = np.random.default_rng(44)
+    N, D, nnz = 600_000, 40_000, 4_500_000
+    rows = rng.integers(0, 262_144 + (N - 524_288), size=nnz)
+    rows = np.where(rows >= 262_144, rows + 262_144, rows)               # nothing in [262144, 524288)
+    cols = rng.integers(20_000, D - 3_000, size=nnz)                      # the first column panel and the last columns empty
+    vals = rng.standard_normal(nnz).astype(np.float32) / 3
+    order = np.lexsort((cols, rows))
+    rp = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=N))]).astype(np.int64)
+    ci = cols[order].astype(np.int32); rv = vals[order]
+    corder = np.argsort(ci, kind="stable")
+    cp = np.concatenate([[0], np.cumsum(np.bincount(ci, minlength=D))]).astype(np.int64)
+    ri = np.repeat(np.arange(N, dtype=np.int32), np.diff(rp))[corder]
+    y = _labels(synth.LOGISTIC, N, rng)
+    T = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    job = glm.SparseJob(T(rp), T(ci), T(rv), T(cp), T(ri), T(rv[corder]), T(y), torch.zeros(D, device="cuda"),
+                        synth.LOGISTIC, 1e-4, 0.5, 3)
+    _check_steps(job, (rp, ci, rv), y, D, synth.LOGISTIC, 1e-4, 0.5, 3, "scatter, empty window")
+    assert job.c.prepared == 1
+    w = job.w.cpu().numpy()
+    assert not np.any(w[:20_000]) and not np.any(w[D - 3_000:])           # columns without entries never move from 0
+
+
 # ---- CSR alone: the library builds the column layout itself -------------------------------------
 
 def _csr_only_twin(job):
