@@ -176,7 +176,7 @@ def bench_single(args, cfg):
                    "loss": synth.LOSS_NAMES[p.loss], "lambda": p.lam, "step": p.eta,
                    "bytes_per_iteration": bytes_per_launch, "scale": args.scale},
         "roofline": {"bound": "latency" if cfg == 0 else "hbm",
-                     "kernel": "resident_kernel (per iteration)" if resident else "row_pass_kernel", "achieved": achieved,
+                     "kernel": "resident_kernel (per iteration)" if resident else "row_pass_one_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": (traffic_from_counters("row_pass_cfg2_hbm_counters.md")
                                  if cfg == 2 and args.scale == 1.0 else None),
@@ -639,7 +639,7 @@ def bench_lbfgs(args):
         "config": {"workload": p.name + "_lbfgs", "config_index": 8, "N": p.N, "D": p.D, "memory": memory,
                    "loss": synth.LOSS_NAMES[p.loss], "lambda": p.lam, "evaluations": int(st.evals),
                    "bytes_per_evaluation": bytes_per_launch, "scale": args.scale},
-        "roofline": {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "row_pass_one_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": avg_ms,
                      "launches": len(ms), "whole_run_GBps": bytes_per_launch * st.evals / sec / 1e9},
         "rerun_bit_identical": rerun_identical, "loss_first": float(hist[0]), "loss_last": float(st.f),

@@ -261,15 +261,17 @@ typedef struct {
 } glm_sparse_job_t;
 
 /* Workspace bytes for glm_step_sparse on this shape (reads N, D, nnz and whether col_ptr is NULL).  From 4,194,304 stored
- * entries on this includes room for the library's own copies of the matrix (20 bytes per entry and
- * a few hundred MB of partial sums); with more than 786,432 rows, below that, for a second copy of
- * the column layout (8 bytes per entry). */
+ * entries on this includes room for the library's own copies of the matrix (16 bytes per entry, a
+ * few percent of padding and some tens of MB of partial sums); with more than 786,432 rows, below
+ * that, for a second copy of the column layout (8 bytes per entry). */
 int glm_sparse_workspace_bytes(const glm_sparse_job_t *job /*HOST*/, size_t *out_bytes /*HOST*/);
 
 /* `iters` gradient-descent iterations of one sparse job: the same iteration as glm_step, with
  * absent entries counting as zeros.  Reads each stored entry twice per iteration (once per
  * layout).  The first call on a matrix (job->prepared == 0) may build auxiliary layouts in the
- * workspace: from 4,194,304 stored entries on, one copy per product ordered by panels of 16384
+ * workspace: from 4,194,304 stored entries on (and N, D up to 4,194,304, with at least 16384
+ * entries for every pair of an output panel of 16384 and a window of 262,144 gathered elements),
+ * one copy per product ordered by panels of 16384
  * outputs, whose sums are then formed in LDS as 64-bit fixed-point integers (order-free, hence
  * bit-identical from run to run, and finer than the fp32 products they add); below that, with more
  * than 786,432 rows, a copy of the column layout ordered by panels of 524,288 rows, which needs the
