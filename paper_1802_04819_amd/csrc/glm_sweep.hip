@@ -32,15 +32,27 @@ __device__ __forceinline__ floatx16 mfma32(float a, float b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
-template <bool HALF>
+// Address arithmetic of the K loops: every global load is "uniform base + a 32-bit byte offset that
+// the thread keeps for the whole kernel"; the base moves from chunk to chunk on the scalar unit.
+// Vector instructions issued between matrix instructions cost matrix-core time (the kernel with
+// 58 of them per 32 matrix instructions in the loop ran 5 % slower than with 6), so the masks for
+// the ragged cases (last chunk of a D that is no multiple of 32, fewer models than the tile holds)
+// exist only in the kernel variant for those cases (PLAIN = false); both variants add the same
+// numbers in the same order.
+__device__ __forceinline__ f4 load_nt_at(const f4 *__restrict__ base, unsigned byte_off) {
+    return __builtin_nontemporal_load(reinterpret_cast<const f4 *>(reinterpret_cast<const char *>(base) + byte_off));
+}
+__device__ __forceinline__ f4 load_at(const f4 *__restrict__ base, unsigned byte_off) {
+    return *reinterpret_cast<const f4 *>(reinterpret_cast<const char *>(base) + byte_off);
+}
+
+template <bool HALF, bool PLAIN>
 __global__ __launch_bounds__(256) void sweep_forward_kernel(
     const float *__restrict__ X, const float *__restrict__ y, const float *__restrict__ W,
     long long N, int D, int M, int loss, float *__restrict__ R, float *__restrict__ lossP, int T) {
     __shared__ f4 Xs4[kFwdRows * kFwdLd / 4];
     __shared__ f4 Ws4[kSweepM * kFwdLd / 4];
     __shared__ float lsm[4][kSweepM];
-    float *Xs = reinterpret_cast<float *>(Xs4);
-    float *Ws = reinterpret_cast<float *>(Ws4);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -49,76 +61,96 @@ __global__ __launch_bounds__(256) void sweep_forward_kernel(
     const int tile = blockIdx.x;
     const long long r0 = (long long)tile * kFwdRows;
     const int D4 = D >> 2;
-    const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X);
-    const f4 *__restrict__ W4 = reinterpret_cast<const f4 *>(W);
+    const f4 *__restrict__ Xb = reinterpret_cast<const f4 *>(X) + r0 * D4;     // the tile's first row
+    const f4 *__restrict__ Wb = reinterpret_cast<const f4 *>(W);
 
     // staging assignments: X chunk = 128 rows x 8 f4, W chunk = 64 rows x 8 f4
     constexpr int WQ = HALF ? 1 : 2;          // W rows staged per thread: 32 or 64 models
     constexpr int RS = HALF ? 32 : kSweepM;   // row stride of R
-    long long xrow[4]; int xc4[4];
+    constexpr int MT = HALF ? 32 : kSweepM;   // models of a full tile
+    unsigned xo[4], xrow_o[4]; int xc4[4];   // byte offsets from Xb: of the thread's slot, of its row
+    f4 *xdst[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int idx = tid + 256 * q;
-        long long r = r0 + (idx >> 3);
-        xrow[q] = (r < N ? r : N - 1) * D4;
+        const long long r = r0 + (idx >> 3);
+        const unsigned rel = (unsigned)((r < N ? r : N - 1) - r0);     // rows past N read the last row
         xc4[q] = idx & 7;
+        xrow_o[q] = rel * (unsigned)D4 * 16u;
+        xo[q] = xrow_o[q] + (unsigned)xc4[q] * 16u;
+        xdst[q] = Xs4 + (idx >> 3) * (kFwdLd / 4) + (idx & 7);
     }
-    int wrow[WQ], wc4[WQ]; float wmask[WQ];   // models past M read row 0 and are multiplied by 0
+    unsigned wo[WQ], wrow_o[WQ]; int wc4[WQ]; float wmask[WQ];   // models past M read row 0 and are multiplied by 0
+    f4 *wdst[WQ];
 #pragma unroll
     for (int q = 0; q < WQ; ++q) {
         const int idx = tid + 256 * q;
         const int m = idx >> 3;
         wmask[q] = m < M ? 1.0f : 0.0f;
-        wrow[q] = (m < M ? m : 0) * D4;
         wc4[q] = idx & 7;
+        wrow_o[q] = (unsigned)(m < M ? m : 0) * (unsigned)D4 * 16u;
+        wo[q] = wrow_o[q] + (unsigned)wc4[q] * 16u;
+        wdst[q] = Ws4 + (idx >> 3) * (kFwdLd / 4) + (idx & 7);
     }
+    const int nchunk = (D + kFwdK - 1) / kFwdK;
+    // PLAIN: D is a multiple of 32 and the tile is full of models (the launch checks it)
+    const int ragged = PLAIN ? -1 : ((D % kFwdK) != 0 ? nchunk - 1 : -1);   // the chunk with slots past the row length
+    (void)MT;
 
     floatx16 acc0 = {0}, acc1 = {0};
-    const int nchunk = (D + kFwdK - 1) / kFwdK;
-    // A chunk is 8 float4 slots of k; slots past the row length (last chunk of a D that is not a
-    // multiple of 32) read a clamped slot and are multiplied by 0 on both operands.
+    // A chunk is 8 float4 slots of k.  Slots past the row length (last chunk of a D that is not a
+    // multiple of 32) read a clamped slot and are multiplied by 0 on both operands; every other
+    // chunk is staged as it is (also its infinities and NaNs).
 #define SLAQ_FWD_FETCH(KC)                                                                   \
     {                                                                                        \
         const int kc_ = (KC);                                                                \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                      \
-            const int c_ = kc_ * (kFwdK / 4) + xc4[q];                                       \
-            xk[q] = c_ < D4 ? 1.0f : 0.0f;                                                   \
-            xr[q] = __builtin_nontemporal_load(X4 + xrow[q] + (c_ < D4 ? c_ : D4 - 1));      \
-        }                                                                                    \
-        _Pragma("unroll") for (int q = 0; q < WQ; ++q) {                                     \
-            const int c_ = kc_ * (kFwdK / 4) + wc4[q];                                       \
-            wk[q] = c_ < D4 ? wmask[q] : 0.0f;                                               \
-            wr[q] = W4[wrow[q] + (c_ < D4 ? c_ : D4 - 1)];                                   \
+        if (PLAIN || kc_ != ragged) {                                                        \
+            const f4 *__restrict__ xc_ = Xb + kc_ * (kFwdK / 4);                             \
+            const f4 *__restrict__ wc_ = Wb + kc_ * (kFwdK / 4);                             \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) xr[q] = load_nt_at(xc_, xo[q]);    \
+            _Pragma("unroll") for (int q = 0; q < WQ; ++q) wr[q] = load_at(wc_, wo[q]);      \
+        } else {                                                                             \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                  \
+                const int c_ = kc_ * (kFwdK / 4) + xc4[q];                                   \
+                xr[q] = load_nt_at(Xb, xrow_o[q] + (unsigned)(c_ < D4 ? c_ : D4 - 1) * 16u); \
+            }                                                                                \
+            _Pragma("unroll") for (int q = 0; q < WQ; ++q) {                                 \
+                const int c_ = kc_ * (kFwdK / 4) + wc4[q];                                   \
+                wr[q] = load_at(Wb, wrow_o[q] + (unsigned)(c_ < D4 ? c_ : D4 - 1) * 16u);    \
+            }                                                                                \
         }                                                                                    \
     }
-#define SLAQ_FWD_STASH()                                                                     \
+#define SLAQ_FWD_STASH(KC)                                                                   \
     {                                                                                        \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                      \
-            const int idx = tid + 256 * q;                                                   \
-            Xs4[(idx >> 3) * (kFwdLd / 4) + (idx & 7)] = full_k ? xr[q] : xr[q] * xk[q];     \
-        }                                                                                    \
-        _Pragma("unroll") for (int q = 0; q < WQ; ++q) {                                     \
-            const int idx = tid + 256 * q;                                                   \
-            Ws4[(idx >> 3) * (kFwdLd / 4) + (idx & 7)] = wr[q] * wk[q];                      \
+        const int kc_ = (KC);                                                                \
+        if (PLAIN) {                                                                         \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) *xdst[q] = xr[q];                  \
+            _Pragma("unroll") for (int q = 0; q < WQ; ++q) *wdst[q] = wr[q];                 \
+        } else if (kc_ != ragged) {                                                          \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) *xdst[q] = xr[q];                  \
+            _Pragma("unroll") for (int q = 0; q < WQ; ++q) *wdst[q] = wr[q] * wmask[q];      \
+        } else {                                                                             \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q)                                    \
+                *xdst[q] = xr[q] * (kc_ * (kFwdK / 4) + xc4[q] < D4 ? 1.0f : 0.0f);          \
+            _Pragma("unroll") for (int q = 0; q < WQ; ++q)                                   \
+                *wdst[q] = wr[q] * (kc_ * (kFwdK / 4) + wc4[q] < D4 ? wmask[q] : 0.0f);      \
         }                                                                                    \
     }
-    const bool full_k = (D % kFwdK) == 0;     // then X is staged as it is (also its infinities and NaNs)
 
     {
         f4 xr[4], wr[WQ];
-        float xk[4], wk[WQ];
         SLAQ_FWD_FETCH(0)
-        SLAQ_FWD_STASH()
+        SLAQ_FWD_STASH(0)
     }
     __syncthreads();
+    const f4 *arow = Xs4 + (wave * 32 + li) * (kFwdLd / 4) + lh;
+    const f4 *b0row = Ws4 + li * (kFwdLd / 4) + lh;
+    const f4 *b1row = Ws4 + (32 + li) * (kFwdLd / 4) + lh;
     for (int kc = 0; kc < nchunk; ++kc) {
         f4 xr[4], wr[WQ];
-        float xk[4], wk[WQ];
-        SLAQ_FWD_FETCH(kc + 1 < nchunk ? kc + 1 : kc)   // last trip re-reads its own chunk (cache hit)
+        const int kn = kc + 1 < nchunk ? kc + 1 : kc;   // last trip re-reads its own chunk (cache hit)
+        SLAQ_FWD_FETCH(kn)
         __builtin_amdgcn_sched_barrier(0);              // keep the prefetch ahead of the matrix ops
-        const f4 *arow = Xs4 + (wave * 32 + li) * (kFwdLd / 4) + lh;
-        const f4 *b0row = Ws4 + li * (kFwdLd / 4) + lh;
-        const f4 *b1row = Ws4 + (32 + li) * (kFwdLd / 4) + lh;
 #pragma unroll
         for (int kb = 0; kb < kFwdK / 8; ++kb) {        // 8 k values: lanes lh=0 take 0..3, lh=1 4..7
             const f4 a = arow[2 * kb];
@@ -137,12 +169,11 @@ __global__ __launch_bounds__(256) void sweep_forward_kernel(
             }
         }
         __syncthreads();
-        SLAQ_FWD_STASH()
+        SLAQ_FWD_STASH(kn)
         __syncthreads();
     }
 #undef SLAQ_FWD_FETCH
 #undef SLAQ_FWD_STASH
-    (void)Xs; (void)Ws;
 
     // epilogue: lane holds models li (acc0) and 32 + li (acc1) for 16 rows of the wave's 32
     float ls0 = 0.0f, ls1 = 0.0f;
@@ -198,45 +229,60 @@ __global__ __launch_bounds__(256) void sweep_backward_kernel(
     constexpr int RS = HALF ? 32 : kSweepM;            // row stride of R (and of its copy in LDS)
     constexpr int RQ = HALF ? 1 : 2;                   // float4 of R staged per thread and chunk
     floatx16 acc[2][2] = {{{0}, {0}}, {{0}, {0}}};     // [model tile][column tile]
+    // Byte offsets from the chunk's first row, kept for the whole kernel (see the forward kernel):
+    // X slot (row = idx / 64, f4 column = idx % 64 of the slab; slab columns past D read a valid
+    // slot, their sums are never stored); the R chunk is contiguous.
+    unsigned xo[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int idx = tid + 256 * q;
+        int c4 = slab * (kBwdCols / 4) + (idx & 63);
+        c4 = c4 < D4 ? c4 : D4 - 1;
+        xo[q] = ((unsigned)(idx >> 6) * (unsigned)D4 + (unsigned)c4) * 16u;
+    }
 #define SLAQ_BWD_FETCH(CH)                                                                   \
     {                                                                                        \
         const long long rbase = (CH) * kBwdRows;                                             \
-        _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                      \
-            const int idx = tid + 256 * q;         /* row = idx / 64, f4 column = idx % 64 */ \
-            long long row = rbase + (idx >> 6);                                              \
-            row = row < N ? row : N - 1;                                                     \
-            int c4 = slab * (kBwdCols / 4) + (idx & 63);   /* slab columns past D read a valid */ \
-            c4 = c4 < D4 ? c4 : D4 - 1;                    /* slot; their sums are never stored */ \
-            xr[q] = __builtin_nontemporal_load(X4 + row * D4 + c4);                          \
-        }                                                                                    \
-        _Pragma("unroll") for (int q = 0; q < RQ; ++q) {                                     \
-            const int idx = tid + 256 * q;         /* row = idx / (RS/4), f4 model = idx % (RS/4) */ \
-            const long long row = rbase + idx / (RS / 4);                                    \
-            rkeep[q] = row < N ? 1.0f : 0.0f;              /* rows past N add nothing */      \
-            rr[q] = R4[(row < N ? row : N - 1) * (RS / 4) + idx % (RS / 4)];                 \
+        if (rbase + kBwdRows <= N) {                   /* every row of the chunk exists */   \
+            const f4 *__restrict__ xc_ = X4 + rbase * D4;                                    \
+            const f4 *__restrict__ rc_ = R4 + rbase * (RS / 4);                              \
+            _Pragma("unroll") for (int q = 0; q < 8; ++q) xr[q] = load_nt_at(xc_, xo[q]);    \
+            _Pragma("unroll") for (int q = 0; q < RQ; ++q)                                   \
+                rr[q] = load_at(rc_, (unsigned)(tid + 256 * q) * 16u);                       \
+        } else {                                                                             \
+            _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                  \
+                const int idx = tid + 256 * q;                                               \
+                long long row = rbase + (idx >> 6);                                          \
+                row = row < N ? row : N - 1;                                                 \
+                xr[q] = load_nt_at(X4 + row * D4, xo[q] - (unsigned)(idx >> 6) * (unsigned)D4 * 16u); \
+            }                                                                                \
+            _Pragma("unroll") for (int q = 0; q < RQ; ++q) {                                 \
+                const int idx = tid + 256 * q;     /* row = idx / (RS/4), f4 model = idx % (RS/4) */ \
+                const long long row = rbase + idx / (RS / 4);                                \
+                const f4 v_ = R4[(row < N ? row : N - 1) * (RS / 4) + idx % (RS / 4)];       \
+                rr[q] = v_ * (row < N ? 1.0f : 0.0f);      /* rows past N add nothing */      \
+            }                                                                                \
         }                                                                                    \
     }
 #define SLAQ_BWD_STASH()                                                                     \
     {                                                                                        \
         _Pragma("unroll") for (int q = 0; q < 8; ++q) Xs4[tid + 256 * q] = xr[q];            \
-        _Pragma("unroll") for (int q = 0; q < RQ; ++q) Rs4[tid + 256 * q] = rr[q] * rkeep[q]; \
+        _Pragma("unroll") for (int q = 0; q < RQ; ++q) Rs4[tid + 256 * q] = rr[q];           \
     }
 
     long long c = s;
     if (c < nchunks) {
         f4 xr[8], rr[RQ];
-        float rkeep[RQ];
         SLAQ_BWD_FETCH(c)
         SLAQ_BWD_STASH()
     }
     __syncthreads();
+    const float *xa = Xs + lh * kBwdCols + wave * 64 + li;
+    const float *ra = Rs + lh * RS + li;
     for (; c < nchunks; c += S) {
         f4 xr[8], rr[RQ];
-        float rkeep[RQ];
         SLAQ_BWD_FETCH(c + S < nchunks ? c + S : c)     // last trip re-reads its own chunk
         __builtin_amdgcn_sched_barrier(0);              // keep the prefetch ahead of the matrix ops
-        const float *xa = Xs + lh * kBwdCols + wave * 64 + li;
-        const float *ra = Rs + lh * RS + li;
 #pragma unroll
         for (int kp = 0; kp < kBwdRows / 2; ++kp) {       // contraction rows 2 kp + lh
             const float a0 = ra[2 * kp * RS];
@@ -333,12 +379,14 @@ hipError_t launch_sweep_iteration(const SweepArgs &a, int k, hipEvent_t *ev, hip
     hipError_t e;
     if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
     const bool half = a.M <= 32;
-    if (half)
-        hipLaunchKernelGGL(sweep_forward_kernel<true>, dim3((unsigned)a.T), dim3(256), 0, st, a.X, a.y, a.W,
-                           a.N, a.D, a.M, a.loss, a.R, a.lossP, a.T);
-    else
-        hipLaunchKernelGGL(sweep_forward_kernel<false>, dim3((unsigned)a.T), dim3(256), 0, st, a.X, a.y, a.W,
-                           a.N, a.D, a.M, a.loss, a.R, a.lossP, a.T);
+    // the plain variant: no ragged last K-chunk and a tile full of models
+    const bool plain = (a.D % kFwdK) == 0 && a.M == (half ? 32 : kSweepM);
+#define SLAQ_FWD_LAUNCH(H, P)                                                                \
+    hipLaunchKernelGGL((sweep_forward_kernel<H, P>), dim3((unsigned)a.T), dim3(256), 0, st, a.X, a.y, a.W, a.N, a.D, \
+                       a.M, a.loss, a.R, a.lossP, a.T)
+    if (half) { if (plain) SLAQ_FWD_LAUNCH(true, true); else SLAQ_FWD_LAUNCH(true, false); }
+    else { if (plain) SLAQ_FWD_LAUNCH(false, true); else SLAQ_FWD_LAUNCH(false, false); }
+#undef SLAQ_FWD_LAUNCH
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
