@@ -96,6 +96,21 @@ def test_sweep_reruns_are_bit_identical():
         assert all(torch.equal(a, b) for a, b in zip(outs[0], o))
 
 
+@pytest.mark.parametrize("M_full,M_less", [(64, 63), (32, 31), (128, 127)])
+def test_sweep_full_and_partial_tiles_give_the_same_bits(M_full, M_less):
+    """A tile full of models runs the forward kernel without masks, a partial tile the one with them;
+    both add the same numbers in the same order, so a model's trajectory does not depend on how many
+    models share its tile."""
+    _say(f"[case] sweep, {M_full} models against the first {M_less} of them: same bits per model")
+    p = synth.make_glm(synth.LOGISTIC, 3001, 256, seed=77, lam=0.0, eta=0.0, K=4)
+    rng = np.random.default_rng(8)
+    lams = (10.0 ** rng.uniform(-5, -1, M_full)).astype(np.float32)
+    etas = (0.5 * 10.0 ** rng.uniform(-2, 0, M_full)).astype(np.float32)
+    Wf, Gf, hf = _run_sweep(p, lams, etas, 4)
+    Wl, Gl, hl = _run_sweep(p, lams[:M_less], etas[:M_less], 4)
+    assert torch.equal(Wf[:M_less], Wl) and torch.equal(Gf[:M_less], Gl) and torch.equal(hf[:, :M_less], hl)
+
+
 def test_sweep_argument_errors():
     _say("[case] sweep error codes")
     p = synth.make_glm(synth.LOGISTIC, 100, 64, seed=1, lam=0.0, eta=0.0, K=1)
