@@ -45,7 +45,7 @@ constexpr int kFxUnroll = 2;             // rounds of four entries per lane in f
 
 // The source is cut into tiles of at most kFxTile entries, none of which crosses the start of a
 // window: wsrc[w] = first source entry whose owner (the gathered index) is >= w 2^18, tfirst[w] =
-// first tile of window w.  One thread; W <= 16.
+// first tile of window w.  One thread; W <= kFxMaxWindows.
 __global__ void fx_tiles_kernel(const long long *__restrict__ ptr, long long M, long long nnz, int W,
                                 long long *__restrict__ wsrc, long long *__restrict__ tfirst) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void fx_scan_add_kernel(long long n, const lon
     if (s == n) a[n] = bsum[nb];
 }
 
-// One thread (P W <= 4096 runs): run (p, w) holds the entries of panel p whose source lies in window
+// One thread (P W <= 16384 runs): run (p, w) holds the entries of panel p whose source lies in window
 // w; after the prefix sum cnt[p * ntiles + tfirst[w]] is its exact start.  rstart = its start in the
 // padded layout (every run is filled up to a multiple of kFxRun), rlen = its entries, shift = how
 // far they move up, pstart[p] = start of panel p's first run.

@@ -50,7 +50,7 @@ constexpr int kFxPanel = 16384;              // outputs per panel: their 64-bit 
 constexpr int kFxPanelBits = 14;
 constexpr int kFxMaxPanels = 256;            // bins of the split that builds the layout
 constexpr int kFxWindowBits = 18;            // a window of the gathered vector: what 32 - kFxPanelBits bits address
-constexpr int kFxMaxWindows = 16;
+constexpr int kFxMaxWindows = 64;
 constexpr int kFxRun = 4096;                 // entries of one (panel, window) run are padded to a multiple of this
 constexpr long long kFxMinEntries = 1LL << 22;
 constexpr int kFxBlocks = 256;               // at most one block per compute unit: the sums of a panel fill its LDS
