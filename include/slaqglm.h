@@ -269,8 +269,8 @@ int glm_sparse_workspace_bytes(const glm_sparse_job_t *job /*HOST*/, size_t *out
 /* `iters` gradient-descent iterations of one sparse job: the same iteration as glm_step, with
  * absent entries counting as zeros.  Reads each stored entry twice per iteration (once per
  * layout).  The first call on a matrix (job->prepared == 0) may build auxiliary layouts in the
- * workspace: from 4,194,304 stored entries on (for a product whose output vector has at most 4,194,304
- * elements and whose other vector at most 16,777,216, with at least 16384
+ * workspace: from 4,194,304 stored entries on (for a product whose two vectors have at most 16,777,216
+ * elements each, with at least 16384
  * entries for every pair of an output panel of 16384 and a window of 262,144 gathered elements),
  * one copy per product ordered by panels of 16384
  * outputs, whose sums are then formed in LDS as 64-bit fixed-point integers (order-free, hence

@@ -48,7 +48,7 @@ hipError_t launch_sparse_csc_build(const SparseArgs &a, const SparseCsc &c, hipS
 // ---- scatter into LDS with fixed-point sums (glm_sparse_fx.hip) --------------------------------
 constexpr int kFxPanel = 16384;              // outputs per panel: their 64-bit sums fill 128 KB of LDS
 constexpr int kFxPanelBits = 14;
-constexpr int kFxMaxPanels = 256;            // bins of the split that builds the layout
+constexpr int kFxMaxPanels = 1024;           // bins of the split that builds the layout
 constexpr int kFxWindowBits = 18;            // a window of the gathered vector: what 32 - kFxPanelBits bits address
 constexpr int kFxMaxWindows = 64;
 constexpr int kFxRun = 4096;                 // entries of one (panel, window) run are padded to a multiple of this

@@ -293,8 +293,10 @@ def test_prepared_flag_is_only_believed_for_the_workspace_it_was_set_on():
 
 @pytest.mark.parametrize("loss,N,D,mean", [(synth.LOGISTIC, 300_000, 200_000, 20.0), (synth.SQUARED, 250_000, 70_000, 18.0),
                                            (synth.HINGE, 1_500_000, 300, 3.2),
-                                           # 18 windows of the gathered residuals; the row product has too many panels for the path
-                                           (synth.SQUARED, 4_500_000, 200, 1.2)])
+                                           # 18 windows of the gathered residuals and 275 panels of margins
+                                           (synth.SQUARED, 4_500_000, 200, 1.2),
+                                           # too few entries for the 306 panels of the row product: only the column product takes the path
+                                           (synth.LOGISTIC, 5_000_000, 200, 0.9)])
 def test_scatter_path_each_step_matches_oracle(loss, N, D, mean):
     _say(f"[case] sparse, fixed-point scatter path: loss {loss}, {N} x {D}, about {mean} entries per row")
     eta = {synth.LOGISTIC: 0.5, synth.HINGE: 0.05, synth.SQUARED: 0.05}[loss]
