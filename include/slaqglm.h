@@ -105,7 +105,9 @@ typedef struct {
  * A job of a few MB (every wave holds at most one tile of rows and the partial sums
  * number at most 16384) runs a whole glm_step call in one launch whose blocks stay on
  * the chip and exchange their partial sums through the workspace; its results are
- * bit-identical to the general path.
+ * bit-identical to the general path.  Such a launch takes at most a quarter of the chip; its
+ * blocks wait for one another with a bound (seconds), and if other work keeps part of them off
+ * the chip beyond that bound the remaining history entries of the call are NaN.
  * Errors: GLM_EINVAL for a null pointer, J < 1, or a shape outside the limits. */
 int glm_workspace_bytes(const glm_job_t *jobs /*HOST [J]*/, int32_t J, int32_t M_sweep,
                         size_t *out_bytes /*HOST*/);

@@ -263,10 +263,14 @@ DevJob device_job(const glm_job_t &src, const JobSlots &s, char *base, int iters
     return d;
 }
 
-// A tiny job runs its whole call in one resident launch when all its row blocks fit on the chip at
-// once (and the barrier count cannot overflow); everything else takes two launches per iteration.
+// A tiny job runs its whole call in one resident launch when its row blocks take at most a quarter
+// of the places the chip has for them (and the iteration tags cannot overflow); everything else
+// takes two launches per iteration.  The blocks of a resident launch wait for one another, so all
+// of them must be on the chip together; the quarter leaves room for other work of the process (up
+// to four such launches on different streams still all fit).  Should blocks be kept off the chip
+// all the same, the waits are bounded and the call ends with NaN in its remaining history entries.
 bool use_resident(const JobSlots &s, int iters) {
-    return s.tiny && (long long)iters * s.P < (1LL << 31) && s.P <= resident_capacity(s.cls);
+    return s.tiny && (long long)iters * s.P < (1LL << 31) && s.P <= resident_capacity(s.cls) / 4;
 }
 
 hipError_t run_single(const glm_job_t &src, int iters, void *ws, hipStream_t st, double *loss64 = nullptr) {
