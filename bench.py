@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--check", action="store_true", help="also compare against the oracle on the full data")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true",
-                    help="with the default workload: do not also measure configurations 0, 1, 3 and 4")
+                    help="with the default workload: do not also measure the other configurations (0, 1, 3-8)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, used to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -669,22 +669,27 @@ def extra_configs(args):
     import gc
     import torch
     res = {}
-    for cfg in (0, 1, 3, 4):
+    runners = {0: lambda a: bench_single(a, 0), 1: lambda a: bench_single(a, 1), 3: bench_batched, 4: bench_sweep,
+               5: bench_sched, 6: bench_sparse, 7: bench_kmeans, 8: bench_lbfgs}
+    for cfg in (0, 1, 3, 4, 5, 6, 7, 8):           # 0-4: the benchmark configurations; 5-8: the steps built after them
         a = copy.copy(args)
-        a.config, a.steps, a.warmup, a.no_cpu_baseline, a.check = cfg, None, 3, True, False
+        a.config, a.steps, a.no_cpu_baseline, a.check = cfg, None, True, False
+        a.warmup = 1 if cfg == 3 else 3
         gc.collect()
         torch.cuda.empty_cache()
         try:
-            o = bench_single(a, cfg) if cfg in (0, 1) else (bench_batched(a) if cfg == 3 else bench_sweep(a))
+            o = runners[cfg](a)
         except Exception as e:                      # a failure here must not take the headline line with it
             res[f"config{cfg}"] = {"error": f"{type(e).__name__}: {e}"}
             continue
         r = o["roofline"]
         res[f"config{cfg}"] = {
             "workload": o["config"]["workload"], "value": o["value"], "unit": o["unit"], "steps": o["steps"],
-            "ms_per_step": o["ms_per_step"], "rerun_bit_identical": o["rerun_bit_identical"],
+            "ms_per_step": o["ms_per_step"], "rerun_bit_identical": o.get("rerun_bit_identical"),
             "roofline": {k: r.get(k) for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "avg_launch_ms",
-                                               "whole_step_GBps", "forward_ms", "backward_ms") if k in r},
+                                               "whole_step_GBps", "whole_run_GBps", "forward_ms", "backward_ms",
+                                               "predict_kernel_ms", "allocate_host_ms", "assign_ms", "accumulate_ms",
+                                               "executed_TFLOPs", "executed_frac") if k in r},
         }
     return res
 
