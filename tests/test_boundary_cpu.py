@@ -151,3 +151,33 @@ def test_header_is_c_and_the_c_consumer_links():
     from paper_1802_04819_amd import build as b
     path = b.build_c_demo()
     assert os.path.exists(path) and os.access(path, os.X_OK)
+
+
+def _sparse_ws(N, D, nnz, csr_only=False):
+    a = 0x10000
+    j = glm.glm_sparse_job_t(a, a, a, 0 if csr_only else a, 0 if csr_only else a, 0 if csr_only else a, a, a, a, a,
+                             N, D, nnz, 0, 1e-3, 0.1, 0, 4, 0, 0)
+    out = ctypes.c_size_t(0)
+    rc = glm.load().glm_sparse_workspace_bytes(ctypes.byref(j), ctypes.byref(out))
+    return rc, out.value
+
+
+def test_sparse_workspace_bytes_over_the_limits_of_the_scatter_path():
+    """The size is a function of (N, D, nnz, CSR alone or not); it stays sane on both sides of every
+    limit of the scatter path (4,194,304 entries, 1024 panels of outputs, 64 windows of the other
+    vector, enough entries per panel and window) and does not shrink when the number of entries grows."""
+    shapes = [(1000, 500, 0), (1000, 500, 10_000), (300_000, 200_000, (1 << 22) - 1), (300_000, 200_000, 1 << 22),
+              (16_777_216, 300, 20_000_000), (16_777_217, 300, 20_000_000),          # 1024 / 1025 panels, 64 / 65 windows
+              (2_000_000, 1_000_000, 199_821_056), (4_194_304, 4_194_304, 5_000_000),  # too few entries per panel and window
+              (50_000_000, 100_000, 400_000_000)]
+    for N, D, nnz in shapes:
+        rc, b = _sparse_ws(N, D, nnz)
+        assert rc == glm.GLM_OK and b % 256 == 0, (N, D, nnz)
+        assert b < 64 * max(nnz, 1) + 64 * (N + D) + (1 << 30), (N, D, nnz, b)       # a few copies of the matrix at most
+        rc2, b2 = _sparse_ws(N, D, nnz, csr_only=True)
+        assert rc2 == glm.GLM_OK and b2 >= b
+        if nnz > 0:
+            rc3, b3 = _sparse_ws(N, D, 2 * nnz)
+            assert rc3 == glm.GLM_OK and b3 >= b
+    assert _sparse_ws(0, 5, 0)[0] == glm.GLM_EINVAL and _sparse_ws(5, 0, 0)[0] == glm.GLM_EINVAL
+    assert _sparse_ws(5, 5, -1)[0] == glm.GLM_EINVAL
