@@ -584,26 +584,32 @@ struct ResidentCtl { unsigned failed; unsigned pad; };
 // segment order starting from its first segment; then (c0 + c1) + (c2 + c3).  The values come from
 // LDS (row block p at base[p * stride]), sixteen loads in flight.
 static_assert(kFinSegs == 64, "the combine below is written for 64 segments");
+// Run k (segments 16 k .. 16 k + 15) of a column when no segment holds more than one row block
+// (P <= kFinSegs): the sixteen loads first, then the sums in segment order.
+__device__ __forceinline__ double column_run_sparse(const float *base, const int stride, const int P, const int k) {
+    float v[16];
+    bool has[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int seg = 16 * k + u;
+        const int p0 = (P * seg) / kFinSegs, p1 = (P * (seg + 1)) / kFinSegs;
+        has[u] = p1 > p0;
+        v[u] = base[(size_t)(has[u] ? p0 : 0) * stride];
+    }
+    double c = 0.0;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const double s = has[u] ? 0.0 + (double)v[u] : 0.0;     // a segment starts from zero
+        c = u == 0 ? s : c + s;
+    }
+    return c;
+}
+
 __device__ __forceinline__ double column_total(const float *base, const int stride, const int P) {
     double c[4] = {0.0, 0.0, 0.0, 0.0};
     if (P <= kFinSegs) {                        // no segment holds more than one row block
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            float v[16];
-            bool has[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int seg = 16 * k + u;
-                const int p0 = (P * seg) / kFinSegs, p1 = (P * (seg + 1)) / kFinSegs;
-                has[u] = p1 > p0;
-                v[u] = base[(size_t)(has[u] ? p0 : 0) * stride];
-            }
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const double s = has[u] ? 0.0 + (double)v[u] : 0.0;     // a segment starts from zero
-                c[k] = u == 0 ? s : c[k] + s;
-            }
-        }
+        for (int k = 0; k < 4; ++k) c[k] = column_run_sparse(base, stride, P, k);
         return (c[0] + c[1]) + (c[2] + c[3]);
     }
     double s = 0.0;
@@ -723,28 +729,43 @@ __device__ __forceinline__ void resident_iterations(const DevJob &jb0, float *gr
         // at most 1024 row blocks a run holds one row block or none.
         const bool last = r == jb0.iters - 1;
         if (vb == lossb && tid >= kRowBlockThreads - 32) {
+            // Sum t32 covers the runs [32 t32, 32 t32 + 32); run v holds row block floor(P v / T) if the
+            // next run starts at a later one, else nothing, so the non-empty runs of the sum hold the
+            // row blocks [P 32 t32 / T, P 32 (t32 + 1) / T) in order.  The empty runs add +0.0 to a sum
+            // that is never -0.0 (it starts at +0.0 and every term is 0.0 + x): leaving them out
+            // gives the same bits.
             const int t32 = tid - (kRowBlockThreads - 32);
             const float *lp = stage + (size_t)P * D;
-            float x[T / 32];
-            bool has[T / 32];
-#pragma unroll
-            for (int q = 0; q < T / 32; ++q) {
-                const int v = t32 * (T / 32) + q;
-                const int p0 = (P * v) / T, p1 = (P * (v + 1)) / T;
-                has[q] = p1 > p0;
-                x[q] = lp[has[q] ? p0 : 0];
-            }
+            const int pa = (P * (T / 32) * t32) / T, pb = (P * (T / 32) * (t32 + 1)) / T;
             double S = 0.0;
-#pragma unroll
-            for (int q = 0; q < T / 32; ++q) S += has[q] ? 0.0 + (double)x[q] : 0.0;
+            for (int pq = pa; pq < pb; ++pq) S += 0.0 + (double)lp[pq];
             lsum2[t32] = S;
         }
-        for (int col = tid; col < D; col += kRowBlockThreads) {
-            const double tot = column_total(stage + col, D, P);
-            float g, wn;
-            column_update(jb0, r, tot, w_lds[col], g, wn);
-            w_lds[col] = wn;                    // read again by the next row pass, after the barrier below
-            if (vb == 0 && last) { jb0.grad[col] = g; jb0.w[col] = wn; }
+        if (P <= kFinSegs) {
+            // four neighbouring lanes per column, one run of sixteen segments each; their sums meet as
+            // (c0 + c1) + (c2 + c3), the order of column_total (4 D is a multiple of four, so the four
+            // lanes of a column take every trip of this loop together)
+            for (int q = tid; q < 4 * D; q += kRowBlockThreads) {
+                const int col = q >> 2, k = q & 3;
+                const double ck = column_run_sparse(stage + col, D, P, k);
+                const double pair = ck + __shfl_xor(ck, 1, 64);          // c0 + c1 in lanes 0, 1; c2 + c3 in lanes 2, 3
+                const double other = __shfl_xor(pair, 2, 64);
+                if (k == 0) {
+                    const double tot = pair + other;
+                    float g, wn;
+                    column_update(jb0, r, tot, w_lds[col], g, wn);
+                    w_lds[col] = wn;            // read again by the next row pass, after the barrier below
+                    if (vb == 0 && last) { jb0.grad[col] = g; jb0.w[col] = wn; }
+                }
+            }
+        } else {
+            for (int col = tid; col < D; col += kRowBlockThreads) {
+                const double tot = column_total(stage + col, D, P);
+                float g, wn;
+                column_update(jb0, r, tot, w_lds[col], g, wn);
+                w_lds[col] = wn;                // read again by the next row pass, after the barrier below
+                if (vb == 0 && last) { jb0.grad[col] = g; jb0.w[col] = wn; }
+            }
         }
         __syncthreads();
         if (vb == lossb && tid == kRowBlockThreads - 1) {
