@@ -638,6 +638,10 @@ __device__ __forceinline__ double column_total(const float *base, const int stri
 
 constexpr int kResidentStage = kResidentMaxPartials + 1032;    // partial gradients + partial losses of a tiny job
 
+// Words of the exchange a thread requests before it waits for any of them: 17 x 256 threads cover the
+// 8256 words of a 64-block, 128-column job in two rounds of loads instead of three.
+constexpr int kResidentInFlight = 17;
+
 template <int LPR, int C, int B, int LOSS>
 __device__ __forceinline__ void resident_iterations(const DevJob &jb0, float *gred, float *lred, float *w_lds,
                                                     double *wn2_lds, float *stage, double *lsum2, int *abandoned) {
@@ -681,13 +685,13 @@ __device__ __forceinline__ void resident_iterations(const DevJob &jb0, float *gr
         if (has_tile) tile_compute<LPR, C, B, LOSS, false>(xv, ysel, rsel, N, wv, ga, lsum, lane);
         row_reduce_store<LPR, C, B, true>(ga, lsum, D, reinterpret_cast<float *>(buf + (size_t)vb * D),
                                           reinterpret_cast<float *>(buf + (size_t)P * D + vb), gred, lred, wid, lane, tag);
-        // every partial of the job into LDS: sixteen words in flight per thread, each loaded again until
+        // every partial of the job into LDS: kResidentInFlight words in flight per thread, each loaded again until
         // it carries this iteration's tag
         bool gave_up = false;
-        for (int i = tid; i < n_words; i += 16 * kRowBlockThreads) {
-            unsigned long long v[16];
+        for (int i = tid; i < n_words; i += kResidentInFlight * kRowBlockThreads) {
+            unsigned long long v[kResidentInFlight];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
+            for (int u = 0; u < kResidentInFlight; ++u) {
                 const int k = i + u * kRowBlockThreads;
                 v[u] = k < n_words ? __hip_atomic_load(buf + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                                    : ((unsigned long long)tag << 32);
@@ -696,7 +700,7 @@ __device__ __forceinline__ void resident_iterations(const DevJob &jb0, float *gr
             while (true) {
                 bool all = true;
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
+                for (int u = 0; u < kResidentInFlight; ++u) {
                     if ((unsigned)(v[u] >> 32) != tag) {
                         v[u] = __hip_atomic_load(buf + i + u * kRowBlockThreads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         all = false;
@@ -711,7 +715,7 @@ __device__ __forceinline__ void resident_iterations(const DevJob &jb0, float *gr
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
+            for (int u = 0; u < kResidentInFlight; ++u) {
                 const int k = i + u * kRowBlockThreads;
                 if (k < n_words) stage[k] = __uint_as_float((unsigned)v[u]);
             }
