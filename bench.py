@@ -331,6 +331,27 @@ def bench_sweep(args):
     rerun_identical = bool(torch.equal(h1, hist[:K]) and torch.equal(W1, W))
 
     sec = t1 - t0
+    # the first 16 of the models alone: a group that small runs the one-pass kernel (X read once)
+    M16 = min(16, M)
+    W16 = torch.zeros(M16, p.D, device="cuda")
+    G16 = torch.zeros(M16, p.D, device="cuda")
+    hist16 = torch.zeros(max(K, 1), M16, device="cuda")
+    glm.glm_sweep(p.X, p.y, p.loss, W16, G16, sp.lams[:M16], sp.etas[:M16], 2, hist16, ws)
+    torch.cuda.synchronize()
+    W16.zero_()
+    t2 = time.perf_counter()
+    glm.glm_sweep(p.X, p.y, p.loss, W16, G16, sp.lams[:M16], sp.etas[:M16], K, hist16, ws)
+    torch.cuda.synchronize()
+    sec16 = time.perf_counter() - t2
+    h16 = hist16[:K].clone()
+    W16.zero_()
+    glm.glm_sweep(p.X, p.y, p.loss, W16, G16, sp.lams[:M16], sp.etas[:M16], K, hist16, ws)
+    torch.cuda.synchronize()
+    small = {"models": M16, "ms_per_step": 1e3 * sec16 / K, "time_vs_all_models": sec16 / sec,
+             "TFLOPs": 4.0 * p.N * p.D * M16 / (sec16 / K) / 1e12,
+             "X_once_GBps": 4.0 * p.N * p.D / (sec16 / K) / 1e9,
+             "rerun_bit_identical": bool(torch.equal(h16, hist16[:K])),
+             "loss_last_model0": float(h16[-1, 0])}
     fwd_ms, bwd_ms = float(np.mean(ms[0::2])), float(np.mean(ms[1::2]))
     flop_each = 2.0 * p.N * p.D * M                 # per matrix product
     x_bytes = 4.0 * p.N * p.D
@@ -353,6 +374,7 @@ def bench_sweep(args):
                      "backward_X_GBps": x_bytes / (bwd_ms * 1e-3) / 1e9},
         "rerun_bit_identical": rerun_identical,
         "loss_first_model0": float(h1[0, 0]), "loss_last_model0": float(h1[-1, 0]),
+        "small_group": small,
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -702,6 +724,8 @@ def extra_configs(args):
                                                "predict_kernel_ms", "allocate_host_ms", "assign_ms", "accumulate_ms",
                                                "executed_TFLOPs", "executed_frac") if k in r},
         }
+        if "small_group" in o:
+            res[f"config{cfg}"]["small_group"] = o["small_group"]
     return res
 
 

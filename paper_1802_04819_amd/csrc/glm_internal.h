@@ -90,6 +90,8 @@ constexpr int kSweepFwdRows = 128;      // rows per forward tile
 constexpr int kSweepBwdRows = 32;       // rows per backward chunk
 constexpr int kSweepBwdCols = 256;      // columns per backward slab
 constexpr int kSweepSplitMax = 128;     // row splits of the backward contraction
+constexpr int kSweepFusedM = 16;        // a group of at most this many models runs the one-pass kernel (row lengths it takes)
+constexpr int kSweepFusedBlocksMax = 512;   // blocks of the one-pass kernel = partial gradients per model
 struct SweepArgs {            // one group of at most kSweepM models
     const float *X; const float *y; float *W; float *G;
     float *loss_row;                                // [M] the group's entries of this iteration's history row

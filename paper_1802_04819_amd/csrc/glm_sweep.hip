@@ -16,6 +16,8 @@
 //
 // Lane layout of the 32x32x2 instruction (lane l of 64): A[i][k] from lane i + 32 k,
 // B[k][j] from lane j + 32 k, D[i][j] in lane j + 32 ((i / 4) % 2), register (i % 4) + 4 (i / 8).
+#include <algorithm>
+
 #include "glm_internal.h"
 #include "glm_loss.h"
 
@@ -316,10 +318,229 @@ __global__ __launch_bounds__(256) void sweep_backward_kernel(
             }
 }
 
+// ------------------------------------------------------------------ one-pass kernel for a group of at most 16 models
+//
+// With 16 models the two products of an iteration are 64 flop per byte of X together: the iteration is
+// bound by the memory, and reading X twice (forward, then backward) costs twice the time.  Here a
+// block keeps a tile of 16 rows x D of X in LDS and uses it for both products, so X is read once and
+// R never leaves the chip.  v_mfma_f32_16x16x4_f32; lane l = (l % 16, l / 16) = (c, g):
+//   A[i][k] from lane (i, k), B[k][j] from lane (j, k), D[i][j] in lane (j, i / 4), register i % 4.
+//   forward : Z[row][model] = sum_k X[row][k] W[model][k].  The wave takes the 16-wide k steps
+//             4 u + wave; its slice of W stays in registers for the whole launch (lane (model, g)
+//             holds W[model][16 s + 4 g .. + 3] of step s, matching the 128-bit LDS read of lane
+//             (row, g) from the tile).  The four waves' partial Z meet in LDS and are added in wave
+//             order; thread (model, row) forms loss and residual and keeps its loss sum.
+//   backward: Gp[model][col] += sum_row R[row][model] X[row][col].  The wave takes the 64-column
+//             groups 4 u + wave; lane (model, g) supplies R[4 g + q][model] in step q, lane (dd, g)
+//             X[4 g + q][64 grp + 4 dd + t] for column tile t from one 128-bit read, so tile t
+//             covers the columns 64 grp + 4 dd + t and the four tiles of a lane store as one float4.
+// Blocks walk the row tiles with stride gridDim and write one partial [16, D] each; the grid is a
+// function of N only, so the order of all additions is fixed by the shape.
+constexpr int kFusedM = kSweepFusedM;
+constexpr int kFusedRows = 16;
+constexpr int kFusedZld = 20;         // LDS row stride of the 16 x 16 exchange tiles
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// Waves per block: eight for the long rows, so that a wave's slice of W, its accumulators and its share
+// of the next tile fit in 128 registers and two blocks (16 waves) share a compute unit.
+constexpr int fused_waves(int dmax) { return dmax >= 512 ? 8 : 4; }
+
+size_t sweep_fused_lds_bytes(int D, int dmax) {
+    return sizeof(float) * ((size_t)kFusedRows * (D + 4) + (size_t)fused_waves(dmax) * kFusedM * kFusedZld +
+                            kFusedM * kFusedZld);
+}
+
+template <int DMAX>
+__global__ __launch_bounds__(64 * fused_waves(DMAX), 4) void sweep_fused_kernel(      // four waves per SIMD
+
+    const float *__restrict__ X, const float *__restrict__ y, const float *__restrict__ W,
+    long long N, int D, int M, int loss, float *__restrict__ Gpart, float *__restrict__ lossP) {
+    extern __shared__ f4 fused_smem[];
+    constexpr int NW = fused_waves(DMAX);
+    constexpr int NT = 64 * NW;
+    constexpr int NSW = DMAX / (16 * NW);   // k steps of 16 per wave (forward)
+    constexpr int NGW = DMAX / (64 * NW);   // column groups of 64 per wave (backward)
+    constexpr int TPR = DMAX / 4;           // threads side by side on a row of the tile when it is fetched
+    constexpr int RP = NT / TPR;            // rows fetched per pass
+    constexpr int NQ = kFusedRows / RP;     // passes = float4 slots of the tile per thread
+    static_assert(NSW >= 1 && NGW >= 1 && RP >= 1 && NQ * RP == kFusedRows, "tile does not divide among the waves");
+    const int LD = D + 4;                   // row stride of the tile in LDS (floats)
+    float *Xs = reinterpret_cast<float *>(fused_smem);
+    float *zs = Xs + kFusedRows * LD;                   // [NW waves][16 models][kFusedZld]
+    float *rs = zs + NW * kFusedM * kFusedZld;          // [16 models][kFusedZld]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lc = lane & 15, lg = lane >> 4;
+    const int D4 = D >> 2;
+    const long long ntiles = (N + kFusedRows - 1) / kFusedRows;
+    const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X);
+
+    // the wave's slice of W: zero for models past M and steps past D
+    f4 wreg[NSW];
+#pragma unroll
+    for (int u = 0; u < NSW; ++u) {
+        const int st = NW * u + wave;
+        const bool ok = lc < M && 16 * st < D;
+        const f4 t = reinterpret_cast<const f4 *>(W)[(size_t)(lc < M ? lc : 0) * D4 + (16 * st < D ? 4 * st + lg : 0)];
+        wreg[u] = ok ? t : f4{0.f, 0.f, 0.f, 0.f};
+    }
+    // fetching a tile: thread (fr, fc) takes float4 column fc of the rows fr, fr + RP, ...
+    const int fc = tid % TPR, fr = tid / TPR;
+    const bool fetches = fc < D4;
+    float *const ldst = Xs + fr * LD + 4 * fc;
+    const int lj = (tid >> 4) & 15, li = tid & 15;      // loss phase: thread (model lj, row li) of the first 256
+
+    floatx4 acc[NGW][4];
+#pragma unroll
+    for (int u = 0; u < NGW; ++u)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[u][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float lsum = 0.0f;
+
+    // A tile is 16 whole rows: one contiguous piece of X.  Rows past N (last tile only) read row N - 1;
+    // their residuals are set to zero below.
+    f4 xr[NQ];
+    float yr = 0.0f;
+    // Slot q of the thread in the tile whose first row is R0: row q RP + fr, or the last row of X where
+    // the tile reaches past it (last tile only); one form for both cases keeps the slots in one set of
+    // registers.
+#define SLAQ_FUSED_LOAD(Q, TB, LIM)                                                              \
+    xr[Q] = load_nt_at(TB, (unsigned)(((Q) * RP + fr < (LIM) ? (Q) * RP + fr : (LIM)) * D4 + (fetches ? fc : 0)) * 16u)
+#define SLAQ_FUSED_STASH()                                                                       \
+    {                                                                                            \
+        if (fetches) {                                                                           \
+            _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                       \
+                *reinterpret_cast<f4 *>(ldst + q * RP * LD) = xr[q];                             \
+        }                                                                                        \
+    }
+
+    long long tile = blockIdx.x;
+    float yc = 0.0f;
+    if (tile < ntiles) {
+        const long long r0 = tile * kFusedRows;
+        const int lim = (int)(N - 1 - r0 < kFusedRows - 1 ? N - 1 - r0 : kFusedRows - 1);
+        const f4 *__restrict__ tb = X4 + r0 * D4;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) SLAQ_FUSED_LOAD(q, tb, lim);
+        yc = y[r0 + li < N ? r0 + li : N - 1];
+        SLAQ_FUSED_STASH()
+    }
+    __syncthreads();
+    for (; tile < ntiles; tile += gridDim.x) {
+        const long long nt = tile + gridDim.x;
+        const bool more = nt < ntiles;
+        // the next tile's loads go out before the products (one per forward step, between the matrix
+        // instructions, was measured 5 % slower)
+        if (more) {
+            const long long nr0 = nt * kFusedRows;
+            const int nlim = (int)(N - 1 - nr0 < kFusedRows - 1 ? N - 1 - nr0 : kFusedRows - 1);
+            const f4 *__restrict__ ntb = X4 + nr0 * D4;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) SLAQ_FUSED_LOAD(q, ntb, nlim);
+            yr = y[nr0 + li < N ? nr0 + li : N - 1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // forward: the wave's share of Z
+        floatx4 zacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < NSW; ++u) {
+            const int st = NW * u + wave;
+            if (16 * st < D) {
+                const f4 xa = *reinterpret_cast<const f4 *>(Xs + lc * LD + 16 * st + 4 * lg);
+                zacc = mfma16(xa.x, wreg[u].x, zacc);
+                zacc = mfma16(xa.y, wreg[u].y, zacc);
+                zacc = mfma16(xa.z, wreg[u].z, zacc);
+                zacc = mfma16(xa.w, wreg[u].w, zacc);
+            }
+        }
+        // lane (model lc, lg) holds Z[4 lg + r][lc]
+        *reinterpret_cast<f4 *>(zs + (wave * kFusedM + lc) * kFusedZld + 4 * lg) = f4{zacc[0], zacc[1], zacc[2], zacc[3]};
+        __syncthreads();
+
+        // loss and residual: thread (model lj, row li); the waves' shares are added in wave order
+        if (tid < kFusedM * kFusedRows) {
+            const float *zp = zs + lj * kFusedZld + li;
+            float z = zp[0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) z = z + zp[w * kFusedM * kFusedZld];
+            float l, r;
+            loss_residual(loss, z, yc, l, r);
+            const bool valid = tile * kFusedRows + li < N;
+            l = valid ? l : 0.0f;
+            r = valid ? r : 0.0f;
+            lsum = lsum + l;
+            rs[lj * kFusedZld + li] = r;
+        }
+        __syncthreads();
+
+        // backward: the wave's column groups
+        {
+            const f4 av = *reinterpret_cast<const f4 *>(rs + lc * kFusedZld + 4 * lg);
+#pragma unroll
+            for (int u = 0; u < NGW; ++u) {
+                const int grp = NW * u + wave;
+                if (64 * grp < D) {
+                    const float *xb = Xs + (4 * lg) * LD + 64 * grp + 4 * lc;
+                    const f4 b0 = *reinterpret_cast<const f4 *>(xb);
+                    const f4 b1 = *reinterpret_cast<const f4 *>(xb + LD);
+                    const f4 b2 = *reinterpret_cast<const f4 *>(xb + 2 * LD);
+                    const f4 b3 = *reinterpret_cast<const f4 *>(xb + 3 * LD);
+                    acc[u][0] = mfma16(av.x, b0.x, acc[u][0]); acc[u][1] = mfma16(av.x, b0.y, acc[u][1]);
+                    acc[u][2] = mfma16(av.x, b0.z, acc[u][2]); acc[u][3] = mfma16(av.x, b0.w, acc[u][3]);
+                    acc[u][0] = mfma16(av.y, b1.x, acc[u][0]); acc[u][1] = mfma16(av.y, b1.y, acc[u][1]);
+                    acc[u][2] = mfma16(av.y, b1.z, acc[u][2]); acc[u][3] = mfma16(av.y, b1.w, acc[u][3]);
+                    acc[u][0] = mfma16(av.z, b2.x, acc[u][0]); acc[u][1] = mfma16(av.z, b2.y, acc[u][1]);
+                    acc[u][2] = mfma16(av.z, b2.z, acc[u][2]); acc[u][3] = mfma16(av.z, b2.w, acc[u][3]);
+                    acc[u][0] = mfma16(av.w, b3.x, acc[u][0]); acc[u][1] = mfma16(av.w, b3.y, acc[u][1]);
+                    acc[u][2] = mfma16(av.w, b3.z, acc[u][2]); acc[u][3] = mfma16(av.w, b3.w, acc[u][3]);
+                }
+            }
+        }
+        __syncthreads();
+        if (more) {
+            SLAQ_FUSED_STASH()
+            yc = yr;
+        }
+        __syncthreads();
+    }
+#undef SLAQ_FUSED_LOAD
+#undef SLAQ_FUSED_STASH
+
+    // the block's partial gradient: lane (dd = lc, lg) holds models 4 lg + r, columns 64 grp + 4 dd + t
+    float *__restrict__ gp = Gpart + (size_t)blockIdx.x * kFusedM * D;
+#pragma unroll
+    for (int u = 0; u < NGW; ++u) {
+        const int grp = NW * u + wave;
+        const int col = 64 * grp + 4 * lc;
+        if (col < D) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                *reinterpret_cast<f4 *>(gp + (size_t)(4 * lg + r) * D + col) =
+                    f4{acc[u][0][r], acc[u][1][r], acc[u][2][r], acc[u][3][r]};
+        }
+    }
+    // the block's loss sums: rows in order for every model
+    if (tid < kFusedM * kFusedRows) zs[lj * kFusedZld + li] = lsum;
+    __syncthreads();
+    if (tid < M) {
+        float sacc = zs[tid * kFusedZld];
+#pragma unroll
+        for (int i = 1; i < kFusedRows; ++i) sacc = sacc + zs[tid * kFusedZld + i];
+        lossP[(size_t)tid * gridDim.x + blockIdx.x] = sacc;
+    }
+}
+
 // One block per model: column sums of the S partials, update, loss.
 __global__ __launch_bounds__(1024) void sweep_finalize_kernel(
     const float *__restrict__ Gpart, const float *__restrict__ lossP, int S, int T, long long N,
-    int D, int M, const float *__restrict__ lambdas, const float *__restrict__ steps,
+    int D, int M, size_t gstride, const float *__restrict__ lambdas, const float *__restrict__ steps,
     float *__restrict__ W, float *__restrict__ G, float *__restrict__ loss_row) {
     __shared__ double red[1024];
     __shared__ double red2[32];
@@ -337,11 +558,11 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(
         for (; sidx + 16 <= S; sidx += 16) {
             float v[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) v[u] = gp[(size_t)(sidx + u) * kSweepM * D];
+            for (int u = 0; u < 16; ++u) v[u] = gp[(size_t)(sidx + u) * gstride];
 #pragma unroll
             for (int u = 0; u < 16; ++u) tot += (double)v[u];
         }
-        for (; sidx < S; ++sidx) tot += (double)gp[(size_t)sidx * kSweepM * D];
+        for (; sidx < S; ++sidx) tot += (double)gp[(size_t)sidx * gstride];
         const float wj = W[(size_t)m * D + d];
         const double g = tot * invN + lam * (double)wj;
         ww += (double)wj * (double)wj;
@@ -375,8 +596,57 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(
     if (tid == 0) loss_row[m] = (float)(out[1] * invN + 0.5 * lam * out[0]);
 }
 
+// A group of at most 16 models with a row length the one-pass kernel takes.
+bool sweep_uses_fused(int D, int M) { return M <= kFusedM && D <= 1024 && (D % 16) == 0; }
+
+// Blocks of the one-pass kernel: a function of N only, and no more than the workspace areas of the
+// two-pass kernels hold partials for (16 G loss sums in 64 T, 16 G gradient rows in 64 S).
+int sweep_fused_blocks(long long N) {
+    const long long tiles = (N + kFusedRows - 1) / kFusedRows;
+    const long long T = (N + kSweepFwdRows - 1) / kSweepFwdRows;
+    const long long S = std::min<long long>((N + kSweepBwdRows - 1) / kSweepBwdRows, kSweepSplitMax);
+    return (int)std::min<long long>(std::min<long long>(tiles, kSweepFusedBlocksMax), std::min<long long>(4 * T, 4 * S));
+}
+
+static hipError_t launch_sweep_fused(const SweepArgs &a, hipEvent_t *ev, hipStream_t st) {
+    hipError_t e;
+    const int G = sweep_fused_blocks(a.N);
+    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
+#define SLAQ_FUSED_LAUNCH(DMAX)                                                                              \
+    {                                                                                                        \
+        static bool attr_set[64];               /* per device: the kernel may use more than 64 KB of LDS */  \
+        int dev = 0;                                                                                         \
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;                                                \
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;                                              \
+        if (!attr_set[dev]) {                                                                                \
+            if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&sweep_fused_kernel<DMAX>),          \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,                         \
+                                         (int)sweep_fused_lds_bytes(DMAX, DMAX))) != hipSuccess)             \
+                return e;                                                                                    \
+            attr_set[dev] = true;                                                                            \
+        }                                                                                                    \
+        hipLaunchKernelGGL(sweep_fused_kernel<DMAX>, dim3((unsigned)G), dim3(64 * fused_waves(DMAX)),        \
+                           sweep_fused_lds_bytes(a.D, DMAX), st, a.X, a.y, a.W, a.N, a.D, a.M, a.loss,       \
+                           a.Gpart, a.lossP);                                                                \
+    }
+    if (a.D <= 256) SLAQ_FUSED_LAUNCH(256)
+    else if (a.D <= 512) SLAQ_FUSED_LAUNCH(512)
+    else SLAQ_FUSED_LAUNCH(1024)
+#undef SLAQ_FUSED_LAUNCH
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev) {       // the one kernel stands where the forward kernel stands; an empty interval for the backward one
+        if ((e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
+        if ((e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
+        if ((e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(sweep_finalize_kernel, dim3((unsigned)a.M), dim3(1024), 0, st, a.Gpart, a.lossP, G, G, a.N,
+                       a.D, a.M, (size_t)kFusedM * a.D, a.lambdas, a.steps, a.W, a.G, a.loss_row);
+    return hipGetLastError();
+}
+
 hipError_t launch_sweep_iteration(const SweepArgs &a, int k, hipEvent_t *ev, hipStream_t st) {
     hipError_t e;
+    if (sweep_uses_fused(a.D, a.M)) return launch_sweep_fused(a, ev, st);
     if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
     const bool half = a.M <= 32;
     // the plain variant: no ragged last K-chunk and a tile full of models
@@ -400,7 +670,8 @@ hipError_t launch_sweep_iteration(const SweepArgs &a, int k, hipEvent_t *ev, hip
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
     hipLaunchKernelGGL(sweep_finalize_kernel, dim3((unsigned)a.M), dim3(1024), 0, st, a.Gpart,
-                       a.lossP, a.S, a.T, a.N, a.D, a.M, a.lambdas, a.steps, a.W, a.G, a.loss_row);
+                       a.lossP, a.S, a.T, a.N, a.D, a.M, (size_t)kSweepM * a.D, a.lambdas, a.steps, a.W, a.G,
+                       a.loss_row);
     (void)k;
     return hipGetLastError();
 }

@@ -33,6 +33,12 @@ def _run_sweep(p, lams, etas, K, W0=None):
     # more than one group of 64 models, a last group of at most 32, row lengths that are not multiples of 32
     (synth.LOGISTIC, 3000, 128, 128), (synth.SQUARED, 2000, 96, 100), (synth.LOGISTIC, 5000, 256, 16),
     (synth.HINGE, 1500, 48, 32), (synth.LOGISTIC, 2222, 100, 70), (synth.SQUARED, 900, 4, 3), (synth.LOGISTIC, 700, 1028, 9),
+    # groups of at most 16 models on row lengths that are multiples of 16 up to 1024 (one-pass kernel): a last
+    # tile of fewer than 16 rows, fewer rows than a tile, several tiles per block, every row-length class,
+    # a last group of 6 after a group of 64
+    (synth.HINGE, 2007, 1024, 16), (synth.SQUARED, 15, 16, 2), (synth.LOGISTIC, 9601, 512, 9),
+    (synth.HINGE, 40000, 768, 12), (synth.LOGISTIC, 3000, 48, 16), (synth.LOGISTIC, 2500, 128, 70),
+    (synth.SQUARED, 5000, 272, 7), (synth.LOGISTIC, 16, 1024, 1),
 ])
 def test_sweep_matches_oracle_trajectories(loss, N, D, M):
     _say(f"[case] sweep parity loss={loss} N={N} D={D} M={M}")
@@ -96,7 +102,7 @@ def test_sweep_reruns_are_bit_identical():
         assert all(torch.equal(a, b) for a, b in zip(outs[0], o))
 
 
-@pytest.mark.parametrize("M_full,M_less", [(64, 63), (32, 31), (128, 127)])
+@pytest.mark.parametrize("M_full,M_less", [(64, 63), (32, 31), (128, 127), (16, 15), (80, 65)])
 def test_sweep_full_and_partial_tiles_give_the_same_bits(M_full, M_less):
     """A tile full of models runs the forward kernel without masks, a partial tile the one with them;
     both add the same numbers in the same order, so a model's trajectory does not depend on how many
