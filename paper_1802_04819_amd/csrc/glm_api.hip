@@ -326,9 +326,13 @@ SweepLayout make_sweep_layout(long long N, int D, int M) {
     size_t off = 0;
     const size_t Mpad = (size_t)(M + kSweepM - 1) / kSweepM * kSweepM;
     L.hyper = off; off = align_up(off + sizeof(float) * 2 * Mpad);
-    L.R = off;     off = align_up(off + sizeof(float) * (size_t)N * kSweepM);
-    L.lossP = off; off = align_up(off + sizeof(float) * (size_t)kSweepM * L.T);
-    L.Gpart = off; off = align_up(off + sizeof(float) * (size_t)L.S * kSweepM * D);
+    // residuals of the two-pass kernels; a sweep whose only group runs the one-pass kernel keeps none
+    const bool needs_R = !sweep_uses_fused(D, M);
+    L.R = off;     off = align_up(off + (needs_R ? sizeof(float) * (size_t)N * kSweepM : 0));
+    // the one-pass kernel of a small last group keeps kSweepFusedM rows per block in the same two areas
+    const size_t Gf = sweep_uses_fused(D, 1) ? (size_t)sweep_fused_blocks(N, D) : 0;
+    L.lossP = off; off = align_up(off + sizeof(float) * std::max((size_t)kSweepM * L.T, Gf * kSweepFusedM));
+    L.Gpart = off; off = align_up(off + sizeof(float) * std::max((size_t)L.S * kSweepM, Gf * kSweepFusedM) * D);
     L.total = off;
     return L;
 }

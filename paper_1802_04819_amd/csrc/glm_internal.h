@@ -91,7 +91,9 @@ constexpr int kSweepBwdRows = 32;       // rows per backward chunk
 constexpr int kSweepBwdCols = 256;      // columns per backward slab
 constexpr int kSweepSplitMax = 128;     // row splits of the backward contraction
 constexpr int kSweepFusedM = 16;        // a group of at most this many models runs the one-pass kernel (row lengths it takes)
-constexpr int kSweepFusedBlocksMax = 512;   // blocks of the one-pass kernel = partial gradients per model
+constexpr int kSweepFusedBlocksMax = 1024;  // most blocks of the one-pass kernel = partial gradients per model
+bool sweep_uses_fused(int D, int M);        // whether a group of M models on rows of D runs the one-pass kernel
+int sweep_fused_blocks(long long N, int D); // its blocks for that shape
 struct SweepArgs {            // one group of at most kSweepM models
     const float *X; const float *y; float *W; float *G;
     float *loss_row;                                // [M] the group's entries of this iteration's history row

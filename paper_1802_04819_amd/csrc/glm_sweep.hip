@@ -347,7 +347,7 @@ __device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c) {
 
 // Waves per block: eight for the long rows, so that a wave's slice of W, its accumulators and its share
 // of the next tile fit in 128 registers and two blocks (16 waves) share a compute unit.
-constexpr int fused_waves(int dmax) { return dmax >= 512 ? 8 : 4; }
+constexpr int fused_waves(int dmax) { return dmax >= 1024 ? 16 : dmax >= 512 ? 8 : 4; }
 
 size_t sweep_fused_lds_bytes(int D, int dmax) {
     return sizeof(float) * ((size_t)kFusedRows * (D + 4) + (size_t)fused_waves(dmax) * kFusedM * kFusedZld +
@@ -356,18 +356,13 @@ size_t sweep_fused_lds_bytes(int D, int dmax) {
 
 template <int DMAX>
 __global__ __launch_bounds__(64 * fused_waves(DMAX), 4) void sweep_fused_kernel(      // four waves per SIMD
-
     const float *__restrict__ X, const float *__restrict__ y, const float *__restrict__ W,
     long long N, int D, int M, int loss, float *__restrict__ Gpart, float *__restrict__ lossP) {
     extern __shared__ f4 fused_smem[];
     constexpr int NW = fused_waves(DMAX);
-    constexpr int NT = 64 * NW;
-    constexpr int NSW = DMAX / (16 * NW);   // k steps of 16 per wave (forward)
-    constexpr int NGW = DMAX / (64 * NW);   // column groups of 64 per wave (backward)
-    constexpr int TPR = DMAX / 4;           // threads side by side on a row of the tile when it is fetched
-    constexpr int RP = NT / TPR;            // rows fetched per pass
-    constexpr int NQ = kFusedRows / RP;     // passes = float4 slots of the tile per thread
-    static_assert(NSW >= 1 && NGW >= 1 && RP >= 1 && NQ * RP == kFusedRows, "tile does not divide among the waves");
+    constexpr int NGW = DMAX / (64 * NW);   // column groups of 64 per wave
+    constexpr int NQ = 4 * NGW;             // float4 slots of the tile per lane: 16 rows x 64 columns per group
+    static_assert(NGW >= 1, "fewer column groups than waves");
     const int LD = D + 4;                   // row stride of the tile in LDS (floats)
     float *Xs = reinterpret_cast<float *>(fused_smem);
     float *zs = Xs + kFusedRows * LD;                   // [NW waves][16 models][kFusedZld]
@@ -381,19 +376,21 @@ __global__ __launch_bounds__(64 * fused_waves(DMAX), 4) void sweep_fused_kernel(
     const long long ntiles = (N + kFusedRows - 1) / kFusedRows;
     const f4 *__restrict__ X4 = reinterpret_cast<const f4 *>(X);
 
-    // the wave's slice of W: zero for models past M and steps past D
-    f4 wreg[NSW];
+    // The wave owns the column groups NW u + wave of the tile: it fetches them, puts them into LDS,
+    // takes their 16-wide k steps in the forward product and their columns in the backward product.
+    // Nobody else touches them, so the tile itself needs no barrier: the wave's own LDS operations
+    // are carried out in program order.
+    // its slice of W: zero for models past M and steps past D
+    f4 wreg[NGW][4];
 #pragma unroll
-    for (int u = 0; u < NSW; ++u) {
-        const int st = NW * u + wave;
-        const bool ok = lc < M && 16 * st < D;
-        const f4 t = reinterpret_cast<const f4 *>(W)[(size_t)(lc < M ? lc : 0) * D4 + (16 * st < D ? 4 * st + lg : 0)];
-        wreg[u] = ok ? t : f4{0.f, 0.f, 0.f, 0.f};
-    }
-    // fetching a tile: thread (fr, fc) takes float4 column fc of the rows fr, fr + RP, ...
-    const int fc = tid % TPR, fr = tid / TPR;
-    const bool fetches = fc < D4;
-    float *const ldst = Xs + fr * LD + 4 * fc;
+    for (int u = 0; u < NGW; ++u)
+#pragma unroll
+        for (int sidx = 0; sidx < 4; ++sidx) {
+            const int st = 4 * (NW * u + wave) + sidx;
+            const bool ok = lc < M && 16 * st < D;
+            const f4 t = reinterpret_cast<const f4 *>(W)[(size_t)(lc < M ? lc : 0) * D4 + (16 * st < D ? 4 * st + lg : 0)];
+            wreg[u][sidx] = ok ? t : f4{0.f, 0.f, 0.f, 0.f};
+        }
     const int lj = (tid >> 4) & 15, li = tid & 15;      // loss phase: thread (model lj, row li) of the first 256
 
     floatx4 acc[NGW][4];
@@ -403,21 +400,26 @@ __global__ __launch_bounds__(64 * fused_waves(DMAX), 4) void sweep_fused_kernel(
         for (int t = 0; t < 4; ++t) acc[u][t] = floatx4{0.f, 0.f, 0.f, 0.f};
     float lsum = 0.0f;
 
-    // A tile is 16 whole rows: one contiguous piece of X.  Rows past N (last tile only) read row N - 1;
-    // their residuals are set to zero below.
+    // Slot (u, q) of the lane: row 4 lg + q, float4 column 16 (NW u + wave) + lc: a load instruction
+    // takes 256 contiguous bytes of each of four rows.  Rows past N (last tile only) read row N - 1 and
+    // get residual zero below; one form for both cases keeps the slots in one set of registers.
     f4 xr[NQ];
     float yr = 0.0f;
-    // Slot q of the thread in the tile whose first row is R0: row q RP + fr, or the last row of X where
-    // the tile reaches past it (last tile only); one form for both cases keeps the slots in one set of
-    // registers.
-#define SLAQ_FUSED_LOAD(Q, TB, LIM)                                                              \
-    xr[Q] = load_nt_at(TB, (unsigned)(((Q) * RP + fr < (LIM) ? (Q) * RP + fr : (LIM)) * D4 + (fetches ? fc : 0)) * 16u)
-#define SLAQ_FUSED_STASH()                                                                       \
-    {                                                                                            \
-        if (fetches) {                                                                           \
-            _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                       \
-                *reinterpret_cast<f4 *>(ldst + q * RP * LD) = xr[q];                             \
-        }                                                                                        \
+#define SLAQ_FUSED_LOAD(U, Q, TB, LIM)                                                                      \
+    {                                                                                                       \
+        const int c4_ = 16 * (NW * (U) + wave) + lc;                                                        \
+        const int row_ = 4 * lg + (Q) < (LIM) ? 4 * lg + (Q) : (LIM);                                       \
+        xr[4 * (U) + (Q)] = load_nt_at(TB, (unsigned)(row_ * D4 + (c4_ < D4 ? c4_ : 0)) * 16u);             \
+    }
+#define SLAQ_FUSED_STASH()                                                                                  \
+    {                                                                                                       \
+        _Pragma("unroll") for (int u = 0; u < NGW; ++u) {                                                   \
+            const int c4_ = 16 * (NW * u + wave) + lc;                                                      \
+            if (c4_ < D4) {                                                                                 \
+                _Pragma("unroll") for (int q = 0; q < 4; ++q)                                               \
+                    *reinterpret_cast<f4 *>(Xs + (4 * lg + q) * LD + 4 * c4_) = xr[4 * u + q];              \
+            }                                                                                               \
+        }                                                                                                   \
     }
 
     long long tile = blockIdx.x;
@@ -427,22 +429,24 @@ __global__ __launch_bounds__(64 * fused_waves(DMAX), 4) void sweep_fused_kernel(
         const int lim = (int)(N - 1 - r0 < kFusedRows - 1 ? N - 1 - r0 : kFusedRows - 1);
         const f4 *__restrict__ tb = X4 + r0 * D4;
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) SLAQ_FUSED_LOAD(q, tb, lim);
-        yc = y[r0 + li < N ? r0 + li : N - 1];
-        SLAQ_FUSED_STASH()
+        for (int u = 0; u < NGW; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) SLAQ_FUSED_LOAD(u, q, tb, lim)
+        yr = y[r0 + li < N ? r0 + li : N - 1];
     }
-    __syncthreads();
     for (; tile < ntiles; tile += gridDim.x) {
+        // the tile's columns into LDS, then the request for the next tile's
+        SLAQ_FUSED_STASH()
+        yc = yr;
         const long long nt = tile + gridDim.x;
-        const bool more = nt < ntiles;
-        // the next tile's loads go out before the products (one per forward step, between the matrix
-        // instructions, was measured 5 % slower)
-        if (more) {
+        if (nt < ntiles) {
             const long long nr0 = nt * kFusedRows;
             const int nlim = (int)(N - 1 - nr0 < kFusedRows - 1 ? N - 1 - nr0 : kFusedRows - 1);
             const f4 *__restrict__ ntb = X4 + nr0 * D4;
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) SLAQ_FUSED_LOAD(q, ntb, nlim);
+            for (int u = 0; u < NGW; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) SLAQ_FUSED_LOAD(u, q, ntb, nlim)
             yr = y[nr0 + li < N ? nr0 + li : N - 1];
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -450,16 +454,18 @@ __global__ __launch_bounds__(64 * fused_waves(DMAX), 4) void sweep_fused_kernel(
         // forward: the wave's share of Z
         floatx4 zacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < NSW; ++u) {
-            const int st = NW * u + wave;
-            if (16 * st < D) {
-                const f4 xa = *reinterpret_cast<const f4 *>(Xs + lc * LD + 16 * st + 4 * lg);
-                zacc = mfma16(xa.x, wreg[u].x, zacc);
-                zacc = mfma16(xa.y, wreg[u].y, zacc);
-                zacc = mfma16(xa.z, wreg[u].z, zacc);
-                zacc = mfma16(xa.w, wreg[u].w, zacc);
+        for (int u = 0; u < NGW; ++u)
+#pragma unroll
+            for (int sidx = 0; sidx < 4; ++sidx) {
+                const int st = 4 * (NW * u + wave) + sidx;
+                if (16 * st < D) {
+                    const f4 xa = *reinterpret_cast<const f4 *>(Xs + lc * LD + 16 * st + 4 * lg);
+                    zacc = mfma16(xa.x, wreg[u][sidx].x, zacc);
+                    zacc = mfma16(xa.y, wreg[u][sidx].y, zacc);
+                    zacc = mfma16(xa.z, wreg[u][sidx].z, zacc);
+                    zacc = mfma16(xa.w, wreg[u][sidx].w, zacc);
+                }
             }
-        }
         // lane (model lc, lg) holds Z[4 lg + r][lc]
         *reinterpret_cast<f4 *>(zs + (wave * kFusedM + lc) * kFusedZld + 4 * lg) = f4{zacc[0], zacc[1], zacc[2], zacc[3]};
         __syncthreads();
@@ -487,28 +493,28 @@ __global__ __launch_bounds__(64 * fused_waves(DMAX), 4) void sweep_fused_kernel(
             for (int u = 0; u < NGW; ++u) {
                 const int grp = NW * u + wave;
                 if (64 * grp < D) {
+                    // two rows of the group in flight at a time: all four at once cost the registers that
+                    // the next tile's slots need
                     const float *xb = Xs + (4 * lg) * LD + 64 * grp + 4 * lc;
-                    const f4 b0 = *reinterpret_cast<const f4 *>(xb);
-                    const f4 b1 = *reinterpret_cast<const f4 *>(xb + LD);
-                    const f4 b2 = *reinterpret_cast<const f4 *>(xb + 2 * LD);
-                    const f4 b3 = *reinterpret_cast<const f4 *>(xb + 3 * LD);
+                    f4 b0 = *reinterpret_cast<const f4 *>(xb);
+                    f4 b1 = *reinterpret_cast<const f4 *>(xb + LD);
+                    __builtin_amdgcn_sched_barrier(0);
                     acc[u][0] = mfma16(av.x, b0.x, acc[u][0]); acc[u][1] = mfma16(av.x, b0.y, acc[u][1]);
                     acc[u][2] = mfma16(av.x, b0.z, acc[u][2]); acc[u][3] = mfma16(av.x, b0.w, acc[u][3]);
+                    b0 = *reinterpret_cast<const f4 *>(xb + 2 * LD);
+                    __builtin_amdgcn_sched_barrier(0);
                     acc[u][0] = mfma16(av.y, b1.x, acc[u][0]); acc[u][1] = mfma16(av.y, b1.y, acc[u][1]);
                     acc[u][2] = mfma16(av.y, b1.z, acc[u][2]); acc[u][3] = mfma16(av.y, b1.w, acc[u][3]);
-                    acc[u][0] = mfma16(av.z, b2.x, acc[u][0]); acc[u][1] = mfma16(av.z, b2.y, acc[u][1]);
-                    acc[u][2] = mfma16(av.z, b2.z, acc[u][2]); acc[u][3] = mfma16(av.z, b2.w, acc[u][3]);
-                    acc[u][0] = mfma16(av.w, b3.x, acc[u][0]); acc[u][1] = mfma16(av.w, b3.y, acc[u][1]);
-                    acc[u][2] = mfma16(av.w, b3.z, acc[u][2]); acc[u][3] = mfma16(av.w, b3.w, acc[u][3]);
+                    b1 = *reinterpret_cast<const f4 *>(xb + 3 * LD);
+                    __builtin_amdgcn_sched_barrier(0);
+                    acc[u][0] = mfma16(av.z, b0.x, acc[u][0]); acc[u][1] = mfma16(av.z, b0.y, acc[u][1]);
+                    acc[u][2] = mfma16(av.z, b0.z, acc[u][2]); acc[u][3] = mfma16(av.z, b0.w, acc[u][3]);
+                    acc[u][0] = mfma16(av.w, b1.x, acc[u][0]); acc[u][1] = mfma16(av.w, b1.y, acc[u][1]);
+                    acc[u][2] = mfma16(av.w, b1.z, acc[u][2]); acc[u][3] = mfma16(av.w, b1.w, acc[u][3]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
-        __syncthreads();
-        if (more) {
-            SLAQ_FUSED_STASH()
-            yc = yr;
-        }
-        __syncthreads();
     }
 #undef SLAQ_FUSED_LOAD
 #undef SLAQ_FUSED_STASH
@@ -527,6 +533,7 @@ __global__ __launch_bounds__(64 * fused_waves(DMAX), 4) void sweep_fused_kernel(
         }
     }
     // the block's loss sums: rows in order for every model
+    __syncthreads();                                    // the last tile's partial Z has been read
     if (tid < kFusedM * kFusedRows) zs[lj * kFusedZld + li] = lsum;
     __syncthreads();
     if (tid < M) {
@@ -599,18 +606,19 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(
 // A group of at most 16 models with a row length the one-pass kernel takes.
 bool sweep_uses_fused(int D, int M) { return M <= kFusedM && D <= 1024 && (D % 16) == 0; }
 
-// Blocks of the one-pass kernel: a function of N only, and no more than the workspace areas of the
-// two-pass kernels hold partials for (16 G loss sums in 64 T, 16 G gradient rows in 64 S).
-int sweep_fused_blocks(long long N) {
+// Blocks of the one-pass kernel = partial gradients and loss sums per model: a function of the shape
+// only, so the order of all additions is fixed by the shape.  As many as the chip holds at once of the
+// instantiation that takes the row length (one 16-wave block per compute unit for the longest rows,
+// two 8-wave blocks, four 4-wave blocks), and no more than there are tiles.
+int sweep_fused_blocks(long long N, int D) {
     const long long tiles = (N + kFusedRows - 1) / kFusedRows;
-    const long long T = (N + kSweepFwdRows - 1) / kSweepFwdRows;
-    const long long S = std::min<long long>((N + kSweepBwdRows - 1) / kSweepBwdRows, kSweepSplitMax);
-    return (int)std::min<long long>(std::min<long long>(tiles, kSweepFusedBlocksMax), std::min<long long>(4 * T, 4 * S));
+    const int cap = D > 512 ? kSweepFusedBlocksMax / 4 : D > 256 ? kSweepFusedBlocksMax / 2 : kSweepFusedBlocksMax;
+    return (int)std::min<long long>(tiles, cap);
 }
 
 static hipError_t launch_sweep_fused(const SweepArgs &a, hipEvent_t *ev, hipStream_t st) {
     hipError_t e;
-    const int G = sweep_fused_blocks(a.N);
+    const int G = sweep_fused_blocks(a.N, a.D);
     if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
 #define SLAQ_FUSED_LAUNCH(DMAX)                                                                              \
     {                                                                                                        \
