@@ -152,7 +152,11 @@ int glm_step_batched(glm_job_t *jobs /*HOST [J]*/, int32_t J, const int32_t *all
  *   loss_hist DEVICE [iters, M], entry [k, m] = L_m at the iterate entering iteration k
  *   lambdas, steps  HOST [M]
  * Models run in groups of 64 that take turns on the workspace (the time grows with ceil(M / 64); a
- * group of at most 32 models costs about half a full one).
+ * group of at most 32 models costs about two thirds of a full one; a group of at most 16 models on
+ * rows of a multiple of 16 up to 1024 floats reads X once per iteration instead of twice and costs
+ * about two fifths).  A model's results do not depend on which other models share its group, but a
+ * model in a group of at most 16 is summed in another order than the same model in a larger group
+ * (both within the tolerance of the job it equals).
  * Limits: 1 <= M <= 65536, D a multiple of 4, 4 <= D <= 4096 (else GLM_EINVAL). */
 int glm_sweep(const float *X /*DEVICE*/, const float *y /*DEVICE*/, int64_t N, int32_t D, int32_t M,
               int32_t loss, float *W /*DEVICE*/, float *G /*DEVICE*/,
