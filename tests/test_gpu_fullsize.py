@@ -138,6 +138,29 @@ def test_config4_full_size_every_model():
                                   G[m].cpu().numpy(), chunks=_threads(), tag=f"cfg4 m={m}")
 
 
+def test_config4_full_size_first_16_models_one_pass():
+    _say("[case] config 4 full size: its first 16 models alone (one-pass kernel), every model against the oracle")
+    sp = synth.config4(device="cuda")
+    p, M = sp.base, 16
+    lams, etas = sp.lams[:M], sp.etas[:M]
+    W = torch.zeros(M, p.D, device="cuda"); G = torch.zeros(M, p.D, device="cuda")
+    hist = torch.zeros(5, M, device="cuda")
+    ws = glm.alloc_sweep_workspace(p.X, M)
+    glm.glm_sweep(p.X, p.y, p.loss, W, G, lams, etas, 4, hist, ws)
+    torch.cuda.synchronize()
+    W4 = W.clone()
+    glm.glm_sweep(p.X, p.y, p.loss, W, G, lams, etas, 1, hist[4:], ws)
+    torch.cuda.synchronize()
+    h = hist.cpu().numpy()
+    assert np.all(np.abs(h[0] - np.log(2.0)) < 2e-6)
+    Xn, yn = p.X.cpu().numpy(), p.y.cpu().numpy()
+    for m in range(M):
+        if m % 8 == 0:
+            _say(f"[case] config 4, 16 models: oracle for models {m}..{m + 7} at iterate 4")
+        check_step_against_oracle(p.loss, Xn, yn, W4[m].cpu().numpy(), float(lams[m]), h[4, m],
+                                  G[m].cpu().numpy(), chunks=_threads(), tag=f"cfg4/16 m={m}")
+
+
 def test_sparse_config_full_size_steps():
     _say("[case] sparse configuration full size: logistic 2e6 x 1e6, ~2e8 entries, 6 iterations")
     p = synth.sparse_config(device="cuda")
