@@ -56,6 +56,27 @@ def test_workspace_bytes_depends_on_shape_only():
     assert rc == glm.GLM_OK and c == a
 
 
+def test_sweep_workspace_bytes_with_and_without_a_residual_area():
+    """A sweep of at most 16 models on rows the one-pass kernel takes (a multiple of 16 floats, at most
+    1024) keeps no residuals [N, 64]; every other sweep does, and its areas for the partial sums also
+    hold those of a small last group."""
+    N, D = 100000, 512
+    rc, small = _ws_bytes(_job(N=N, D=D), M=16)
+    rc2, big = _ws_bytes(_job(N=N, D=D), M=17)
+    assert rc == glm.GLM_OK and rc2 == glm.GLM_OK
+    assert big - small >= 4 * N * 64 and small < 4 * N * 64
+    # the one-pass kernel's partial gradients: one [16, D] per block, 512 blocks at this row length
+    assert small >= 4 * 512 * 16 * D
+    # rows the one-pass kernel does not take: the residual area is there whatever the number of models
+    for Dx in (520, 2048):
+        rc, a = _ws_bytes(_job(N=N, D=Dx), M=16)
+        assert rc == glm.GLM_OK and a >= 4 * N * 64
+    # tiny N: one block per tile of 16 rows, never fewer bytes than the two-pass areas need
+    rc, t1 = _ws_bytes(_job(N=5, D=64), M=3)
+    rc2, t2 = _ws_bytes(_job(N=5, D=64), M=64)
+    assert rc == glm.GLM_OK and rc2 == glm.GLM_OK and 0 < t1 <= t2
+
+
 @pytest.mark.parametrize("bad", [dict(N=0), dict(D=0), dict(D=6), dict(D=4100), dict(N=-5)])
 def test_workspace_bytes_rejects_bad_shapes(bad):
     rc, _ = _ws_bytes(_job(**bad))
