@@ -93,10 +93,12 @@ def test_sweep_per_step_from_nonzero_start():
         assert np.max(np.abs(gg - gr)) <= REL_TOL * np.max(np.abs(gr))
 
 
-def test_sweep_reruns_are_bit_identical():
-    _say("[case] sweep rerun determinism")
+@pytest.mark.parametrize("M", [64, 16])
+def test_sweep_reruns_are_bit_identical(M):
+    _say(f"[case] sweep rerun determinism, {M} models")
     p = synth.make_glm(synth.LOGISTIC, 50000, 256, seed=4, lam=0.0, eta=0.0, K=4, device="cuda")
     lams, etas = synth.sweep_grid()
+    lams, etas = lams[:M], etas[:M]
     outs = [_run_sweep(p, lams, etas, 4) for _ in range(3)]
     for o in outs[1:]:
         assert all(torch.equal(a, b) for a, b in zip(outs[0], o))
